@@ -1,0 +1,271 @@
+"""Pins for the oracle's quantizer (CPU only): App. B Eq. 1-4, Sec. 4.2-4.4, App. B.4."""
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2509_25149_amd import synth
+
+E2M1 = np.array([0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0], dtype=np.float32)
+
+
+def bits(values):
+    return synth.f32_to_bf16_bits(np.asarray(values, dtype=np.float32))
+
+
+def unpack(codes):
+    """[outer, inner/2] bytes -> [outer, inner] 4-bit codes (even element in the low nibble)."""
+    lo, hi = codes & 0xF, codes >> 4
+    return np.stack([lo, hi], axis=-1).reshape(codes.shape[0], -1)
+
+
+def code_values(c4):
+    return np.where(c4 & 8, -E2M1[c4 & 7], E2M1[c4 & 7]).astype(np.float32)
+
+
+def e4m3_values(sc):
+    return np.array([oracle.e4m3_decode(int(v)) for v in sc.ravel()], dtype=np.float32).reshape(sc.shape)
+
+
+def read_golden(path):
+    out = {}
+    with open(path) as fh:
+        for line in fh:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            k, v = line.split(":")
+            out[k.strip()] = v.split()
+    return out
+
+
+@pytest.mark.parametrize("name", ["handworked_A.txt", "handworked_B.txt"])
+def test_handworked_tensors(golden_dir, name):
+    g = read_golden(os.path.join(golden_dir, name))
+    x = np.array([float(t) for t in g["x"]], dtype=np.float32)
+    xb = bits(x).reshape(1, -1)
+    assert np.array_equal(synth.bf16_bits_to_f32(xb).ravel(), x), "fixture must be bf16-exact"
+    q = oracle.quantize(xb, oracle.ROW)
+    assert q.amax.view(np.uint32) == int(g["amax_bits"][0], 16)
+    assert q.s_dec.view(np.uint32) == int(g["s_dec_bits"][0], 16)
+    assert [int(v) for v in q.scales.ravel()] == [int(t, 16) for t in g["scales"]]
+    assert [int(v) for v in unpack(q.codes).ravel()] == [int(t, 16) for t in g["codes"]]
+    # the same numbers as a column: the col copy of the transposed tensor is the same bytes
+    qc = oracle.quantize(np.ascontiguousarray(np.tile(xb.T, (1, 16))), oracle.COL)
+    assert np.array_equal(qc.codes[0], q.codes[0]) and np.array_equal(qc.scales[0], q.scales[0])
+
+
+def random_tensor(rows, cols, seed):
+    return synth.normal_with_outliers(rows, cols, 1.0, seed, frac=0.01)
+
+
+def test_scale_invariants_of_app_b2():
+    xb = random_tensor(64, 256, 1)
+    x = synth.bf16_bits_to_f32(xb)
+    q = oracle.quantize(xb, oracle.ROW)
+    assert q.amax == np.abs(x).max()
+    s_enc = np.float32(2688.0) / q.amax                       # Eq. 1
+    assert q.s_dec == np.float32(1.0) / s_enc
+    blk = np.abs(x).reshape(64, 16, 16)
+    amax_b = blk.max(axis=2)
+    # the block holding the tensor amax is remapped to the E4M3 maximum (App. B.2)
+    r, c = np.unravel_index(np.argmax(np.abs(x)), x.shape)
+    assert q.scales[r, c // 16] == 0x7E
+    sd = e4m3_values(q.scales)
+    c4 = unpack(q.codes).reshape(64, 16, 16)
+    normal = q.scales >= 0x08
+    assert normal.sum() > 0.9 * normal.size
+    for (o, b) in zip(*np.nonzero(normal)):
+        k = int(np.argmax(blk[o, b]))
+        assert (c4[o, b, k] & 7) == 7                         # block amax -> FP4 maximum (Fig. 1)
+        rec = np.float32(6.0) * sd[o, b] * q.s_dec
+        assert abs(rec - amax_b[o, b]) <= 2.0 ** -4 * amax_b[o, b] * (1 + 1e-6)
+        # s_enc_b * s_dec * stored scale ~ 1
+        s_enc_b = np.float32(1.0) / (sd[o, b] * q.s_dec)
+        assert abs(float(s_enc_b) * float(q.s_dec) * float(sd[o, b]) - 1.0) < 4e-7
+
+
+def test_roundtrip_error_bound_rne_and_sr():
+    xb = random_tensor(32, 128, 2)
+    x = synth.bf16_bits_to_f32(xb)
+    for rounding, widest in ((oracle.RNE, 1.0), (oracle.SR, 2.0)):
+        q = oracle.quantize(xb, oracle.ROW, rounding=rounding, sr_seed=5)
+        xd = oracle.dequantize(q)
+        sd = np.repeat(e4m3_values(q.scales), 16, axis=1)
+        unit = sd * q.s_dec                                   # one scaled unit in tensor units
+        ok = np.abs(xd - x) <= widest * unit * (1 + 1e-5) + 1e-30
+        ok |= sd == 0
+        assert ok.all()
+        # dequantize is value * stored scale * s_dec
+        want = (code_values(unpack(q.codes)) * sd) * q.s_dec
+        assert np.array_equal(xd, want)
+
+
+def test_nvfp4_keeps_the_block_amax_where_a_power_of_two_scale_would_not():
+    # App. B.4: with amax_b = 3 + delta a rounded-up power-of-two scale leaves the
+    # amax at 3; the E4M3 scale must bring it to +-6 and decode close to 3 + delta.
+    x = np.full((1, 32), 0.5, dtype=np.float32)
+    x[0, 5] = -3.015625
+    x[0, 16] = 100.0
+    q = oracle.quantize(bits(x), oracle.ROW)
+    c4 = unpack(q.codes)
+    assert c4[0, 5] == 0xF
+    rec = 6.0 * oracle.e4m3_decode(int(q.scales[0, 0])) * float(q.s_dec)
+    assert abs(rec - 3.015625) <= 2.0 ** -4 * 3.015625
+    assert oracle.e4m3_decode(int(q.scales[0, 0])) not in (8.0, 16.0, 32.0)   # not a bare power of two
+
+
+def test_2d_blocks_make_w_and_w_transposed_identical():
+    wb = synth.normal(96, 64, 0.02, 3)
+    row = oracle.quantize(wb, oracle.ROW, oracle.BLOCK_16x16)
+    col = oracle.quantize(wb, oracle.COL, oracle.BLOCK_16x16)
+    assert row.s_dec == col.s_dec and row.amax == col.amax
+    assert np.array_equal(unpack(row.codes), unpack(col.codes).T)
+    sr_, sc_ = np.repeat(row.scales, 16, axis=1), np.repeat(col.scales, 16, axis=1)
+    assert np.array_equal(sr_, sc_.T)
+    # one scale per 16x16 tile, replicated over the tile's 16 rows
+    assert np.array_equal(row.scales.reshape(6, 16, 4), np.repeat(row.scales.reshape(6, 16, 4)[:, :1], 16, axis=1))
+    # the transposed tensor quantizes to the transposed bytes
+    rowT = oracle.quantize(np.ascontiguousarray(wb.T), oracle.ROW, oracle.BLOCK_16x16)
+    assert np.array_equal(rowT.codes, col.codes) and np.array_equal(rowT.scales, col.scales)
+    # 1x16 blocks do NOT have this property on the same data
+    r1 = oracle.quantize(wb, oracle.ROW)
+    c1 = oracle.quantize(wb, oracle.COL)
+    assert not np.array_equal(unpack(r1.codes), unpack(c1.codes).T)
+    # tile amax really is over 256 elements
+    w = synth.bf16_bits_to_f32(wb)
+    t_amax = np.abs(w).reshape(6, 16, 4, 16).max(axis=(1, 3))
+    s_enc = np.float32(2688.0) / row.amax
+    for ot in range(6):
+        for b in range(4):
+            want = oracle.e4m3_encode_rne_sat(float((t_amax[ot, b] / np.float32(6.0)) * s_enc))
+            assert row.scales[16 * ot, b] == want
+
+
+def test_col_copy_is_row_copy_of_the_transpose():
+    xb = random_tensor(48, 80, 4)
+    for kw in (dict(), dict(use_rht=True, rht_seed=9)):
+        a = oracle.quantize(xb, oracle.COL, **kw)
+        b = oracle.quantize(np.ascontiguousarray(xb.T), oracle.ROW, **kw)
+        assert np.array_equal(a.codes, b.codes) and np.array_equal(a.scales, b.scales)
+        assert a.s_dec == b.s_dec and a.amax == b.amax
+
+
+def test_rotated_copy_scales_come_from_the_rotated_space():
+    xb = random_tensor(64, 32, 6)
+    x = synth.bf16_bits_to_f32(xb)
+    seed = 1234
+    mask = oracle.rht_sign_mask(seed)
+    q = oracle.quantize(xb, oracle.COL, use_rht=True, rht_seed=seed)
+    rot = np.zeros((32, 64), dtype=np.float32)
+    for c in range(32):
+        for g in range(4):
+            rot[c, 16 * g:16 * g + 16] = oracle.rht16_forward(x[16 * g:16 * g + 16, c], mask)
+    assert q.amax == np.abs(rot).max()                         # App. C: scale computed on x H
+    plain = oracle.quantize(xb, oracle.COL)
+    assert plain.amax == np.abs(x).max() and plain.amax != q.amax
+    # undoing the rotation after dequantization approximates the input
+    back = oracle.dequantize(q, undo_rht=True, rht_seed=seed)
+    err = np.linalg.norm(back - x.T) / np.linalg.norm(x)
+    assert err < 0.15
+    # and quantizing the pre-rotated values without the flag gives the same codes
+    # when the rotated values happen to be bf16-exact (small integers)
+    xi = np.random.default_rng(1).integers(-4, 5, (32, 16)).astype(np.float32) * 4
+    qi = oracle.quantize(bits(xi), oracle.COL, use_rht=True, rht_seed=seed)
+    roti = np.stack([np.concatenate([oracle.rht16_forward(xi[16 * g:16 * g + 16, c], mask) for g in range(2)])
+                     for c in range(16)])
+    assert np.array_equal(synth.bf16_bits_to_f32(bits(roti)), roti)
+    qj = oracle.quantize(bits(roti), oracle.ROW)
+    assert np.array_equal(qi.codes, qj.codes) and np.array_equal(qi.scales, qj.scales)
+
+
+def test_degenerate_tensors():
+    z = np.zeros((16, 32), dtype=np.float32)
+    q = oracle.quantize(bits(z), oracle.ROW)
+    assert q.amax == 0 and q.s_dec == 1 and not q.codes.any() and not q.scales.any()
+    z[3, 7] = -0.0
+    z[0, 16] = 1.0
+    z[1, 0] = -1e-6            # its block scale underflows E4M3 -> zero scale, zero codes
+    z[1, 1] = 1e-7
+    q = oracle.quantize(bits(z), oracle.ROW)
+    c4 = unpack(q.codes)
+    assert q.scales[0, 1] == 0x7E and c4[0, 16] == 7
+    assert q.scales[1, 0] == 0 and c4[1, 0] == 8 and c4[1, 1] == 0     # sign of x * 0
+    assert c4[3, 7] == 8
+    assert np.array_equal(oracle.dequantize(q)[1], np.zeros(32, dtype=np.float32))
+    # tiny amax: 2688/amax overflows binary32 and is clamped
+    t = np.zeros((16, 16), dtype=np.float32)
+    t[0, 0] = 1e-38
+    q = oracle.quantize(bits(t), oracle.ROW)
+    assert np.isfinite(q.s_dec) and q.s_dec > 0
+    with pytest.raises(ValueError):
+        oracle.quantize(bits(np.zeros((16, 24))), oracle.ROW)
+    with pytest.raises(ValueError):
+        oracle.quantize(bits(np.zeros((16, 16))), oracle.COL, oracle.BLOCK_16x16, use_rht=True)
+
+
+# ---------------------------------------------------------------- stochastic rounding
+
+def test_sr_never_moves_grid_values_and_stays_between_neighbours():
+    rng = np.random.default_rng(8)
+    for g in E2M1:
+        for r in (0, 1, 32768, 65535):
+            assert oracle.e2m1_decode(oracle.e2m1_encode_sr(float(g), r)) == g
+            assert oracle.e2m1_decode(oracle.e2m1_encode_sr(-float(g), r)) == -g
+    for v in rng.uniform(-6.5, 6.5, 500).astype(np.float32):
+        a = min(abs(float(v)), 6.0)
+        lo = E2M1[E2M1 <= a].max()
+        hi = E2M1[E2M1 >= a].min()
+        for r in rng.integers(0, 65536, 8):
+            got = oracle.e2m1_decode(oracle.e2m1_encode_sr(float(v), int(r)))
+            assert abs(got) in (lo, hi) and np.signbit(got) == np.signbit(v)
+    assert oracle.e2m1_encode_sr(7.0, 0) == 7 and oracle.e2m1_encode_sr(-1e9, 65535) == 15
+
+
+def test_sr_probability_is_the_position_between_neighbours():
+    # sweeping all 2^16 random values rounds up exactly floor(p * 2^16) times
+    for v, lo, step in ((0.3, 0.0, 0.5), (0.8125, 0.5, 0.5), (1.9, 1.5, 0.5), (2.25, 2.0, 1.0),
+                        (3.999, 3.0, 1.0), (4.5, 4.0, 2.0), (5.99, 4.0, 2.0), (1e-6, 0.0, 0.5)):
+        v32 = np.float32(v)
+        ups = sum(oracle.e2m1_decode(oracle.e2m1_encode_sr(float(v32), r)) > lo for r in range(65536))
+        p = (float(v32) - lo) / step
+        assert ups == int(np.floor(p * 65536))
+
+
+def test_sr_mean_over_1e5_seeds_is_unbiased_within_3_sigma():
+    n = 100_000
+    for v, step in ((0.37, 0.5), (-1.3, 0.5), (2.6, 1.0), (4.9, 2.0), (0.02, 0.5)):
+        v32 = float(np.float32(v))
+        vals = np.array([oracle.e2m1_decode(oracle.e2m1_encode_sr(v32, oracle.sr_random16(s, 17, 29)))
+                         for s in range(n)])
+        lo = np.floor(abs(v32) / step) * step
+        p = (abs(v32) - lo) / step
+        sigma = step * np.sqrt(p * (1 - p) / n)
+        assert abs(vals.mean() - v32) <= 3 * sigma + step * 2.0 ** -16
+
+
+def test_sr_in_the_tensor_path_uses_the_element_draw_for_both_copies():
+    xb = synth.student_t3(32, 48, 1e-3, 10)
+    x = synth.bf16_bits_to_f32(xb)
+    seed = 0xFEEDFACE12345
+    for copy in (oracle.ROW, oracle.COL):
+        q = oracle.quantize(xb, copy, rounding=oracle.SR, sr_seed=seed)
+        view = x if copy == oracle.ROW else x.T
+        sd = np.repeat(e4m3_values(q.scales), 16, axis=1)
+        with np.errstate(divide="ignore"):
+            s_enc_b = np.where(sd == 0, np.float32(0), np.float32(1.0) / (sd * q.s_dec)).astype(np.float32)
+        v = (view * s_enc_b).astype(np.float32)
+        c4 = unpack(q.codes)
+        for o in range(view.shape[0]):
+            for k in range(view.shape[1]):
+                i, j = (o, k) if copy == oracle.ROW else (k, o)
+                want = oracle.e2m1_encode_sr(float(v[o, k]), oracle.sr_random16(seed, i, j))
+                assert c4[o, k] == want
+    # a different seed changes some codes; RNE ignores the seed
+    a = oracle.quantize(xb, oracle.ROW, rounding=oracle.SR, sr_seed=1)
+    b = oracle.quantize(xb, oracle.ROW, rounding=oracle.SR, sr_seed=2)
+    assert not np.array_equal(a.codes, b.codes) and np.array_equal(a.scales, b.scales)
+    c = oracle.quantize(xb, oracle.ROW, sr_seed=1)
+    d = oracle.quantize(xb, oracle.ROW, sr_seed=2)
+    assert np.array_equal(c.codes, d.codes)
