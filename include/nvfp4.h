@@ -1,0 +1,169 @@
+/*
+ * nvfp4.h -- C ABI of the MI355X (gfx950) NVFP4 quantize-and-GEMM library.
+ *
+ * Implements the per-linear-layer hot path of "Pretraining Large Language
+ * Models with NVFP4" (arXiv 2509.25149): two-level scaled E2M1 quantization
+ * (Sec. 2, App. B), 16x16 weight blocks (Sec. 4.3), the 16-point random
+ * Hadamard rotation of the Wgrad operands (Sec. 4.2, App. C), stochastic
+ * rounding of gradients (Sec. 4.4) and the block-scaled GEMM with FP32
+ * accumulation (Sec. 2, App. B.3 Eq. 5).
+ *
+ * General rules
+ *   - Every data pointer is a DEVICE pointer unless marked "host".  The
+ *     library never allocates, frees or retains device memory: the caller
+ *     owns every buffer, including the small workspace.
+ *   - Every call only enqueues kernels on the given HIP stream (a
+ *     hipStream_t passed as void*; NULL is the default stream) and returns
+ *     without waiting.  Argument checks are synchronous: a call that returns
+ *     an error has enqueued nothing.
+ *   - Return value: NVFP4_OK (0) or a negative nvfp4_status.
+ *   - Data-dependent trouble never aborts: a tensor containing Inf/NaN yields
+ *     amax = Inf/NaN in tensor_scale[1] and unspecified codes.
+ *   - No global state; calls on different streams with disjoint buffers are
+ *     independent.
+ *
+ * Storage format (the paper fixes the number formats, not the layout)
+ *   - E2M1 code: bit 3 sign, bits 2..0 index into {0, .5, 1, 1.5, 2, 3, 4, 6}
+ *     (Sec. 2).  Two codes per byte, element 2j in the low nibble.
+ *   - Block scale: one E4M3 byte (bias 7, max 448, App. B.1) per 16
+ *     consecutive elements along the copy's contiguous dimension.
+ *   - "row copy" of a logical [rows, cols] tensor: codes [rows, cols/2] bytes,
+ *     scales [rows, cols/16] bytes, blocks along cols.
+ *   - "col copy": the row-wise quantization of the transposed tensor, stored
+ *     transposed: codes [cols, rows/2] bytes, scales [cols, rows/16] bytes,
+ *     blocks along rows.  This is the operand layout a GEMM contracting over
+ *     `rows` needs (Sec. 4.3: scaling runs along the dot-product dimension).
+ *   - tensor_scale: float[2] per copy, [0] = s_dec = 1/s_enc (App. B.1 Eq. 1),
+ *     [1] = the amax it was derived from (in the rotated space for a rotated
+ *     copy, App. C).
+ *   - With 16x16 blocks (weights) one scale per tile is replicated into every
+ *     1x16 slot of both copies, so the col copy is the exact transpose of the
+ *     row copy (Sec. 4.3).
+ */
+#ifndef NVFP4_H_
+#define NVFP4_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef void* nvfp4_stream_t; /* a hipStream_t */
+
+typedef enum nvfp4_status {
+  NVFP4_OK = 0,
+  NVFP4_ERR_INVALID_ARG = -1,  /* null pointer, unknown enum value */
+  NVFP4_ERR_BAD_SHAPE = -2,    /* rows or cols not a positive multiple of 16, ld too small */
+  NVFP4_ERR_MISSING_COPY = -3, /* the copy an operation needs is absent from the descriptor */
+  NVFP4_ERR_MISMATCH = -4,     /* operands disagree on K, rotation flag or rotation seed */
+  NVFP4_ERR_HIP = -5,          /* a HIP runtime call failed (launch error) */
+  NVFP4_ERR_WORKSPACE = -6     /* workspace missing or too small */
+} nvfp4_status;
+
+enum { NVFP4_LAYOUT_ROW = 1, NVFP4_LAYOUT_COL = 2 };       /* layout mask bits */
+enum { NVFP4_BLOCK_1x16 = 1, NVFP4_BLOCK_16x16 = 16 };     /* block_dim */
+enum { NVFP4_ROUND_RNE = 0, NVFP4_ROUND_SR = 1 };          /* rounding */
+enum { NVFP4_OP_FPROP = 0, NVFP4_OP_DGRAD = 1, NVFP4_OP_WGRAD = 2 };
+enum { NVFP4_OUT_F32 = 0, NVFP4_OUT_BF16 = 1 };
+enum { NVFP4_COPY_ROW = 0, NVFP4_COPY_COL = 1 };
+
+/*
+ * Descriptor of a quantized tensor.  Caller-owned plain struct; the caller
+ * fills the pointers of the copies it wants before nvfp4_quantize, which
+ * fills the remaining fields.  Unused copies have NULL pointers.
+ */
+typedef struct nvfp4_qtensor {
+  int64_t rows, cols;       /* logical shape of the source tensor */
+  void* row_codes;          /* [rows, cols/2] bytes */
+  void* row_scales;         /* [rows, cols/16] bytes */
+  float* row_tensor_scale;  /* float[2]: s_dec, amax */
+  void* col_codes;          /* [cols, rows/2] bytes */
+  void* col_scales;         /* [cols, rows/16] bytes */
+  float* col_tensor_scale;  /* float[2]: s_dec, amax */
+  int32_t layout_mask;      /* which copies hold data (set by nvfp4_quantize) */
+  int32_t block_dim;        /* NVFP4_BLOCK_* used */
+  int32_t rounding;         /* NVFP4_ROUND_* used */
+  int32_t col_has_rht;      /* 1 if the col copy was rotated */
+  uint64_t rht_seed;        /* seed of the sign diagonal, if rotated */
+} nvfp4_qtensor;
+
+/*
+ * Byte counts for one copy of a [rows, cols] tensor and for the workspace
+ * nvfp4_quantize needs (host pointers, any may be NULL).  codes_bytes and
+ * scales_bytes are the same for the row and the col copy.
+ */
+int nvfp4_quantized_sizes(int64_t rows, int64_t cols, size_t* codes_bytes, size_t* scales_bytes,
+                          size_t* workspace_bytes);
+
+/*
+ * Quantize a bf16 tensor to NVFP4 (App. B Eq. 1-4).
+ *   x            device, bf16 [rows, cols], row-major with leading dimension ld (elements)
+ *   layout_mask  NVFP4_LAYOUT_ROW | NVFP4_LAYOUT_COL: which copies to emit
+ *   block_dim    1x16 (activations, gradients) or 16x16 (weights, Sec. 4.3)
+ *   rounding     RNE (weights, activations) or SR (gradients), Sec. 4.4
+ *   rht_on_col   rotate the col copy: every aligned group of 16 consecutive
+ *                rows of a column is multiplied by the sign diagonal and the
+ *                16-point Hadamard matrix before scaling (Sec. 4.2, App. C).
+ *                Not allowed with 16x16 blocks.
+ *   rht_seed     selects the sign diagonal (nvfp4_rht_sign_mask)
+ *   sr_seed      key of the Philox4x32-10 stream used for SR; element (i, j)
+ *                uses counter (j/8, i, 0, 0), 16 bits per element, so both
+ *                copies round with the same draw
+ *   out          host pointer to the descriptor; its copy pointers for the
+ *                requested layouts must be set (device memory sized by
+ *                nvfp4_quantized_sizes)
+ *   workspace    device, >= workspace_bytes; contents irrelevant on entry
+ * The global amax costs a first pass over x (App. B.1); the second pass
+ * scales, rounds, packs and writes every requested copy.
+ */
+int nvfp4_quantize(const void* x, int64_t rows, int64_t cols, int64_t ld, int layout_mask,
+                   int block_dim, int rounding, int rht_on_col, uint64_t rht_seed, uint64_t sr_seed,
+                   nvfp4_qtensor* out, void* workspace, size_t workspace_bytes,
+                   nvfp4_stream_t stream);
+
+/*
+ * Block-scaled GEMM (Eq. 5): D[m, n] = s_dec^A s_dec^B sum_b sA[m,b] sB[n,b]
+ * sum_{k in b} A[m,k] B[n,k], FP32 accumulation.  `op` picks the copies:
+ *   FPROP  Y  = X W      A = row copy of X [M,K],   B = col copy of W [K,N] (-> [N,K])
+ *   DGRAD  dX = dY W^T   A = row copy of dY [M,K],  B = row copy of W [N,K]
+ *   WGRAD  dW = A^T B    A = col copy of the first tensor [K,M] (-> [M,K]),
+ *                        B = col copy of the second [K,N] (-> [N,K]); both must
+ *                        agree on rotation flag and seed (App. C)
+ * D is device memory, [M, N] row-major with leading dimension ldd, FP32 or
+ * bf16 (bf16 = round-to-nearest-even of the FP32 result).
+ */
+int nvfp4_gemm(const nvfp4_qtensor* a, const nvfp4_qtensor* b, int op, void* d, int out_dtype,
+               int64_t ldd, nvfp4_stream_t stream);
+
+/*
+ * Decode one copy back to FP32 or bf16: value(code) * block scale * s_dec
+ * (Sec. 2; App. B.2).  The output has the copy's own orientation: [rows, cols]
+ * for the row copy, [cols, rows] for the col copy, leading dimension ld_out.
+ * undo_rht rotates each group of 16 back (only meaningful for a rotated copy).
+ */
+int nvfp4_dequantize(const nvfp4_qtensor* q, int which_copy, int undo_rht, void* out, int out_dtype,
+                     int64_t ld_out, nvfp4_stream_t stream);
+
+/* 16-bit sign diagonal for a seed: bit i set means s_i = -1 (App. C). */
+uint32_t nvfp4_rht_sign_mask(uint64_t rht_seed);
+
+/*
+ * Device self-test of the gfx950 conversion instructions the quantizer relies
+ * on, against explicit integer/compare implementations run on the device.
+ * mismatches: DEVICE pointer to uint64[3], zeroed by the caller; the kernels
+ * add their mismatch counts: [0] FP32->E2M1 RNE over all 2^32 bit patterns,
+ * [1] FP32->E2M1 SR over a grid of values x all 2^16 random values,
+ * [2] FP32->E4M3 (and back) over all non-negative finite patterns.
+ * Asynchronous like every other call.
+ */
+int nvfp4_selftest_conversions(uint64_t* mismatches, nvfp4_stream_t stream);
+
+const char* nvfp4_status_string(int status);
+int nvfp4_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NVFP4_H_ */

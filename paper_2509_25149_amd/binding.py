@@ -1,0 +1,188 @@
+"""Thin Python binding of the NVFP4 C ABI (include/nvfp4.h).
+
+Argument marshalling only: every step of the path runs in the HIP kernels of
+``libnvfp4_hip.so``.  PyTorch supplies device memory and the current stream.
+There is no CPU fallback: if the library is missing, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libnvfp4_hip.so")
+
+LAYOUT_ROW, LAYOUT_COL = 1, 2
+BLOCK_1x16, BLOCK_16x16 = 1, 16
+ROUND_RNE, ROUND_SR = 0, 1
+OP_FPROP, OP_DGRAD, OP_WGRAD = 0, 1, 2
+OUT_F32, OUT_BF16 = 0, 1
+COPY_ROW, COPY_COL = 0, 1
+
+EXPORTS = ["nvfp4_quantized_sizes", "nvfp4_quantize", "nvfp4_gemm", "nvfp4_dequantize",
+           "nvfp4_rht_sign_mask", "nvfp4_selftest_conversions", "nvfp4_status_string", "nvfp4_version"]
+
+
+class QTensorStruct(ctypes.Structure):
+    """Mirror of ``nvfp4_qtensor``."""
+    _fields_ = [("rows", ctypes.c_int64), ("cols", ctypes.c_int64),
+                ("row_codes", ctypes.c_void_p), ("row_scales", ctypes.c_void_p),
+                ("row_tensor_scale", ctypes.c_void_p),
+                ("col_codes", ctypes.c_void_p), ("col_scales", ctypes.c_void_p),
+                ("col_tensor_scale", ctypes.c_void_p),
+                ("layout_mask", ctypes.c_int32), ("block_dim", ctypes.c_int32),
+                ("rounding", ctypes.c_int32), ("col_has_rht", ctypes.c_int32),
+                ("rht_seed", ctypes.c_uint64)]
+
+
+_lib = None
+
+
+def load_library() -> ctypes.CDLL:
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with __graft_entry__.build() "
+                               "(there is no fallback path)")
+        L = ctypes.CDLL(LIB_PATH)
+        i64, vp, ci, u64 = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int, ctypes.c_uint64
+        L.nvfp4_quantized_sizes.restype = ci
+        L.nvfp4_quantized_sizes.argtypes = [i64, i64, vp, vp, vp]
+        L.nvfp4_quantize.restype = ci
+        L.nvfp4_quantize.argtypes = [vp, i64, i64, i64, ci, ci, ci, ci, u64, u64,
+                                     ctypes.POINTER(QTensorStruct), vp, ctypes.c_size_t, vp]
+        L.nvfp4_gemm.restype = ci
+        L.nvfp4_gemm.argtypes = [ctypes.POINTER(QTensorStruct), ctypes.POINTER(QTensorStruct), ci, vp, ci, i64, vp]
+        L.nvfp4_dequantize.restype = ci
+        L.nvfp4_dequantize.argtypes = [ctypes.POINTER(QTensorStruct), ci, ci, vp, ci, i64, vp]
+        L.nvfp4_rht_sign_mask.restype = ctypes.c_uint32
+        L.nvfp4_rht_sign_mask.argtypes = [u64]
+        L.nvfp4_selftest_conversions.restype = ci
+        L.nvfp4_selftest_conversions.argtypes = [vp, vp]
+        L.nvfp4_status_string.restype = ctypes.c_char_p
+        L.nvfp4_status_string.argtypes = [ci]
+        L.nvfp4_version.restype = ci
+        L.nvfp4_version.argtypes = []
+        _lib = L
+    return _lib
+
+
+class NVFP4Error(RuntimeError):
+    def __init__(self, status: int):
+        self.status = status
+        super().__init__(f"nvfp4 error {status}: {load_library().nvfp4_status_string(status).decode()}")
+
+
+def _check(status: int) -> None:
+    if status != 0:
+        raise NVFP4Error(status)
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def quantized_sizes(rows: int, cols: int):
+    c, s, w = ctypes.c_size_t(), ctypes.c_size_t(), ctypes.c_size_t()
+    _check(load_library().nvfp4_quantized_sizes(rows, cols, ctypes.addressof(c), ctypes.addressof(s),
+                                                ctypes.addressof(w)))
+    return c.value, s.value, w.value
+
+
+def rht_sign_mask(seed: int) -> int:
+    return int(load_library().nvfp4_rht_sign_mask(seed))
+
+
+@dataclass
+class QTensor:
+    """Device buffers of a quantized tensor plus its C descriptor."""
+    desc: QTensorStruct
+    rows: int
+    cols: int
+    row_codes: Optional[torch.Tensor] = None
+    row_scales: Optional[torch.Tensor] = None
+    row_ts: Optional[torch.Tensor] = None
+    col_codes: Optional[torch.Tensor] = None
+    col_scales: Optional[torch.Tensor] = None
+    col_ts: Optional[torch.Tensor] = None
+
+
+def alloc_qtensor(rows: int, cols: int, layout_mask: int, device="cuda") -> QTensor:
+    codes_b, scales_b, _ = quantized_sizes(rows, cols)
+    q = QTensor(QTensorStruct(), rows, cols)
+    q.desc.rows, q.desc.cols = rows, cols
+    if layout_mask & LAYOUT_ROW:
+        q.row_codes = torch.empty((rows, cols // 2), dtype=torch.uint8, device=device)
+        q.row_scales = torch.empty((rows, cols // 16), dtype=torch.uint8, device=device)
+        q.row_ts = torch.empty(2, dtype=torch.float32, device=device)
+        q.desc.row_codes, q.desc.row_scales = q.row_codes.data_ptr(), q.row_scales.data_ptr()
+        q.desc.row_tensor_scale = q.row_ts.data_ptr()
+    if layout_mask & LAYOUT_COL:
+        q.col_codes = torch.empty((cols, rows // 2), dtype=torch.uint8, device=device)
+        q.col_scales = torch.empty((cols, rows // 16), dtype=torch.uint8, device=device)
+        q.col_ts = torch.empty(2, dtype=torch.float32, device=device)
+        q.desc.col_codes, q.desc.col_scales = q.col_codes.data_ptr(), q.col_scales.data_ptr()
+        q.desc.col_tensor_scale = q.col_ts.data_ptr()
+    return q
+
+
+_workspaces = {}
+
+
+def _workspace(device) -> torch.Tensor:
+    key = (torch.device(device).index or 0, _stream())
+    if key not in _workspaces:
+        _workspaces[key] = torch.empty(256, dtype=torch.uint8, device=device)
+    return _workspaces[key]
+
+
+def nvfp4_quantize(x: torch.Tensor, layout_mask: int, block_dim: int = BLOCK_1x16, rounding: int = ROUND_RNE,
+                   rht_on_col: bool = False, rht_seed: int = 0, sr_seed: int = 0,
+                   out: Optional[QTensor] = None, workspace: Optional[torch.Tensor] = None) -> QTensor:
+    """x: bf16 CUDA tensor [rows, cols] (last dim contiguous)."""
+    if not x.is_cuda or x.dtype != torch.bfloat16 or x.dim() != 2 or x.stride(1) != 1:
+        raise ValueError("x must be a 2-D bf16 CUDA tensor with unit inner stride")
+    rows, cols = x.shape
+    if out is None:
+        out = alloc_qtensor(rows, cols, layout_mask, x.device)
+    ws = workspace if workspace is not None else _workspace(x.device)
+    _check(load_library().nvfp4_quantize(x.data_ptr(), rows, cols, x.stride(0), layout_mask, block_dim, rounding,
+                                         int(rht_on_col), rht_seed, sr_seed, ctypes.byref(out.desc),
+                                         ws.data_ptr(), ws.numel(), _stream()))
+    return out
+
+
+def nvfp4_gemm(a: QTensor, b: QTensor, op: int, out_dtype: int = OUT_F32,
+               out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    m = a.cols if op == OP_WGRAD else a.rows
+    n = b.rows if op == OP_DGRAD else b.cols
+    if out is None:
+        dt = torch.float32 if out_dtype == OUT_F32 else torch.bfloat16
+        dev = (a.row_codes if a.row_codes is not None else a.col_codes).device
+        out = torch.empty((m, n), dtype=dt, device=dev)
+    _check(load_library().nvfp4_gemm(ctypes.byref(a.desc), ctypes.byref(b.desc), op, out.data_ptr(), out_dtype,
+                                     out.stride(0), _stream()))
+    return out
+
+
+def nvfp4_dequantize(q: QTensor, which_copy: int, undo_rht: bool = False, out_dtype: int = OUT_F32,
+                     out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    outer, inner = (q.cols, q.rows) if which_copy == COPY_COL else (q.rows, q.cols)
+    if out is None:
+        dt = torch.float32 if out_dtype == OUT_F32 else torch.bfloat16
+        dev = (q.row_codes if q.row_codes is not None else q.col_codes).device
+        out = torch.empty((outer, inner), dtype=dt, device=dev)
+    _check(load_library().nvfp4_dequantize(ctypes.byref(q.desc), which_copy, int(undo_rht), out.data_ptr(),
+                                           out_dtype, out.stride(0), _stream()))
+    return out
+
+
+def nvfp4_selftest_conversions() -> list:
+    counts = torch.zeros(3, dtype=torch.int64, device="cuda")
+    _check(load_library().nvfp4_selftest_conversions(counts.data_ptr(), _stream()))
+    torch.cuda.synchronize()
+    return [int(v) for v in counts.cpu()]

@@ -1,0 +1,198 @@
+// C ABI of the NVFP4 library (see include/nvfp4.h): argument validation and
+// dispatch only; every step of the path runs in the kernels.
+#include "nvfp4.h"
+#include "nvfp4_internal.h"
+
+namespace nvfp4 {
+
+namespace {
+
+void host_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]) {
+  uint32_t c[4] = {ctr[0], ctr[1], ctr[2], ctr[3]};
+  uint32_t k[2] = {key[0], key[1]};
+  for (int round = 0; round < 10; ++round) {
+    const uint64_t lo = 0xD2511F53ull * c[0], hi = 0xCD9E8D57ull * c[2];
+    const uint32_t t0 = static_cast<uint32_t>(hi >> 32) ^ c[1] ^ k[0];
+    const uint32_t t2 = static_cast<uint32_t>(lo >> 32) ^ c[3] ^ k[1];
+    c[1] = static_cast<uint32_t>(hi);
+    c[3] = static_cast<uint32_t>(lo);
+    c[0] = t0;
+    c[2] = t2;
+    k[0] += 0x9E3779B9u;
+    k[1] += 0xBB67AE85u;
+  }
+  for (int i = 0; i < 4; ++i) out[i] = c[i];
+}
+
+bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+constexpr size_t kWorkspaceBytes = 256;
+
+}  // namespace
+
+uint32_t host_rht_sign_mask(uint64_t seed) {
+  const uint32_t ctr[4] = {0u, 0u, 0u, 0xFFFFFFFFu};
+  const uint32_t key[2] = {static_cast<uint32_t>(seed), static_cast<uint32_t>(seed >> 32)};
+  uint32_t out[4];
+  host_philox4x32_10(ctr, key, out);
+  return out[0] & 0xFFFFu;
+}
+
+}  // namespace nvfp4
+
+using namespace nvfp4;
+
+extern "C" {
+
+int nvfp4_version(void) { return 100; }
+
+const char* nvfp4_status_string(int status) {
+  switch (status) {
+    case NVFP4_OK: return "ok";
+    case NVFP4_ERR_INVALID_ARG: return "invalid argument (null pointer, unknown enum, misaligned pointer)";
+    case NVFP4_ERR_BAD_SHAPE: return "bad shape (rows/cols must be positive multiples of 16; leading dimension too small or misaligned)";
+    case NVFP4_ERR_MISSING_COPY: return "the quantized tensor lacks the copy this operation needs";
+    case NVFP4_ERR_MISMATCH: return "operands disagree (contraction length, rotation flag or rotation seed)";
+    case NVFP4_ERR_HIP: return "HIP runtime error";
+    case NVFP4_ERR_WORKSPACE: return "workspace missing or too small";
+    default: return "unknown status";
+  }
+}
+
+uint32_t nvfp4_rht_sign_mask(uint64_t rht_seed) { return host_rht_sign_mask(rht_seed); }
+
+int nvfp4_quantized_sizes(int64_t rows, int64_t cols, size_t* codes_bytes, size_t* scales_bytes,
+                          size_t* workspace_bytes) {
+  if (rows <= 0 || cols <= 0 || rows % 16 || cols % 16) return NVFP4_ERR_BAD_SHAPE;
+  if (codes_bytes) *codes_bytes = static_cast<size_t>(rows) * static_cast<size_t>(cols) / 2;
+  if (scales_bytes) *scales_bytes = static_cast<size_t>(rows) * static_cast<size_t>(cols) / 16;
+  if (workspace_bytes) *workspace_bytes = kWorkspaceBytes;
+  return NVFP4_OK;
+}
+
+int nvfp4_quantize(const void* x, int64_t rows, int64_t cols, int64_t ld, int layout_mask, int block_dim,
+                   int rounding, int rht_on_col, uint64_t rht_seed, uint64_t sr_seed, nvfp4_qtensor* out,
+                   void* workspace, size_t workspace_bytes, nvfp4_stream_t stream) {
+  if (!x || !out) return NVFP4_ERR_INVALID_ARG;
+  if (layout_mask <= 0 || (layout_mask & ~(NVFP4_LAYOUT_ROW | NVFP4_LAYOUT_COL))) return NVFP4_ERR_INVALID_ARG;
+  if (block_dim != NVFP4_BLOCK_1x16 && block_dim != NVFP4_BLOCK_16x16) return NVFP4_ERR_INVALID_ARG;
+  if (rounding != NVFP4_ROUND_RNE && rounding != NVFP4_ROUND_SR) return NVFP4_ERR_INVALID_ARG;
+  const bool want_row = layout_mask & NVFP4_LAYOUT_ROW, want_col = layout_mask & NVFP4_LAYOUT_COL;
+  if (rht_on_col && (block_dim == NVFP4_BLOCK_16x16 || !want_col)) return NVFP4_ERR_INVALID_ARG;
+  if (rows <= 0 || cols <= 0 || rows % 16 || cols % 16 || ld < cols || ld % 8) return NVFP4_ERR_BAD_SHAPE;
+  if (!aligned(x, 16)) return NVFP4_ERR_INVALID_ARG;
+  if (want_row && (!out->row_codes || !out->row_scales || !out->row_tensor_scale)) return NVFP4_ERR_INVALID_ARG;
+  if (want_col && (!out->col_codes || !out->col_scales || !out->col_tensor_scale)) return NVFP4_ERR_INVALID_ARG;
+  if (want_row && !aligned(out->row_codes, 16)) return NVFP4_ERR_INVALID_ARG;
+  if (want_col && !aligned(out->col_codes, 16)) return NVFP4_ERR_INVALID_ARG;
+  if (!workspace || workspace_bytes < kWorkspaceBytes || !aligned(workspace, 16)) return NVFP4_ERR_WORKSPACE;
+
+  QuantizeArgs a;
+  a.x = x;
+  a.rows = rows;
+  a.cols = cols;
+  a.ld = ld;
+  a.want_row = want_row;
+  a.want_col = want_col;
+  a.rht = rht_on_col != 0;
+  a.sr = rounding == NVFP4_ROUND_SR;
+  a.block2d = block_dim == NVFP4_BLOCK_16x16;
+  a.sign_mask = a.rht ? host_rht_sign_mask(rht_seed) : 0u;
+  a.key0 = static_cast<uint32_t>(sr_seed);
+  a.key1 = static_cast<uint32_t>(sr_seed >> 32);
+  a.ws = static_cast<uint32_t*>(workspace);
+  a.row_codes = static_cast<uint8_t*>(out->row_codes);
+  a.row_scales = static_cast<uint8_t*>(out->row_scales);
+  a.row_ts = out->row_tensor_scale;
+  a.col_codes = static_cast<uint8_t*>(out->col_codes);
+  a.col_scales = static_cast<uint8_t*>(out->col_scales);
+  a.col_ts = out->col_tensor_scale;
+  if (launch_quantize(a, static_cast<hipStream_t>(stream)) != hipSuccess) return NVFP4_ERR_HIP;
+
+  out->rows = rows;
+  out->cols = cols;
+  out->layout_mask = layout_mask;
+  out->block_dim = block_dim;
+  out->rounding = rounding;
+  out->col_has_rht = a.rht ? 1 : 0;
+  out->rht_seed = a.rht ? rht_seed : 0;
+  return NVFP4_OK;
+}
+
+static int pick_operand(const nvfp4_qtensor* q, bool col_copy, Operand* op, int64_t* K) {
+  if (col_copy) {
+    if (!(q->layout_mask & NVFP4_LAYOUT_COL) || !q->col_codes || !q->col_scales || !q->col_tensor_scale)
+      return NVFP4_ERR_MISSING_COPY;
+    op->codes = static_cast<const uint8_t*>(q->col_codes);
+    op->scales = static_cast<const uint8_t*>(q->col_scales);
+    op->ts = q->col_tensor_scale;
+    op->outer = q->cols;
+    *K = q->rows;
+  } else {
+    if (!(q->layout_mask & NVFP4_LAYOUT_ROW) || !q->row_codes || !q->row_scales || !q->row_tensor_scale)
+      return NVFP4_ERR_MISSING_COPY;
+    op->codes = static_cast<const uint8_t*>(q->row_codes);
+    op->scales = static_cast<const uint8_t*>(q->row_scales);
+    op->ts = q->row_tensor_scale;
+    op->outer = q->rows;
+    *K = q->cols;
+  }
+  return NVFP4_OK;
+}
+
+int nvfp4_gemm(const nvfp4_qtensor* a, const nvfp4_qtensor* b, int op, void* d, int out_dtype, int64_t ldd,
+               nvfp4_stream_t stream) {
+  if (!a || !b || !d) return NVFP4_ERR_INVALID_ARG;
+  if (out_dtype != NVFP4_OUT_F32 && out_dtype != NVFP4_OUT_BF16) return NVFP4_ERR_INVALID_ARG;
+  bool a_col, b_col;
+  switch (op) {
+    case NVFP4_OP_FPROP: a_col = false; b_col = true; break;
+    case NVFP4_OP_DGRAD: a_col = false; b_col = false; break;
+    case NVFP4_OP_WGRAD: a_col = true; b_col = true; break;
+    default: return NVFP4_ERR_INVALID_ARG;
+  }
+  GemmArgs g;
+  int64_t ka = 0, kb = 0;
+  int rc = pick_operand(a, a_col, &g.a, &ka);
+  if (rc != NVFP4_OK) return rc;
+  rc = pick_operand(b, b_col, &g.b, &kb);
+  if (rc != NVFP4_OK) return rc;
+  if (ka != kb) return NVFP4_ERR_MISMATCH;
+  // Rotated operands only make sense in pairs that rotate the same way (App. C).
+  const bool a_rot = a_col && a->col_has_rht, b_rot = b_col && b->col_has_rht;
+  if (a_rot != b_rot || (a_rot && a->rht_seed != b->rht_seed)) return NVFP4_ERR_MISMATCH;
+  if (ka <= 0 || ka % 16 || g.a.outer <= 0 || g.b.outer <= 0) return NVFP4_ERR_BAD_SHAPE;
+  if (ldd < g.b.outer || ldd % 4) return NVFP4_ERR_BAD_SHAPE;
+  if (!aligned(d, 16) || !aligned(g.a.codes, 8) || !aligned(g.b.codes, 8)) return NVFP4_ERR_INVALID_ARG;
+  g.K = ka;
+  g.d = d;
+  g.ldd = ldd;
+  g.out_bf16 = out_dtype == NVFP4_OUT_BF16;
+  return launch_gemm(g, static_cast<hipStream_t>(stream)) == hipSuccess ? NVFP4_OK : NVFP4_ERR_HIP;
+}
+
+int nvfp4_dequantize(const nvfp4_qtensor* q, int which_copy, int undo_rht, void* out, int out_dtype,
+                     int64_t ld_out, nvfp4_stream_t stream) {
+  if (!q || !out) return NVFP4_ERR_INVALID_ARG;
+  if (which_copy != NVFP4_COPY_ROW && which_copy != NVFP4_COPY_COL) return NVFP4_ERR_INVALID_ARG;
+  if (out_dtype != NVFP4_OUT_F32 && out_dtype != NVFP4_OUT_BF16) return NVFP4_ERR_INVALID_ARG;
+  DequantArgs d;
+  int rc = pick_operand(q, which_copy == NVFP4_COPY_COL, &d.q, &d.K);
+  if (rc != NVFP4_OK) return rc;
+  if (undo_rht && !(which_copy == NVFP4_COPY_COL && q->col_has_rht)) return NVFP4_ERR_MISMATCH;
+  if (d.K <= 0 || d.K % 16 || ld_out < d.K || ld_out % 8) return NVFP4_ERR_BAD_SHAPE;
+  if (!aligned(out, 16) || !aligned(d.q.codes, 8)) return NVFP4_ERR_INVALID_ARG;
+  d.undo_rht = undo_rht != 0;
+  d.sign_mask = d.undo_rht ? host_rht_sign_mask(q->rht_seed) : 0u;
+  d.out = out;
+  d.ld_out = ld_out;
+  d.out_bf16 = out_dtype == NVFP4_OUT_BF16;
+  return launch_dequantize(d, static_cast<hipStream_t>(stream)) == hipSuccess ? NVFP4_OK : NVFP4_ERR_HIP;
+}
+
+int nvfp4_selftest_conversions(uint64_t* mismatches, nvfp4_stream_t stream) {
+  if (!mismatches || !aligned(mismatches, 8)) return NVFP4_ERR_INVALID_ARG;
+  return run_selftest(mismatches, static_cast<hipStream_t>(stream)) == hipSuccess ? NVFP4_OK : NVFP4_ERR_HIP;
+}
+
+}  // extern "C"

@@ -1,0 +1,78 @@
+// NVFP4 -> FP32 / bf16 decode for gfx950: value(code) * block scale * s_dec
+// (Sec. 2: decode with the reciprocal of the encode scale; App. B.2), with an
+// optional inverse of the 16-point rotation of App. C.
+#include "nvfp4_internal.h"
+#include "nvfp4_device.h"
+
+namespace nvfp4 {
+
+namespace {
+
+template <int kByte>
+__device__ __forceinline__ void decode_pair_f32(uint32_t codes, float* out) {
+  const float2v p = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(codes, 1.0f, kByte);
+  out[0] = p.x;
+  out[1] = p.y;
+}
+
+template <bool kBf16Out>
+__global__ __launch_bounds__(256) void dequantize_kernel(Operand q, int64_t K, bool undo_rht,
+                                                         uint32_t sign_mask, void* __restrict__ outv,
+                                                         int64_t ld_out) {
+  const int64_t nblk = K / 16;
+  const int64_t idx = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+  if (idx >= q.outer * nblk) return;
+  const int64_t o = idx / nblk, b = idx % nblk;
+  const uint2 c = *reinterpret_cast<const uint2*>(q.codes + o * (K / 2) + b * 8);
+  const float sd = e4m3_decode(q.scales[o * nblk + b]);
+  const float s_dec = q.ts[0];
+  float v[16];
+  decode_pair_f32<0>(c.x, v + 0);
+  decode_pair_f32<1>(c.x, v + 2);
+  decode_pair_f32<2>(c.x, v + 4);
+  decode_pair_f32<3>(c.x, v + 6);
+  decode_pair_f32<0>(c.y, v + 8);
+  decode_pair_f32<1>(c.y, v + 10);
+  decode_pair_f32<2>(c.y, v + 12);
+  decode_pair_f32<3>(c.y, v + 14);
+#pragma unroll
+  for (int k = 0; k < 16; ++k) {
+    const float t = v[k] * sd;
+    v[k] = t * s_dec;
+  }
+  if (undo_rht) rht16_inverse(v, sign_mask);
+  if (kBf16Out) {
+    uint32_t w[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) w[k] = f32_to_bf16(v[2 * k]) | (f32_to_bf16(v[2 * k + 1]) << 16);
+    uint4* dst = reinterpret_cast<uint4*>(static_cast<uint16_t*>(outv) + o * ld_out + b * 16);
+    dst[0] = make_uint4(w[0], w[1], w[2], w[3]);
+    dst[1] = make_uint4(w[4], w[5], w[6], w[7]);
+  } else {
+    float4v* dst = reinterpret_cast<float4v*>(static_cast<float*>(outv) + o * ld_out + b * 16);
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      float4v f;
+      f[0] = v[4 * t];
+      f[1] = v[4 * t + 1];
+      f[2] = v[4 * t + 2];
+      f[3] = v[4 * t + 3];
+      dst[t] = f;
+    }
+  }
+}
+
+}  // namespace
+
+hipError_t launch_dequantize(const DequantArgs& d, hipStream_t s) {
+  const int64_t total = d.q.outer * (d.K / 16);
+  if (total == 0) return hipSuccess;
+  const dim3 grid(static_cast<unsigned>((total + 255) / 256));
+  if (d.out_bf16)
+    hipLaunchKernelGGL(dequantize_kernel<true>, grid, dim3(256), 0, s, d.q, d.K, d.undo_rht, d.sign_mask, d.out, d.ld_out);
+  else
+    hipLaunchKernelGGL(dequantize_kernel<false>, grid, dim3(256), 0, s, d.q, d.K, d.undo_rht, d.sign_mask, d.out, d.ld_out);
+  return hipGetLastError();
+}
+
+}  // namespace nvfp4

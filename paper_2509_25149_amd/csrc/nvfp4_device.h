@@ -1,0 +1,155 @@
+// Device-side helpers shared by the gfx950 kernels: number-format conversions,
+// the Philox4x32-10 counter generator and the 16-point Hadamard butterfly.
+// gfx950 only; wavefront size 64.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace nvfp4 {
+
+typedef float float2v __attribute__((ext_vector_type(2)));
+typedef float float4v __attribute__((ext_vector_type(4)));
+typedef float float16v __attribute__((ext_vector_type(16)));
+typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+typedef _Float16 half8v __attribute__((ext_vector_type(8)));
+
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
+
+// FP32 -> bf16, round to nearest even (finite inputs; NaN stays NaN).
+__device__ __forceinline__ uint32_t f32_to_bf16(float f) {
+  uint32_t w = __float_as_uint(f);
+  if ((w & 0x7FFFFFFFu) > 0x7F800000u) return (w >> 16) | 0x40u;
+  return (w + 0x7FFFu + ((w >> 16) & 1u)) >> 16;
+}
+
+// Tensor-level encode / decode scale from the amax (App. B.1 Eq. 1).
+__device__ __forceinline__ void tensor_scales(float amax, float& s_enc, float& s_dec) {
+  if (amax == 0.0f) {
+    s_enc = 1.0f;
+  } else {
+    s_enc = 2688.0f / amax;  // 6 * 448
+    if (__builtin_isinf(s_enc)) s_enc = 3.4028234663852886e38f;
+  }
+  s_dec = 1.0f / s_enc;
+}
+
+// Non-negative FP32 -> E4M3 byte, RNE, saturating at 448 (App. B.2 Eq. 3).
+// v_cvt_pk_fp8_f32 rounds to nearest even and returns NaN above the range, so
+// the value is clamped first.
+__device__ __forceinline__ uint32_t e4m3_encode(float u) {
+  u = fminf(u, 448.0f);
+  return static_cast<uint32_t>(__builtin_amdgcn_cvt_pk_fp8_f32(u, 0.0f, 0, false)) & 0xFFu;
+}
+
+__device__ __forceinline__ float e4m3_decode(uint32_t code) {
+  return __builtin_amdgcn_cvt_f32_fp8(static_cast<int>(code), 0);
+}
+
+// Stored block scale and the "real" block encode scale (App. B.2):
+//   code    = e4m3(amax_b / 6 * s_enc)
+//   s_enc_b = 1 / (fp32(code) * s_dec), 0 when the stored scale is 0.
+__device__ __forceinline__ float block_scale(float amax_b, float s_enc, float s_dec, uint32_t& code) {
+  const float t = amax_b / 6.0f;
+  code = e4m3_encode(t * s_enc);
+  const float den = e4m3_decode(code) * s_dec;
+  return den == 0.0f ? 0.0f : 1.0f / den;
+}
+
+// Two scaled values -> one byte of two E2M1 codes written into byte `kSel`
+// of `old` (round to nearest even, saturating; matches the tie rule "even
+// code").  The instruction's scale operand divides by a power of two only; it
+// is held at 1.
+template <int kSel>
+__device__ __forceinline__ uint32_t cvt_rne_pair(uint32_t old, float v0, float v1) {
+  return __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(old, v0, v1, 1.0f, kSel);
+}
+
+// Stochastic rounding of one value with a 16-bit random integer placed in the
+// top half of `rand_hi16`: the instruction adds the top 22 bits of its random
+// operand below the kept mantissa bit, so with the low 16 bits clear it rounds
+// up iff floor(p * 2^16) + r >= 2^16.  The result's only meaningful bits are
+// the low nibble of byte `kSel`: the high nibble belongs to the pair's second
+// value (which sees a rotated random word), and the other three bytes are
+// whatever the destination register held -- this compiler does not tie the
+// builtin's first operand to its result, so partial results cannot be chained
+// through it and are merged with merge_bytes() instead.
+template <int kSel>
+__device__ __forceinline__ uint32_t cvt_sr_single(float v, uint32_t rand_hi16) {
+  float2v p;
+  p.x = v;
+  p.y = v;
+  return __builtin_amdgcn_cvt_scalef32_sr_pk_fp4_f32(0u, p, rand_hi16, 1.0f, kSel);
+}
+
+// byte t of the result is byte t of b[t]
+__device__ __forceinline__ uint32_t merge_bytes(uint32_t b0, uint32_t b1, uint32_t b2, uint32_t b3) {
+  const uint32_t hi = (b2 & 0x00FF0000u) | (b3 & ~0x00FF0000u);
+  const uint32_t lo = (b0 & 0x000000FFu) | (b1 & ~0x000000FFu);
+  return (lo & 0x0000FFFFu) | (hi & ~0x0000FFFFu);
+}
+
+// low nibbles of `even` and of `odd` interleaved: byte t = odd.nibble(2t) << 4 | even.nibble(2t)
+__device__ __forceinline__ uint32_t interleave_nibbles(uint32_t even, uint32_t odd) {
+  return (even & 0x0F0F0F0Fu) | ((odd << 4) & ~0x0F0F0F0Fu);
+}
+
+// Philox4x32-10 (Salmon et al., SC'11).
+__device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                              uint32_t k0, uint32_t k1, uint32_t out[4]) {
+#pragma unroll
+  for (int r = 0; r < 10; ++r) {
+    const uint64_t p0 = static_cast<uint64_t>(c0) * 0xD2511F53ull;
+    const uint64_t p1 = static_cast<uint64_t>(c2) * 0xCD9E8D57ull;
+    const uint32_t n0 = static_cast<uint32_t>(p1 >> 32) ^ c1 ^ k0;
+    const uint32_t n2 = static_cast<uint32_t>(p0 >> 32) ^ c3 ^ k1;
+    c1 = static_cast<uint32_t>(p1);
+    c3 = static_cast<uint32_t>(p0);
+    c0 = n0;
+    c2 = n2;
+    k0 += 0x9E3779B9u;
+    k1 += 0xBB67AE85u;
+  }
+  out[0] = c0;
+  out[1] = c1;
+  out[2] = c2;
+  out[3] = c3;
+}
+
+// y = H16 (s .* v): sign diagonal, butterfly stages h = 1, 2, 4, 8 in this
+// order, then the 1/4 normalisation (App. C).  Every add is one FP32 rounding.
+__device__ __forceinline__ void rht16(float v[16], uint32_t sign_mask) {
+#pragma unroll
+  for (int i = 0; i < 16; ++i)
+    v[i] = __uint_as_float(__float_as_uint(v[i]) ^ (((sign_mask >> i) & 1u) << 31));
+#pragma unroll
+  for (int h = 1; h < 16; h <<= 1) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      if ((i & h) == 0) {
+        const float a = v[i], b = v[i + h];
+        v[i] = a + b;
+        v[i + h] = a - b;
+      }
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < 16; ++i) v[i] *= 0.25f;
+}
+
+// x = s .* (H16 y)
+__device__ __forceinline__ void rht16_inverse(float v[16], uint32_t sign_mask) {
+  rht16(v, 0u);
+#pragma unroll
+  for (int i = 0; i < 16; ++i)
+    v[i] = __uint_as_float(__float_as_uint(v[i]) ^ (((sign_mask >> i) & 1u) << 31));
+}
+
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
+  return v;
+}
+
+}  // namespace nvfp4

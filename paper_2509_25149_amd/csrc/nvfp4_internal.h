@@ -1,0 +1,54 @@
+// Host-side launch interfaces between the C ABI (api.hip) and the kernel files.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace nvfp4 {
+
+struct QuantizeArgs {
+  const void* x;
+  int64_t rows, cols, ld;
+  bool want_row, want_col, rht, sr, block2d;
+  uint32_t sign_mask, key0, key1;
+  uint32_t* ws;  // device, 4 words: [0] raw amax bits, [1] rotated amax bits
+  uint8_t *row_codes, *row_scales;
+  float* row_ts;
+  uint8_t *col_codes, *col_scales;
+  float* col_ts;
+};
+hipError_t launch_quantize(const QuantizeArgs& a, hipStream_t s);
+
+// One K-contiguous operand: codes [outer, K/2], scales [outer, K/16], ts = {s_dec, amax}.
+struct Operand {
+  const uint8_t* codes;
+  const uint8_t* scales;
+  const float* ts;
+  int64_t outer;
+};
+struct GemmArgs {
+  Operand a, b;  // D[m, n] = sum_k A[m, k] B[n, k]
+  int64_t K;
+  void* d;
+  int64_t ldd;
+  bool out_bf16;
+};
+hipError_t launch_gemm(const GemmArgs& g, hipStream_t s);
+
+struct DequantArgs {
+  Operand q;
+  int64_t K;
+  bool undo_rht;
+  uint32_t sign_mask;
+  void* out;
+  int64_t ld_out;
+  bool out_bf16;
+};
+hipError_t launch_dequantize(const DequantArgs& d, hipStream_t s);
+
+hipError_t run_selftest(uint64_t* mismatches_dev, hipStream_t s);
+
+// Host Philox4x32-10, used only to derive the 16-bit sign diagonal from a seed.
+uint32_t host_rht_sign_mask(uint64_t seed);
+
+}  // namespace nvfp4

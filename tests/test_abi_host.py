@@ -1,0 +1,110 @@
+"""CPU-only checks of the C ABI: the library loads, exports every declared symbol,
+and rejects bad arguments synchronously (no kernel is ever enqueued here)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2509_25149_amd import binding as nv
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(nv.LIB_PATH):
+        from paper_2509_25149_amd import build
+        build.build_library()
+    return nv.load_library()
+
+
+def test_every_declared_symbol_is_exported(lib):
+    header = open(os.path.join(ROOT, "include", "nvfp4.h")).read()
+    declared = set(re.findall(r"\b(nvfp4_[a-z0-9_]+)\s*\(", header))
+    assert declared == set(nv.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert lib.nvfp4_version() >= 100
+
+
+def test_struct_layout_matches_header():
+    assert ctypes.sizeof(nv.QTensorStruct) == 2 * 8 + 6 * 8 + 4 * 4 + 8
+    assert nv.QTensorStruct.rht_seed.offset == 80
+
+
+def test_sizes(lib):
+    assert nv.quantized_sizes(256, 512) == (256 * 512 // 2, 256 * 512 // 16, 256)
+    for bad in ((0, 16), (16, 0), (24, 16), (16, 40), (-16, 16)):
+        with pytest.raises(nv.NVFP4Error) as e:
+            nv.quantized_sizes(*bad)
+        assert e.value.status == -2
+
+
+def test_status_strings(lib):
+    seen = set()
+    for s in range(0, -7, -1):
+        txt = lib.nvfp4_status_string(s).decode()
+        assert txt and txt != "unknown status"
+        seen.add(txt)
+    assert len(seen) == 7
+    assert lib.nvfp4_status_string(-99).decode() == "unknown status"
+
+
+def _desc(rows=16, cols=16, mask=3, rht=0, seed=0):
+    d = nv.QTensorStruct()
+    d.rows, d.cols = rows, cols
+    for f in ("row_codes", "row_scales", "row_tensor_scale", "col_codes", "col_scales", "col_tensor_scale"):
+        setattr(d, f, 0x10000)          # fake, aligned, never dereferenced by the checks below
+    d.layout_mask, d.block_dim, d.col_has_rht, d.rht_seed = mask, 1, rht, seed
+    return d
+
+
+def test_quantize_rejects_bad_arguments(lib):
+    d = _desc()
+    X, WS = 0x20000, 0x30000
+    q = lambda *a, **k: lib.nvfp4_quantize(*a)
+    ok_tail = (ctypes.byref(d), WS, 256, None)
+    assert lib.nvfp4_quantize(None, 16, 16, 16, 1, 1, 0, 0, 0, 0, *ok_tail) == -1
+    assert lib.nvfp4_quantize(X, 16, 16, 16, 0, 1, 0, 0, 0, 0, *ok_tail) == -1      # empty layout mask
+    assert lib.nvfp4_quantize(X, 16, 16, 16, 4, 1, 0, 0, 0, 0, *ok_tail) == -1
+    assert lib.nvfp4_quantize(X, 16, 16, 16, 1, 2, 0, 0, 0, 0, *ok_tail) == -1      # unknown block_dim
+    assert lib.nvfp4_quantize(X, 16, 16, 16, 1, 1, 7, 0, 0, 0, *ok_tail) == -1      # unknown rounding
+    assert lib.nvfp4_quantize(X, 16, 16, 16, 3, 16, 0, 1, 0, 0, *ok_tail) == -1     # rotation with 16x16 blocks
+    assert lib.nvfp4_quantize(X, 16, 16, 16, 1, 1, 0, 1, 0, 0, *ok_tail) == -1      # rotation without a col copy
+    assert lib.nvfp4_quantize(X, 24, 16, 16, 1, 1, 0, 0, 0, 0, *ok_tail) == -2
+    assert lib.nvfp4_quantize(X, 16, 40, 40, 1, 1, 0, 0, 0, 0, *ok_tail) == -2
+    assert lib.nvfp4_quantize(X, 16, 32, 16, 1, 1, 0, 0, 0, 0, *ok_tail) == -2      # ld < cols
+    assert lib.nvfp4_quantize(X + 2, 16, 16, 16, 1, 1, 0, 0, 0, 0, *ok_tail) == -1  # misaligned input
+    assert lib.nvfp4_quantize(X, 16, 16, 16, 1, 1, 0, 0, 0, 0, ctypes.byref(d), None, 256, None) == -6
+    assert lib.nvfp4_quantize(X, 16, 16, 16, 1, 1, 0, 0, 0, 0, ctypes.byref(d), WS, 8, None) == -6
+    d2 = _desc()
+    d2.col_codes = None
+    assert lib.nvfp4_quantize(X, 16, 16, 16, 2, 1, 0, 0, 0, 0, ctypes.byref(d2), WS, 256, None) == -1
+
+
+def test_gemm_and_dequantize_reject_bad_arguments(lib):
+    a, b = _desc(32, 64), _desc(64, 48)
+    D = 0x40000
+    assert lib.nvfp4_gemm(None, ctypes.byref(b), 0, D, 0, 48, None) == -1
+    assert lib.nvfp4_gemm(ctypes.byref(a), ctypes.byref(b), 9, D, 0, 48, None) == -1
+    assert lib.nvfp4_gemm(ctypes.byref(a), ctypes.byref(b), 0, D, 5, 48, None) == -1
+    assert lib.nvfp4_gemm(ctypes.byref(a), ctypes.byref(b), 0, D, 0, 32, None) == -2     # ldd < N
+    assert lib.nvfp4_gemm(ctypes.byref(a), ctypes.byref(b), 1, D, 0, 64, None) == -4     # DGRAD: K 64 vs 48
+    only_row = _desc(64, 48, mask=1)
+    assert lib.nvfp4_gemm(ctypes.byref(a), ctypes.byref(only_row), 0, D, 0, 48, None) == -3
+    # WGRAD operands must rotate alike
+    p, q = _desc(64, 32, rht=1, seed=5), _desc(64, 48, rht=0)
+    assert lib.nvfp4_gemm(ctypes.byref(p), ctypes.byref(q), 2, D, 0, 48, None) == -4
+    q2 = _desc(64, 48, rht=1, seed=6)
+    assert lib.nvfp4_gemm(ctypes.byref(p), ctypes.byref(q2), 2, D, 0, 48, None) == -4
+    assert lib.nvfp4_dequantize(ctypes.byref(a), 3, 0, D, 0, 64, None) == -1
+    assert lib.nvfp4_dequantize(ctypes.byref(a), 0, 1, D, 0, 64, None) == -4            # undo_rht on a plain copy
+    assert lib.nvfp4_dequantize(ctypes.byref(a), 0, 0, D, 0, 32, None) == -2
+    assert lib.nvfp4_dequantize(ctypes.byref(only_row), 1, 0, D, 0, 64, None) == -3
+
+
+def test_sign_mask_matches_the_oracle(lib):
+    import oracle
+    for seed in (0, 1, 2025, 0xDEADBEEFCAFE, 2 ** 64 - 1):
+        assert nv.rht_sign_mask(seed) == oracle.rht_sign_mask(seed)

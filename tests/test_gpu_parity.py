@@ -1,0 +1,227 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU oracle.
+
+Bar: codes, block scales, tensor scale and amax bit-exact (also under stochastic
+rounding with the same Philox counters and under the rotation with the fixed
+butterfly order); dequantize bit-exact; GEMM relative Frobenius error <= 1e-5
+against the binary64 reference on the dequantized operands.
+"""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2509_25149_amd import binding as nv, synth
+
+pytestmark = pytest.mark.gpu
+
+GEMM_TOL = 1e-5
+
+
+def to_dev(bits: np.ndarray) -> torch.Tensor:
+    return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda().view(torch.bfloat16)
+
+
+def assert_copy_equal(codes, scales, ts, ref: oracle.QCopy, what: str):
+    torch.cuda.synchronize()
+    c, s, t = codes.cpu().numpy(), scales.cpu().numpy(), ts.cpu().numpy()
+    assert t[1].view(np.uint32) == ref.amax.view(np.uint32), f"{what}: amax {t[1]} vs {ref.amax}"
+    assert t[0].view(np.uint32) == ref.s_dec.view(np.uint32), f"{what}: s_dec {t[0]} vs {ref.s_dec}"
+    bad_s = np.argwhere(s != ref.scales)
+    assert bad_s.size == 0, f"{what}: {len(bad_s)} scale bytes differ, first at {bad_s[0]}"
+    bad_c = np.argwhere(c != ref.codes)
+    assert bad_c.size == 0, f"{what}: {len(bad_c)} code bytes differ, first at {bad_c[0]}"
+
+
+def check_quantize(xb, layout, block_dim=nv.BLOCK_1x16, rounding=nv.ROUND_RNE, rht=False, rht_seed=0, sr_seed=0,
+                   x_dev=None):
+    x = to_dev(xb) if x_dev is None else x_dev
+    q = nv.nvfp4_quantize(x, layout, block_dim, rounding, rht, rht_seed, sr_seed)
+    ob = oracle.BLOCK_16x16 if block_dim == nv.BLOCK_16x16 else oracle.BLOCK_1x16
+    orr = oracle.SR if rounding == nv.ROUND_SR else oracle.RNE
+    refs = {}
+    if layout & nv.LAYOUT_ROW:
+        refs["row"] = oracle.quantize(xb, oracle.ROW, ob, orr, False, 0, sr_seed)
+        assert_copy_equal(q.row_codes, q.row_scales, q.row_ts, refs["row"], "row copy")
+    if layout & nv.LAYOUT_COL:
+        refs["col"] = oracle.quantize(xb, oracle.COL, ob, orr, rht, rht_seed, sr_seed)
+        assert_copy_equal(q.col_codes, q.col_scales, q.col_ts, refs["col"], "col copy")
+    return q, refs
+
+
+def test_conversion_instructions_selftest():
+    assert nv.nvfp4_selftest_conversions() == [0, 0, 0]
+
+
+@pytest.mark.parametrize("name", ["handworked_A.txt", "handworked_B.txt"])
+def test_handworked_tensors(golden_dir, name):
+    g = {}
+    for line in open(os.path.join(golden_dir, name)):
+        line = line.strip()
+        if line and not line.startswith("#"):
+            k, v = line.split(":")
+            g[k.strip()] = v.split()
+    x = np.array([float(t) for t in g["x"]], dtype=np.float32)
+    xb = np.tile(synth.f32_to_bf16_bits(x).reshape(1, -1), (16, 1))
+    q, _ = check_quantize(xb, nv.LAYOUT_ROW)
+    codes = q.row_codes.cpu().numpy()[0]
+    c4 = np.stack([codes & 15, codes >> 4], -1).ravel()
+    assert [int(v) for v in c4] == [int(t, 16) for t in g["codes"]]
+    assert [int(v) for v in q.row_scales.cpu().numpy()[0]] == [int(t, 16) for t in g["scales"]]
+    assert q.row_ts.cpu().numpy()[0].view(np.uint32) == int(g["s_dec_bits"][0], 16)
+
+
+SHAPES = [(16, 16), (16, 1040), (80, 528), (144, 2064)]   # several 512-column tiles plus ragged tails
+MODES = [
+    dict(layout=nv.LAYOUT_ROW),
+    dict(layout=nv.LAYOUT_COL),
+    dict(layout=nv.LAYOUT_ROW | nv.LAYOUT_COL),
+    dict(layout=nv.LAYOUT_COL, rht=True, rht_seed=2025),
+    dict(layout=nv.LAYOUT_ROW | nv.LAYOUT_COL, rht=True, rht_seed=7),
+    dict(layout=nv.LAYOUT_ROW, rounding=nv.ROUND_SR, sr_seed=0xC0FFEE1234),
+    dict(layout=nv.LAYOUT_COL, rounding=nv.ROUND_SR, sr_seed=99),
+    dict(layout=nv.LAYOUT_ROW | nv.LAYOUT_COL, rounding=nv.ROUND_SR, rht=True, rht_seed=11, sr_seed=2 ** 63 + 17),
+    dict(layout=nv.LAYOUT_ROW | nv.LAYOUT_COL, block_dim=nv.BLOCK_16x16),
+    dict(layout=nv.LAYOUT_COL, block_dim=nv.BLOCK_16x16),
+    dict(layout=nv.LAYOUT_ROW | nv.LAYOUT_COL, block_dim=nv.BLOCK_16x16, rounding=nv.ROUND_SR, sr_seed=3),
+]
+
+
+@pytest.mark.parametrize("shape", SHAPES)
+@pytest.mark.parametrize("mode", MODES, ids=lambda m: "-".join(f"{k}{v}" for k, v in m.items()))
+def test_quantize_modes(shape, mode):
+    rows, cols = shape
+    gen = [synth.normal_with_outliers(rows, cols, 1.0, 1000 + rows + cols, frac=0.01),
+           synth.student_t3(rows, cols, 1e-3, 2000 + rows + cols)]
+    for xb in gen:
+        check_quantize(xb, **mode)
+
+
+def test_quantize_with_leading_dimension():
+    xb = synth.normal(48, 96, 1.0, 77)
+    big = torch.zeros((48, 128), dtype=torch.bfloat16, device="cuda")
+    big[:, :96] = to_dev(xb)
+    check_quantize(xb, nv.LAYOUT_ROW | nv.LAYOUT_COL, rht=True, rht_seed=5, x_dev=big[:, :96])
+
+
+def test_quantize_degenerate_inputs():
+    z = np.zeros((32, 64), dtype=np.float32)
+    check_quantize(synth.f32_to_bf16_bits(z), nv.LAYOUT_ROW | nv.LAYOUT_COL)
+    z[3, 7] = -0.0
+    z[0, 16] = 1.0
+    z[1, 0] = -1e-6
+    z[1, 1] = 1e-7
+    z[20, 40] = -3.0
+    for kw in (dict(), dict(rht=True, rht_seed=1), dict(block_dim=nv.BLOCK_16x16), dict(rounding=nv.ROUND_SR, sr_seed=4)):
+        check_quantize(synth.f32_to_bf16_bits(z), nv.LAYOUT_ROW | nv.LAYOUT_COL, **kw)
+    # subnormal-range tensors: 2688/amax overflows and is clamped; s_dec is subnormal
+    t = np.zeros((16, 32), dtype=np.float32)
+    t[0, 0] = 1e-38
+    t[5, 20] = -3e-39
+    t[9, 9] = 1e-40
+    check_quantize(synth.f32_to_bf16_bits(t), nv.LAYOUT_ROW | nv.LAYOUT_COL)
+    # huge values
+    h = synth.bf16_bits_to_f32(synth.normal(32, 32, 1.0, 5)) * np.float32(1e37)
+    check_quantize(synth.f32_to_bf16_bits(h), nv.LAYOUT_ROW | nv.LAYOUT_COL, rht=True, rht_seed=3)
+
+
+def test_nonfinite_input_is_flagged_in_amax():
+    x = synth.bf16_bits_to_f32(synth.normal(16, 32, 1.0, 6))
+    x[3, 3] = np.inf
+    q = nv.nvfp4_quantize(to_dev(synth.f32_to_bf16_bits(x)), nv.LAYOUT_ROW)
+    torch.cuda.synchronize()
+    assert not np.isfinite(q.row_ts.cpu().numpy()[1])
+
+
+def test_two_d_weight_copies_are_transposes():
+    wb = synth.normal(96, 160, 0.02, 8)
+    q, _ = check_quantize(wb, nv.LAYOUT_ROW | nv.LAYOUT_COL, nv.BLOCK_16x16)
+    r, c = q.row_codes.cpu().numpy(), q.col_codes.cpu().numpy()
+    un = lambda b: np.stack([b & 15, b >> 4], -1).reshape(b.shape[0], -1)
+    assert np.array_equal(un(r), un(c).T)
+
+
+def test_quantize_is_deterministic():
+    xb = synth.student_t3(64, 1024, 1e-3, 9)
+    x = to_dev(xb)
+    a = nv.nvfp4_quantize(x, 3, rounding=nv.ROUND_SR, rht_on_col=True, rht_seed=1, sr_seed=2)
+    b = nv.nvfp4_quantize(x, 3, rounding=nv.ROUND_SR, rht_on_col=True, rht_seed=1, sr_seed=2)
+    torch.cuda.synchronize()
+    assert torch.equal(a.row_codes, b.row_codes) and torch.equal(a.col_codes, b.col_codes)
+    assert torch.equal(a.col_scales, b.col_scales)
+
+
+# ---------------------------------------------------------------- dequantize
+
+def test_dequantize_matches_oracle_bitwise():
+    xb = synth.normal_with_outliers(48, 160, 1.0, 21, frac=0.01)
+    q, refs = check_quantize(xb, nv.LAYOUT_ROW | nv.LAYOUT_COL, rht=True, rht_seed=31)
+    for copy, key, undo in ((nv.COPY_ROW, "row", False), (nv.COPY_COL, "col", False), (nv.COPY_COL, "col", True)):
+        got = nv.nvfp4_dequantize(q, copy, undo).cpu().numpy()
+        want = oracle.dequantize(refs[key], undo, 31)
+        assert np.array_equal(got.view(np.uint32), want.view(np.uint32)), (key, undo)
+        got16 = nv.nvfp4_dequantize(q, copy, undo, nv.OUT_BF16).view(torch.int16).cpu().numpy().view(np.uint16)
+        assert np.array_equal(got16, synth.f32_to_bf16_bits(want))
+    back = nv.nvfp4_dequantize(q, nv.COPY_COL, True).cpu().numpy().T
+    x = synth.bf16_bits_to_f32(xb)
+    assert np.linalg.norm(back - x) < 0.15 * np.linalg.norm(x)
+
+
+# ---------------------------------------------------------------- GEMM
+
+def rel_fro(got, ref):
+    return float(np.linalg.norm(got.astype(np.float64) - ref) / np.linalg.norm(ref))
+
+
+def test_config1_fprop_full():
+    t = synth.config_tensors(1)
+    qx, rx = check_quantize(t["X"], nv.LAYOUT_ROW)
+    qw, rw = check_quantize(t["W"], nv.LAYOUT_ROW | nv.LAYOUT_COL, nv.BLOCK_16x16)
+    y = nv.nvfp4_gemm(qx, qw, nv.OP_FPROP, nv.OUT_F32)
+    ref = oracle.gemm_f64(rx["row"], rw["col"])
+    assert y.shape == (256, 256)
+    assert rel_fro(y.cpu().numpy(), ref) <= GEMM_TOL
+    y16 = nv.nvfp4_gemm(qx, qw, nv.OP_FPROP, nv.OUT_BF16)
+    assert np.array_equal(y16.view(torch.int16).cpu().numpy().view(np.uint16), synth.f32_to_bf16_bits(y.cpu().numpy()))
+    # Dgrad reuses the same quantized weight, transposed, without requantizing (Sec. 4.3)
+    dyb = synth.student_t3(256, 256, 1e-3, 103)
+    qd, rd = check_quantize(dyb, nv.LAYOUT_ROW, rounding=nv.ROUND_SR, sr_seed=1)
+    dx = nv.nvfp4_gemm(qd, qw, nv.OP_DGRAD, nv.OUT_F32)
+    assert dx.shape == (256, 512)
+    assert rel_fro(dx.cpu().numpy(), oracle.gemm_f64(rd["row"], rw["row"])) <= GEMM_TOL
+
+
+@pytest.mark.parametrize("mnk", [(16, 16, 16), (80, 48, 80), (272, 144, 176), (128, 384, 1040)])
+def test_gemm_ragged_shapes_all_ops(mnk):
+    M, N, K = mnk
+    xb = synth.normal_with_outliers(M, K, 1.0, 300 + M, frac=0.01)
+    wb = synth.normal(K, N, 0.02, 400 + N)
+    qx, rx = check_quantize(xb, nv.LAYOUT_ROW | nv.LAYOUT_COL, rht=True, rht_seed=12)
+    qw, rw = check_quantize(wb, nv.LAYOUT_ROW | nv.LAYOUT_COL, nv.BLOCK_16x16)
+    y = nv.nvfp4_gemm(qx, qw, nv.OP_FPROP).cpu().numpy()
+    assert rel_fro(y, oracle.gemm_f64(rx["row"], rw["col"])) <= GEMM_TOL
+    dyb = synth.student_t3(M, N, 1e-3, 500 + M)
+    qd, rd = check_quantize(dyb, nv.LAYOUT_ROW | nv.LAYOUT_COL, rounding=nv.ROUND_SR, rht=True, rht_seed=12, sr_seed=8)
+    dx = nv.nvfp4_gemm(qd, qw, nv.OP_DGRAD).cpu().numpy()
+    assert dx.shape == (M, K)
+    assert rel_fro(dx, oracle.gemm_f64(rd["row"], rw["row"])) <= GEMM_TOL
+    dw = nv.nvfp4_gemm(qd, qx, nv.OP_WGRAD).cpu().numpy()          # dY^T X : [N, K]
+    assert dw.shape == (N, K)
+    ref = oracle.gemm_f64(rd["col"], rx["col"])
+    assert rel_fro(dw, ref) <= GEMM_TOL
+    # the rotation cancels: the result approximates the unquantized product
+    exact = synth.bf16_bits_to_f32(dyb).astype(np.float64).T @ synth.bf16_bits_to_f32(xb).astype(np.float64)
+    if M >= 80:
+        assert np.linalg.norm(ref - exact) <= 0.3 * np.linalg.norm(exact)
+
+
+def test_gemm_output_with_leading_dimension():
+    xb, wb = synth.normal(32, 64, 1.0, 61), synth.normal(64, 48, 0.02, 62)
+    qx, rx = check_quantize(xb, nv.LAYOUT_ROW)
+    qw, rw = check_quantize(wb, nv.LAYOUT_COL, nv.BLOCK_16x16)
+    buf = torch.full((32, 64), 7.0, dtype=torch.float32, device="cuda")
+    nv.nvfp4_gemm(qx, qw, nv.OP_FPROP, out=buf[:, :48])
+    got = buf.cpu().numpy()
+    assert np.all(got[:, 48:] == 7.0)
+    assert rel_fro(got[:, :48], oracle.gemm_f64(rx["row"], rw["col"])) <= GEMM_TOL
