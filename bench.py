@@ -1,0 +1,197 @@
+#!/usr/bin/env python3
+"""Benchmark of the NVFP4 hot path on one MI355X.
+
+One "step" is one NVFP4 linear layer of the 12B model's MLP up-projection,
+forward and backward, on 8192 tokens (model dimension 5120, FFN dimension 20480):
+
+    qX  = quantize(X,  row + rotated col, 1x16, RNE)
+    qW  = quantize(W,  row + col, 16x16, RNE)
+    Y   = gemm(qX, qW, FPROP)  -> bf16  [8192, 20480]   (K = 5120)
+    qdY = quantize(dY, row + rotated col, 1x16, SR)
+    dX  = gemm(qdY, qW, DGRAD) -> bf16  [8192, 5120]    (K = 20480)
+    dW  = gemm(qX, qdY, WGRAD) -> fp32  [5120, 20480]   (K = 8192)
+    Xd  = dequantize(qX row copy) -> bf16
+
+Inputs are seeded synthetic tensors already resident in HBM.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+TOKENS, D_MODEL, D_FFN = 8192, 5120, 20480
+PEAK_HBM_GBPS = 8000.0
+PEAK_MFMA_F16_TFLOPS = 2500.0
+PEAK_MFMA_F8_TFLOPS = 5000.0
+
+
+def make_inputs(torch):
+    g = torch.Generator(device="cuda")
+    g.manual_seed(20250925)
+    x = torch.randn((TOKENS, D_MODEL), generator=g, device="cuda", dtype=torch.float32)
+    hit = torch.rand((TOKENS, D_MODEL), generator=g, device="cuda") < 1e-3
+    x = torch.where(hit, x * 50.0, x).to(torch.bfloat16)                       # N(0,1) + 0.1% x50 outliers
+    w = (torch.randn((D_MODEL, D_FFN), generator=g, device="cuda", dtype=torch.float32) * 0.02).to(torch.bfloat16)
+    z = torch.randn((4, TOKENS, D_FFN), generator=g, device="cuda", dtype=torch.float32)
+    dy = (z[0] / torch.sqrt((z[1] ** 2 + z[2] ** 2 + z[3] ** 2) / 3.0) * 1e-3).to(torch.bfloat16)  # 1e-3 * t(3)
+    del z, hit
+    return x, w, dy
+
+
+def quant_bytes(n_elems: int, copies: int) -> float:
+    """Algorithmic HBM bytes of one quantize call, one-pass accounting: the bf16
+    tensor read once, plus per copy n/2 code bytes and n/16 scale bytes."""
+    return 2.0 * n_elems + copies * (n_elems / 2.0 + n_elems / 16.0)
+
+
+def cpu_baseline(torch, nv, x, w):
+    """Time the CPU oracle on a bounded sample of the same workload."""
+    import numpy as np
+    import oracle
+    m, n = 8192, 8192
+    xb = x[:m].contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+    wb = w[:, :n].contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+    oracle.lib()
+    t0 = time.perf_counter()
+    ox = oracle.quantize(xb, oracle.ROW)
+    ow = oracle.quantize(wb, oracle.COL, oracle.BLOCK_16x16)
+    t1 = time.perf_counter()
+    ref = oracle.gemm_f64(ox, ow)
+    t2 = time.perf_counter()
+    # spot-check the GPU path on the same sample while we are here
+    qx = nv.nvfp4_quantize(x[:m].contiguous(), nv.LAYOUT_ROW)
+    qw = nv.nvfp4_quantize(w[:, :n].contiguous(), nv.LAYOUT_COL, nv.BLOCK_16x16)
+    y = nv.nvfp4_gemm(qx, qw, nv.OP_FPROP).cpu().numpy().astype(np.float64)
+    err = float(np.linalg.norm(y - ref) / np.linalg.norm(ref))
+    exact = bool(np.array_equal(qx.row_codes.cpu().numpy(), ox.codes) and
+                 np.array_equal(qw.col_codes.cpu().numpy(), ow.codes) and
+                 np.array_equal(qx.row_scales.cpu().numpy(), ox.scales))
+    flops = 2.0 * m * n * D_MODEL
+    q_bytes = quant_bytes(m * D_MODEL, 1) + quant_bytes(D_MODEL * n, 1)
+    return {
+        "value": flops / (t2 - t0) / 1e12, "unit": "TFLOP/s", "cores": oracle.num_threads(), "kind": "oracle",
+        "sample": f"Fprop on {m} tokens x {n} FFN columns: quantize X[{m}x{D_MODEL}] (1x16) and "
+                  f"W[{D_MODEL}x{n}] (16x16), fp64 GEMM {m}x{n}x{D_MODEL}",
+        "gemm_TFLOPs": flops / (t2 - t1) / 1e12, "quantize_GBps": q_bytes / (t1 - t0) / 1e9,
+        "seconds": t2 - t0, "gpu_vs_oracle_rel_fro": err, "gpu_codes_bit_exact": exact,
+    }
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2509_25149_amd import binding as nv
+    nv.load_library()
+    torch.cuda.set_device(0)
+    x, w, dy = make_inputs(torch)
+
+    RC = nv.LAYOUT_ROW | nv.LAYOUT_COL
+    qx = nv.alloc_qtensor(TOKENS, D_MODEL, RC)
+    qw = nv.alloc_qtensor(D_MODEL, D_FFN, RC)
+    qdy = nv.alloc_qtensor(TOKENS, D_FFN, RC)
+    y = torch.empty((TOKENS, D_FFN), dtype=torch.bfloat16, device="cuda")
+    dx = torch.empty((TOKENS, D_MODEL), dtype=torch.bfloat16, device="cuda")
+    dw = torch.empty((D_MODEL, D_FFN), dtype=torch.float32, device="cuda")
+    xd = torch.empty((TOKENS, D_MODEL), dtype=torch.bfloat16, device="cuda")
+    RHT_SEED, SR_SEED = 2025, 0x5EED
+
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    gemm_events, quant_events = [], []
+
+    def step(timed: bool, it: int):
+        marks = [ev() for _ in range(8)] if timed else None
+        rec = (lambda i: marks[i].record()) if timed else (lambda i: None)
+        rec(0)
+        nv.nvfp4_quantize(x, RC, nv.BLOCK_1x16, nv.ROUND_RNE, True, RHT_SEED, 0, out=qx)
+        rec(1)
+        nv.nvfp4_quantize(w, RC, nv.BLOCK_16x16, nv.ROUND_RNE, False, 0, 0, out=qw)
+        rec(2)
+        nv.nvfp4_gemm(qx, qw, nv.OP_FPROP, nv.OUT_BF16, out=y)
+        rec(3)
+        nv.nvfp4_quantize(dy, RC, nv.BLOCK_1x16, nv.ROUND_SR, True, RHT_SEED, SR_SEED + it, out=qdy)
+        rec(4)
+        nv.nvfp4_gemm(qdy, qw, nv.OP_DGRAD, nv.OUT_BF16, out=dx)
+        rec(5)
+        nv.nvfp4_gemm(qx, qdy, nv.OP_WGRAD, nv.OUT_F32, out=dw)
+        rec(6)
+        nv.nvfp4_dequantize(qx, nv.COPY_ROW, False, nv.OUT_BF16, out=xd)
+        rec(7)
+        if timed:
+            gemm_events.extend([(marks[2], marks[3]), (marks[4], marks[5]), (marks[5], marks[6])])
+            quant_events.append([(marks[0], marks[1]), (marks[1], marks[2]), (marks[3], marks[4])])
+
+    for i in range(args.warmup):
+        step(False, i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(True, args.warmup + i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    gemm_flops = 2.0 * TOKENS * D_MODEL * D_FFN            # per GEMM launch
+    step_flops = 3.0 * gemm_flops
+    gemm_ms = [a.elapsed_time(b) for a, b in gemm_events]
+    gemm_avg_ms = sum(gemm_ms) / len(gemm_ms)
+    gemm_tflops = gemm_flops / (gemm_avg_ms * 1e-3) / 1e12
+    per_op = {k: sum(gemm_ms[i::3]) / args.steps for i, k in enumerate(("fprop", "dgrad", "wgrad"))}
+
+    n_x, n_w, n_dy = TOKENS * D_MODEL, D_MODEL * D_FFN, TOKENS * D_FFN
+    q_ms = [[a.elapsed_time(b) for a, b in trio] for trio in quant_events]
+    q_avg = [sum(t[i] for t in q_ms) / len(q_ms) for i in range(3)]
+    q_bytes = [quant_bytes(n_x, 2), quant_bytes(n_w, 2), quant_bytes(n_dy, 2)]
+    q_gbps = [b / (ms * 1e-3) / 1e9 for b, ms in zip(q_bytes, q_avg)]
+    q_total_gbps = sum(q_bytes) / (sum(q_avg) * 1e-3) / 1e9
+
+    out = {
+        "metric": "NVFP4 quantize GB/s + block-scaled GEMM TFLOP/s at 12B linear shapes, %roofline",
+        "value": step_flops / (ms_per_step * 1e-3) / 1e12,
+        "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "fp4(e2m1)xe4m3 operands decoded to f16, f32 accumulate", "data": "synthetic",
+        "config": {"workload": "one NVFP4 linear layer fwd+bwd at the 12B MLP up-projection shape: 8192 tokens, "
+                               "5120 -> 20480 (BASELINE configs 3+4+5 plus Wgrad at the same shape): quantize X, W, dY "
+                               "(row + col copies, RHT on the Wgrad copies, SR on dY), Fprop/Dgrad/Wgrad GEMM, dequantize",
+                   "tokens": TOKENS, "d_model": D_MODEL, "d_ffn": D_FFN},
+        "value_definition": "3 GEMMs x 2*8192*5120*20480 flop divided by the whole step time (quantizers and dequantize included)",
+        "gemm": {"TFLOPs_per_launch_avg": gemm_tflops, "ms": per_op,
+                 "frac_of_f16_mfma_peak": gemm_tflops / PEAK_MFMA_F16_TFLOPS,
+                 "frac_of_fp8_mfma_peak": gemm_tflops / PEAK_MFMA_F8_TFLOPS},
+        "quantize": {"GBps_total_one_pass_accounting": q_total_gbps,
+                     "per_tensor": {"X_8192x5120_rne_rht": {"ms": q_avg[0], "GBps": q_gbps[0]},
+                                    "W_5120x20480_2d": {"ms": q_avg[1], "GBps": q_gbps[1]},
+                                    "dY_8192x20480_sr_rht": {"ms": q_avg[2], "GBps": q_gbps[2]}},
+                     "note": "call time = clear + amax pass + cast pass; bytes = bf16 read once + both copies written"},
+        "roofline": {"kernel": "gemm_kernel", "bound": "mfma", "achieved": gemm_tflops, "peak": PEAK_MFMA_F16_TFLOPS,
+                     "unit": "TFLOP/s", "frac": gemm_tflops / PEAK_MFMA_F16_TFLOPS, "traffic": None},
+        "roofline_quantize": {"kernel": "amax_kernel + cast_kernel", "bound": "hbm", "achieved": q_total_gbps,
+                              "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": q_total_gbps / PEAK_HBM_GBPS,
+                              "traffic": None},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(torch, nv, x, w)
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -151,9 +151,221 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_kernel(Operand A, Operand B
   }
 }
 
+
+// ---------------------------------------------------------------- large-tile kernel
+// 256 x 256 outputs per workgroup, K step 64, 512 threads = 8 wavefronts in a
+// 2 (m) x 4 (n) grid, each owning 128 x 64 outputs as 4 x 2 MFMA 32x32 blocks
+// (128 accumulator registers per lane).  The decoded FP16 tiles are
+// double-buffered in LDS (2 x 64 KiB), one barrier per K step.
+//
+// The two halves of the workgroup run the step's two phases in opposite
+// order ("ping-pong"): wavefronts 0-3 (one per SIMD) issue their global loads,
+// run the step's 32 MFMAs and then decode the NEXT A tile into the other LDS
+// buffer; wavefronts 4-7 first decode the next B tile, then issue their loads
+// for the step after and run their MFMAs.  On every SIMD one wavefront is
+// therefore in its VALU/LDS-write phase while the other keeps the matrix pipe
+// busy.  Inside the MFMA phase the fragments of sub-step kk+1 are read from LDS
+// before the MFMAs of sub-step kk are issued.
+//
+// LDS layout: one row = 64 FP16 = eight 16-byte chunks, no padding; chunk c of
+// row r is stored at chunk position c ^ ((r >> 1) & 7).  With a 128-byte row
+// stride, 16 consecutive rows reading the same logical chunk then touch 16
+// different 16-byte bank groups, and the staging writes are conflict free too.
+constexpr int TM = 256, TN = 256, TK = 64;
+constexpr int kBigThreads = 512;
+constexpr int kRowBytes = TK * 2;                         // 128
+constexpr int kOperandBytes = TM * kRowBytes;              // 32 KiB per operand tile
+constexpr int kStageBytes = 2 * kOperandBytes;             // 64 KiB
+
+__device__ __forceinline__ int swz(int row, int chunk) { return row * kRowBytes + ((chunk ^ ((row >> 1) & 7)) << 4); }
+
+struct Prefetch {
+  uint4 lo, hi;     // 64 codes of one row
+  uint32_t scales;  // four E4M3 bytes
+};
+
+__device__ __forceinline__ void fetch_row(Prefetch& p, const Operand& op, int64_t K, int64_t row, int64_t k) {
+  p.lo = make_uint4(0u, 0u, 0u, 0u);
+  p.hi = make_uint4(0u, 0u, 0u, 0u);
+  p.scales = 0u;
+  if (row < op.outer) {
+    const uint4* c = reinterpret_cast<const uint4*>(op.codes + row * (K / 2) + k / 2);
+    p.lo = c[0];
+    p.hi = c[1];
+    p.scales = *reinterpret_cast<const uint32_t*>(op.scales + row * (K / 16) + k / 16);
+  }
+}
+
+__device__ __forceinline__ void stage_decoded(const Prefetch& p, char* tile, int row) {
+  const half2v h0 = scale_to_half2(p.scales & 0xFFu), h1 = scale_to_half2((p.scales >> 8) & 0xFFu);
+  const half2v h2 = scale_to_half2((p.scales >> 16) & 0xFFu), h3 = scale_to_half2(p.scales >> 24);
+  *reinterpret_cast<uint4*>(tile + swz(row, 0)) = decode8(p.lo.x, h0);
+  *reinterpret_cast<uint4*>(tile + swz(row, 1)) = decode8(p.lo.y, h0);
+  *reinterpret_cast<uint4*>(tile + swz(row, 2)) = decode8(p.lo.z, h1);
+  *reinterpret_cast<uint4*>(tile + swz(row, 3)) = decode8(p.lo.w, h1);
+  *reinterpret_cast<uint4*>(tile + swz(row, 4)) = decode8(p.hi.x, h2);
+  *reinterpret_cast<uint4*>(tile + swz(row, 5)) = decode8(p.hi.y, h2);
+  *reinterpret_cast<uint4*>(tile + swz(row, 6)) = decode8(p.hi.z, h3);
+  *reinterpret_cast<uint4*>(tile + swz(row, 7)) = decode8(p.hi.w, h3);
+}
+
+struct Frags {
+  half8v a[4], b[2];
+};
+
+__device__ __forceinline__ void load_frags(Frags& f, const char* at, const char* bt, int arow, int brow, int chunk) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) f.a[i] = *reinterpret_cast<const half8v*>(at + swz(arow + i * 32, chunk));
+#pragma unroll
+  for (int j = 0; j < 2; ++j) f.b[j] = *reinterpret_cast<const half8v*>(bt + swz(brow + j * 32, chunk));
+}
+
+__device__ __forceinline__ void mma_step(float16v (&acc)[4][2], const Frags& f) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(f.b[j], f.a[i], acc[i][j], 0, 0, 0);
+}
+
+// The 32 MFMAs of one K step, fragments prefetched one sub-step ahead.
+__device__ __forceinline__ void mma_tile(float16v (&acc)[4][2], const char* at, const char* bt, int arow, int brow,
+                                         int lhi) {
+  Frags f0, f1;
+  load_frags(f0, at, bt, arow, brow, 0 + lhi);
+  load_frags(f1, at, bt, arow, brow, 2 + lhi);
+  mma_step(acc, f0);
+  load_frags(f0, at, bt, arow, brow, 4 + lhi);
+  mma_step(acc, f1);
+  load_frags(f1, at, bt, arow, brow, 6 + lhi);
+  mma_step(acc, f0);
+  mma_step(acc, f1);
+}
+
+template <bool kBf16Out>
+__global__ __launch_bounds__(kBigThreads) void gemm_kernel_256(Operand A, Operand B, int64_t K,
+                                                               void* __restrict__ Dv, int64_t ldd,
+                                                               int tiles_m, int tiles_n) {
+  extern __shared__ __attribute__((aligned(16))) char lds[];
+
+  // Workgroup -> output tile.  Consecutive workgroup ids land on different XCDs
+  // (round robin over 8), each with its own L2: give every XCD a contiguous
+  // range of tiles, walked in bands of 8 tile-rows so that the A and B panels a
+  // band touches stay L2 resident.
+  const int num_tiles = tiles_m * tiles_n;
+  int pid = blockIdx.x;
+  if ((num_tiles & 7) == 0) pid = (pid & 7) * (num_tiles >> 3) + (pid >> 3);
+  constexpr int kBand = 8;
+  const int band = pid / (kBand * tiles_n);
+  const int band_rows = min(kBand, tiles_m - band * kBand);
+  const int in_band = pid - band * kBand * tiles_n;
+  const int tm = band * kBand + in_band % band_rows;
+  const int tn = in_band / band_rows;
+  const int64_t m0 = static_cast<int64_t>(tm) * TM, n0 = static_cast<int64_t>(tn) * TN;
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int group = wave >> 2;           // 0: stages A, MFMA first; 1: stages B, decode first
+  const int wm = wave >> 2, wn = wave & 3;
+  const int l32 = lane & 31, lhi = lane >> 5;
+  const int srow = tid & 255;            // the operand-tile row this thread stages
+  const int arow = wm * 128 + l32, brow = wn * 64 + l32;
+
+  float16v acc[4][2];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+  const Operand& mine = group == 0 ? A : B;
+  const int64_t my_row = (group == 0 ? m0 : n0) + srow;
+  const int my_off = group == 0 ? 0 : kOperandBytes;
+  const int KT = static_cast<int>(K / TK);
+
+  // Schedule per K step t (S = decode + store to LDS, M = the step's MFMAs, | = barrier):
+  //   wavefronts 0-3:  M(t) S_A(t+1) | M(t+1) S_A(t+2) | ...
+  //   wavefronts 4-7:  S_B(t+1) M(t) | S_B(t+2) M(t+1) | ...
+  // written as one loop body  "fetch; M(t); [group 0: S(t+1)]; barrier; [group 1: S(t+2)]".
+  Prefetch cur, nxt;
+  fetch_row(cur, mine, K, my_row, 0);
+  stage_decoded(cur, lds + my_off, srow);
+  if (group == 1 && KT > 1) {
+    fetch_row(cur, mine, K, my_row, TK);
+    stage_decoded(cur, lds + kStageBytes + my_off, srow);
+  }
+  // Global loads run two K steps ahead of their decode, so the decode never waits on memory.
+  if (1 + group < KT) fetch_row(cur, mine, K, my_row, static_cast<int64_t>(1 + group) * TK);
+  __syncthreads();
+
+  for (int kt = 0; kt < KT; ++kt) {
+    const char* tile = lds + (kt & 1) * kStageBytes;
+    const int ahead = kt + 1 + group;    // the K step this wavefront stages during step kt
+    if (ahead + 1 < KT) fetch_row(nxt, mine, K, my_row, static_cast<int64_t>(ahead + 1) * TK);
+    mma_tile(acc, tile, tile + kOperandBytes, arow, brow, lhi);
+    if (group == 0 && ahead < KT) stage_decoded(cur, lds + (ahead & 1) * kStageBytes + my_off, srow);
+    __syncthreads();
+    if (group == 1 && ahead < KT) stage_decoded(cur, lds + (ahead & 1) * kStageBytes + my_off, srow);
+    cur = nxt;
+  }
+
+  const float out_scale = A.ts[0] * B.ts[0];
+  const int M = static_cast<int>(A.outer - m0 < TM ? A.outer - m0 : TM);
+  const int N = static_cast<int>(B.outer - n0 < TN ? B.outer - n0 : TN);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int m = wm * 128 + i * 32 + l32;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int n = wn * 64 + j * 32 + q * 8 + lhi * 4;
+        if (m < M && n < N) {
+          float4v v;
+#pragma unroll
+          for (int t = 0; t < 4; ++t) v[t] = acc[i][j][q * 4 + t] * out_scale;
+          if (kBf16Out) {
+            uint16_t* d = static_cast<uint16_t*>(Dv) + (m0 + m) * ldd + n0 + n;
+            uint2 o;
+            o.x = f32_to_bf16(v[0]) | (f32_to_bf16(v[1]) << 16);
+            o.y = f32_to_bf16(v[2]) | (f32_to_bf16(v[3]) << 16);
+            *reinterpret_cast<uint2*>(d) = o;
+          } else {
+            float* d = static_cast<float*>(Dv) + (m0 + m) * ldd + n0 + n;
+            *reinterpret_cast<float4v*>(d) = v;
+          }
+        }
+      }
+    }
+  }
+}
+
 }  // namespace
 
 hipError_t launch_gemm(const GemmArgs& g, hipStream_t s) {
+  // The large-tile kernel needs whole K steps of 64 and 16-byte aligned code rows.
+  const bool big = (g.K % TK == 0) && (reinterpret_cast<uintptr_t>(g.a.codes) % 16 == 0) &&
+                   (reinterpret_cast<uintptr_t>(g.b.codes) % 16 == 0);
+  if (big) {
+    static bool attr_set = false;
+    if (!attr_set) {
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel_256<true>),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, 2 * kStageBytes);
+      if (e == hipSuccess)
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel_256<false>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, 2 * kStageBytes);
+      if (e != hipSuccess) return e;
+      attr_set = true;
+    }
+    const int tiles_m = static_cast<int>((g.a.outer + TM - 1) / TM), tiles_n = static_cast<int>((g.b.outer + TN - 1) / TN);
+    const dim3 grid(static_cast<unsigned>(tiles_m * tiles_n));
+    if (g.out_bf16)
+      hipLaunchKernelGGL(gemm_kernel_256<true>, grid, dim3(kBigThreads), 2 * kStageBytes, s, g.a, g.b, g.K, g.d, g.ldd, tiles_m, tiles_n);
+    else
+      hipLaunchKernelGGL(gemm_kernel_256<false>, grid, dim3(kBigThreads), 2 * kStageBytes, s, g.a, g.b, g.K, g.d, g.ldd, tiles_m, tiles_n);
+    return hipGetLastError();
+  }
   const dim3 grid(static_cast<unsigned>((g.b.outer + BN - 1) / BN), static_cast<unsigned>((g.a.outer + BM - 1) / BM));
   if (g.out_bf16)
     hipLaunchKernelGGL(gemm_kernel<true>, grid, dim3(kGemmThreads), 0, s, g.a, g.b, g.K, g.d, g.ldd);
