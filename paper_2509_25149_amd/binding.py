@@ -133,10 +133,10 @@ def alloc_qtensor(rows: int, cols: int, layout_mask: int, device="cuda") -> QTen
 _workspaces = {}
 
 
-def _workspace(device) -> torch.Tensor:
+def _workspace(device, nbytes: int) -> torch.Tensor:
     key = (torch.device(device).index or 0, _stream())
-    if key not in _workspaces:
-        _workspaces[key] = torch.empty(256, dtype=torch.uint8, device=device)
+    if key not in _workspaces or _workspaces[key].numel() < nbytes:
+        _workspaces[key] = torch.empty(max(nbytes, 1 << 16), dtype=torch.uint8, device=device)
     return _workspaces[key]
 
 
@@ -149,7 +149,7 @@ def nvfp4_quantize(x: torch.Tensor, layout_mask: int, block_dim: int = BLOCK_1x1
     rows, cols = x.shape
     if out is None:
         out = alloc_qtensor(rows, cols, layout_mask, x.device)
-    ws = workspace if workspace is not None else _workspace(x.device)
+    ws = workspace if workspace is not None else _workspace(x.device, quantized_sizes(rows, cols)[2])
     _check(load_library().nvfp4_quantize(x.data_ptr(), rows, cols, x.stride(0), layout_mask, block_dim, rounding,
                                          int(rht_on_col), rht_seed, sr_seed, ctypes.byref(out.desc),
                                          ws.data_ptr(), ws.numel(), _stream()))

@@ -26,7 +26,6 @@ void host_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t o
 
 bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
-constexpr size_t kWorkspaceBytes = 256;
 
 }  // namespace
 
@@ -66,7 +65,7 @@ int nvfp4_quantized_sizes(int64_t rows, int64_t cols, size_t* codes_bytes, size_
   if (rows <= 0 || cols <= 0 || rows % 16 || cols % 16) return NVFP4_ERR_BAD_SHAPE;
   if (codes_bytes) *codes_bytes = static_cast<size_t>(rows) * static_cast<size_t>(cols) / 2;
   if (scales_bytes) *scales_bytes = static_cast<size_t>(rows) * static_cast<size_t>(cols) / 16;
-  if (workspace_bytes) *workspace_bytes = kWorkspaceBytes;
+  if (workspace_bytes) *workspace_bytes = quantize_workspace_bytes(rows, cols);
   return NVFP4_OK;
 }
 
@@ -83,9 +82,9 @@ int nvfp4_quantize(const void* x, int64_t rows, int64_t cols, int64_t ld, int la
   if (!aligned(x, 16)) return NVFP4_ERR_INVALID_ARG;
   if (want_row && (!out->row_codes || !out->row_scales || !out->row_tensor_scale)) return NVFP4_ERR_INVALID_ARG;
   if (want_col && (!out->col_codes || !out->col_scales || !out->col_tensor_scale)) return NVFP4_ERR_INVALID_ARG;
-  if (want_row && !aligned(out->row_codes, 16)) return NVFP4_ERR_INVALID_ARG;
-  if (want_col && !aligned(out->col_codes, 16)) return NVFP4_ERR_INVALID_ARG;
-  if (!workspace || workspace_bytes < kWorkspaceBytes || !aligned(workspace, 16)) return NVFP4_ERR_WORKSPACE;
+  if (want_row && (!aligned(out->row_codes, 16) || !aligned(out->row_scales, 16))) return NVFP4_ERR_INVALID_ARG;
+  if (want_col && (!aligned(out->col_codes, 16) || !aligned(out->col_scales, 16))) return NVFP4_ERR_INVALID_ARG;
+  if (!workspace || workspace_bytes < quantize_workspace_bytes(rows, cols) || !aligned(workspace, 16)) return NVFP4_ERR_WORKSPACE;
 
   QuantizeArgs a;
   a.x = x;

@@ -11,13 +11,14 @@ struct QuantizeArgs {
   int64_t rows, cols, ld;
   bool want_row, want_col, rht, sr, block2d;
   uint32_t sign_mask, key0, key1;
-  uint32_t* ws;  // device, 4 words: [0] raw amax bits, [1] rotated amax bits
+  uint32_t* ws;  // device workspace: [0] raw amax bits, [1] rotated amax bits, then per-workgroup partials
   uint8_t *row_codes, *row_scales;
   float* row_ts;
   uint8_t *col_codes, *col_scales;
   float* col_ts;
 };
 hipError_t launch_quantize(const QuantizeArgs& a, hipStream_t s);
+size_t quantize_workspace_bytes(int64_t rows, int64_t cols);
 
 // One K-contiguous operand: codes [outer, K/2], scales [outer, K/16], ts = {s_dec, amax}.
 struct Operand {

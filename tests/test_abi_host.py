@@ -34,7 +34,9 @@ def test_struct_layout_matches_header():
 
 
 def test_sizes(lib):
-    assert nv.quantized_sizes(256, 512) == (256 * 512 // 2, 256 * 512 // 16, 256)
+    assert nv.quantized_sizes(256, 512)[:2] == (256 * 512 // 2, 256 * 512 // 16)
+    assert 64 <= nv.quantized_sizes(256, 512)[2] <= 4096
+    assert nv.quantized_sizes(8192, 20480)[2] >= 2 * 40 * 64 * 4
     for bad in ((0, 16), (16, 0), (24, 16), (16, 40), (-16, 16)):
         with pytest.raises(nv.NVFP4Error) as e:
             nv.quantized_sizes(*bad)
