@@ -1,0 +1,128 @@
+"""GPU parity at the full sizes of the BASELINE configs 2-5 (the shapes bench.py times).
+
+Quantizer outputs are compared with the CPU oracle in full (bit-exact).  The big
+GEMMs are compared on a seeded sample of output entries the oracle computes one
+by one in binary64 (full rows, full columns and tiles), relative Frobenius error
+over the sample <= 1e-5; properties that hold at any size (bf16 output equals the
+rounded FP32 output, determinism) are checked on the whole matrix.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2509_25149_amd import binding as nv, synth
+
+pytestmark = pytest.mark.gpu
+
+GEMM_TOL = 1e-5
+RHT_SEED, SR_SEED = 2025, 0x5EED5EED5EED
+
+
+def to_dev(bits):
+    return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda().view(torch.bfloat16)
+
+
+def assert_copy(codes, scales, ts, ref, what):
+    torch.cuda.synchronize()
+    t = ts.cpu().numpy()
+    assert t[1].view(np.uint32) == ref.amax.view(np.uint32), f"{what}: amax"
+    assert t[0].view(np.uint32) == ref.s_dec.view(np.uint32), f"{what}: s_dec"
+    assert np.array_equal(scales.cpu().numpy(), ref.scales), f"{what}: scales differ"
+    assert np.array_equal(codes.cpu().numpy(), ref.codes), f"{what}: codes differ"
+
+
+def sample_entries(M, N, seed, rows=4, cols=4, tile=32):
+    """Seeded sample: a few full rows, full columns and two tiles (one touching the last row/column)."""
+    rng = np.random.default_rng(seed)
+    m_list, n_list = [], []
+    for r in rng.choice(M, rows, replace=False):
+        m_list.append(np.full(N, r)); n_list.append(np.arange(N))
+    for c in rng.choice(N, cols, replace=False):
+        m_list.append(np.arange(M)); n_list.append(np.full(M, c))
+    for (r0, c0) in ((M - tile, N - tile), (int(rng.integers(0, M - tile)), int(rng.integers(0, N - tile)))):
+        mm, nn = np.meshgrid(np.arange(r0, r0 + tile), np.arange(c0, c0 + tile), indexing="ij")
+        m_list.append(mm.ravel()); n_list.append(nn.ravel())
+    return np.concatenate(m_list), np.concatenate(n_list)
+
+
+def check_gemm_sample(d_gpu, a_ref, b_ref, seed):
+    M, N = d_gpu.shape
+    m, n = sample_entries(M, N, seed)
+    want = oracle.gemm_f64_entries(a_ref, b_ref, m, n)
+    got = d_gpu[torch.from_numpy(m).cuda(), torch.from_numpy(n).cuda()].double().cpu().numpy()
+    err = np.linalg.norm(got - want) / np.linalg.norm(want)
+    assert err <= GEMM_TOL, f"relative Frobenius error over {m.size} sampled entries: {err}"
+    return err
+
+
+@pytest.fixture(scope="module")
+def weight():
+    """W 5120x20480 of configs 3 and 4, quantized once with 16x16 blocks, both orientations."""
+    wb = synth.normal(5120, 20480, 0.02, 302)
+    qw = nv.nvfp4_quantize(to_dev(wb), nv.LAYOUT_ROW | nv.LAYOUT_COL, nv.BLOCK_16x16)
+    ref_col = oracle.quantize(wb, oracle.COL, oracle.BLOCK_16x16)
+    ref_row = oracle.quantize(wb, oracle.ROW, oracle.BLOCK_16x16)
+    assert_copy(qw.col_codes, qw.col_scales, qw.col_ts, ref_col, "W col copy")
+    assert_copy(qw.row_codes, qw.row_scales, qw.row_ts, ref_row, "W row copy")
+    return qw, ref_row, ref_col
+
+
+def test_config2_wgrad_rht_sr():
+    t = synth.config_tensors(2)
+    qdy = nv.nvfp4_quantize(to_dev(t["dY"]), nv.LAYOUT_COL, rounding=nv.ROUND_SR, rht_on_col=True,
+                            rht_seed=RHT_SEED, sr_seed=SR_SEED)
+    qx = nv.nvfp4_quantize(to_dev(t["X"]), nv.LAYOUT_COL, rht_on_col=True, rht_seed=RHT_SEED)
+    rdy = oracle.quantize(t["dY"], oracle.COL, rounding=oracle.SR, use_rht=True, rht_seed=RHT_SEED, sr_seed=SR_SEED)
+    rx = oracle.quantize(t["X"], oracle.COL, use_rht=True, rht_seed=RHT_SEED)
+    assert_copy(qdy.col_codes, qdy.col_scales, qdy.col_ts, rdy, "dY col copy (RHT, SR)")
+    assert_copy(qx.col_codes, qx.col_scales, qx.col_ts, rx, "X col copy (RHT, RNE)")
+    dw = nv.nvfp4_gemm(qdy, qx, nv.OP_WGRAD, nv.OUT_F32)
+    assert dw.shape == (5120, 5120)
+    check_gemm_sample(dw, rdy, rx, 22)
+    again = nv.nvfp4_gemm(qdy, qx, nv.OP_WGRAD, nv.OUT_F32)
+    assert torch.equal(dw, again)
+
+
+def test_config3_fprop(weight):
+    qw, _, ref_col = weight
+    xb = synth.normal_with_outliers(8192, 5120, 1.0, 301)
+    qx = nv.nvfp4_quantize(to_dev(xb), nv.LAYOUT_ROW)
+    rx = oracle.quantize(xb, oracle.ROW)
+    assert_copy(qx.row_codes, qx.row_scales, qx.row_ts, rx, "X row copy")
+    y = nv.nvfp4_gemm(qx, qw, nv.OP_FPROP, nv.OUT_F32)
+    assert y.shape == (8192, 20480)
+    check_gemm_sample(y, rx, ref_col, 33)
+    y16 = nv.nvfp4_gemm(qx, qw, nv.OP_FPROP, nv.OUT_BF16)
+    assert torch.equal(y16, y.to(torch.bfloat16))          # bf16 output = RNE of the FP32 output
+
+
+def test_config4_dgrad(weight):
+    qw, ref_row, _ = weight
+    dyb = synth.student_t3(8192, 20480, 1e-3, 401)
+    qdy = nv.nvfp4_quantize(to_dev(dyb), nv.LAYOUT_ROW, rounding=nv.ROUND_SR, sr_seed=SR_SEED)
+    rdy = oracle.quantize(dyb, oracle.ROW, rounding=oracle.SR, sr_seed=SR_SEED)
+    assert_copy(qdy.row_codes, qdy.row_scales, qdy.row_ts, rdy, "dY row copy (SR)")
+    dx = nv.nvfp4_gemm(qdy, qw, nv.OP_DGRAD, nv.OUT_F32)       # same quantized W, transposed, no requantization
+    assert dx.shape == (8192, 5120)
+    check_gemm_sample(dx, rdy, ref_row, 44)
+
+
+@pytest.mark.parametrize("name,mode", [
+    ("T1", dict(rounding=nv.ROUND_RNE, rht_on_col=True)),                    # activation: row RNE + col RHT RNE
+    ("T2", dict(rounding=nv.ROUND_SR, rht_on_col=True)),                     # gradient: row SR + col RHT SR
+    ("T3", dict(block_dim=nv.BLOCK_16x16)),                                  # weight: 16x16, both orientations
+])
+def test_config5_quantize_sweep(name, mode):
+    shapes = {"T1": (8192, 5120, 501), "T2": (8192, 20480, 502), "T3": (5120, 20480, 503)}
+    rows, cols, seed = shapes[name]
+    xb = synth.student_t3(rows, cols, 0.02, seed)
+    q = nv.nvfp4_quantize(to_dev(xb), nv.LAYOUT_ROW | nv.LAYOUT_COL, rht_seed=RHT_SEED, sr_seed=SR_SEED, **mode)
+    ob = oracle.BLOCK_16x16 if mode.get("block_dim") == nv.BLOCK_16x16 else oracle.BLOCK_1x16
+    orr = oracle.SR if mode.get("rounding") == nv.ROUND_SR else oracle.RNE
+    rht = bool(mode.get("rht_on_col"))
+    row = oracle.quantize(xb, oracle.ROW, ob, orr, False, 0, SR_SEED)
+    assert_copy(q.row_codes, q.row_scales, q.row_ts, row, f"{name} row copy")
+    del row
+    col = oracle.quantize(xb, oracle.COL, ob, orr, rht, RHT_SEED, SR_SEED)
+    assert_copy(q.col_codes, q.col_scales, q.col_ts, col, f"{name} col copy")
