@@ -137,6 +137,13 @@ def main() -> int:
             gemm_events.extend([(marks[2], marks[3]), (marks[4], marks[5]), (marks[5], marks[6])])
             quant_events.append([(marks[0], marks[1]), (marks[1], marks[2]), (marks[3], marks[4])])
 
+    # A plain device copy of known size (1 GiB read + 1 GiB write), outside the timed region: under
+    # rocprofv3 --pmc it calibrates FETCH_SIZE / WRITE_SIZE against known HBM traffic.
+    cal_src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+    cal_dst = torch.empty_like(cal_src)
+    cal_dst.copy_(cal_src)
+    del cal_src, cal_dst
+
     for i in range(args.warmup):
         step(False, i)
     torch.cuda.synchronize()
