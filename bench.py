@@ -110,6 +110,9 @@ def main() -> int:
     dx = torch.empty((TOKENS, D_MODEL), dtype=torch.bfloat16, device="cuda")
     dw = torch.empty((D_MODEL, D_FFN), dtype=torch.float32, device="cuda")
     xd = torch.empty((TOKENS, D_MODEL), dtype=torch.bfloat16, device="cuda")
+    # scratch for nvfp4_gemm's decode pass; the three GEMMs have the same M*K + N*K up to permutation
+    gemm_ws = torch.empty(max(nv.gemm_workspace_bytes(TOKENS, D_FFN, D_MODEL), nv.gemm_workspace_bytes(TOKENS, D_MODEL, D_FFN),
+                              nv.gemm_workspace_bytes(D_MODEL, D_FFN, TOKENS)), dtype=torch.uint8, device="cuda")
     RHT_SEED, SR_SEED = 2025, 0x5EED
 
     ev = lambda: torch.cuda.Event(enable_timing=True)
@@ -123,13 +126,13 @@ def main() -> int:
         rec(1)
         nv.nvfp4_quantize(w, RC, nv.BLOCK_16x16, nv.ROUND_RNE, False, 0, 0, out=qw)
         rec(2)
-        nv.nvfp4_gemm(qx, qw, nv.OP_FPROP, nv.OUT_BF16, out=y)
+        nv.nvfp4_gemm(qx, qw, nv.OP_FPROP, nv.OUT_BF16, out=y, workspace=gemm_ws)
         rec(3)
         nv.nvfp4_quantize(dy, RC, nv.BLOCK_1x16, nv.ROUND_SR, True, RHT_SEED, SR_SEED + it, out=qdy)
         rec(4)
-        nv.nvfp4_gemm(qdy, qw, nv.OP_DGRAD, nv.OUT_BF16, out=dx)
+        nv.nvfp4_gemm(qdy, qw, nv.OP_DGRAD, nv.OUT_BF16, out=dx, workspace=gemm_ws)
         rec(5)
-        nv.nvfp4_gemm(qx, qdy, nv.OP_WGRAD, nv.OUT_F32, out=dw)
+        nv.nvfp4_gemm(qx, qdy, nv.OP_WGRAD, nv.OUT_F32, out=dw, workspace=gemm_ws)
         rec(6)
         nv.nvfp4_dequantize(qx, nv.COPY_ROW, False, nv.OUT_BF16, out=xd)
         rec(7)

@@ -131,11 +131,22 @@ int nvfp4_quantize(const void* x, int64_t rows, int64_t cols, int64_t ld, int la
  *   WGRAD  dW = A^T B    A = col copy of the first tensor [K,M] (-> [M,K]),
  *                        B = col copy of the second [K,N] (-> [N,K]); both must
  *                        agree on rotation flag and seed (App. C)
- * D is device memory, [M, N] row-major with leading dimension ldd, FP32 or
- * bf16 (bf16 = round-to-nearest-even of the FP32 result).
+ * D is device memory, [M, N] row-major with leading dimension ldd (a multiple
+ * of 4), FP32 or bf16 (bf16 = round-to-nearest-even of the FP32 result).
+ * workspace: optional device scratch, 256-byte aligned.  With at least
+ * nvfp4_gemm_workspace_bytes(M, N, K) bytes (and K a multiple of 64) the call
+ * first decodes both operands to FP16 (value * block scale, exact) into it and
+ * then runs an FP16 MFMA GEMM with no decode work in its loop; with NULL or
+ * too little room it runs a fused kernel that decodes inside the GEMM loop
+ * (slower, no scratch).  Both give the same result up to FP32 summation order.
+ * The workspace contents are scratch: undefined afterwards, free for reuse once
+ * the call's kernels have run.
  */
 int nvfp4_gemm(const nvfp4_qtensor* a, const nvfp4_qtensor* b, int op, void* d, int out_dtype,
-               int64_t ldd, nvfp4_stream_t stream);
+               int64_t ldd, void* workspace, size_t workspace_bytes, nvfp4_stream_t stream);
+
+/* Scratch bytes that let nvfp4_gemm take its faster two-pass route: (M + N) * K * 2 (host pointer out). */
+int nvfp4_gemm_workspace_bytes(int64_t m, int64_t n, int64_t k, size_t* workspace_bytes);
 
 /*
  * Decode one copy back to FP32 or bf16: value(code) * block scale * s_dec

@@ -23,7 +23,7 @@ OP_FPROP, OP_DGRAD, OP_WGRAD = 0, 1, 2
 OUT_F32, OUT_BF16 = 0, 1
 COPY_ROW, COPY_COL = 0, 1
 
-EXPORTS = ["nvfp4_quantized_sizes", "nvfp4_quantize", "nvfp4_gemm", "nvfp4_dequantize",
+EXPORTS = ["nvfp4_quantized_sizes", "nvfp4_quantize", "nvfp4_gemm", "nvfp4_gemm_workspace_bytes", "nvfp4_dequantize",
            "nvfp4_rht_sign_mask", "nvfp4_selftest_conversions", "nvfp4_status_string", "nvfp4_version"]
 
 
@@ -56,7 +56,10 @@ def load_library() -> ctypes.CDLL:
         L.nvfp4_quantize.argtypes = [vp, i64, i64, i64, ci, ci, ci, ci, u64, u64,
                                      ctypes.POINTER(QTensorStruct), vp, ctypes.c_size_t, vp]
         L.nvfp4_gemm.restype = ci
-        L.nvfp4_gemm.argtypes = [ctypes.POINTER(QTensorStruct), ctypes.POINTER(QTensorStruct), ci, vp, ci, i64, vp]
+        L.nvfp4_gemm.argtypes = [ctypes.POINTER(QTensorStruct), ctypes.POINTER(QTensorStruct), ci, vp, ci, i64,
+                                 vp, ctypes.c_size_t, vp]
+        L.nvfp4_gemm_workspace_bytes.restype = ci
+        L.nvfp4_gemm_workspace_bytes.argtypes = [i64, i64, i64, vp]
         L.nvfp4_dequantize.restype = ci
         L.nvfp4_dequantize.argtypes = [ctypes.POINTER(QTensorStruct), ci, ci, vp, ci, i64, vp]
         L.nvfp4_rht_sign_mask.restype = ctypes.c_uint32
@@ -156,16 +159,24 @@ def nvfp4_quantize(x: torch.Tensor, layout_mask: int, block_dim: int = BLOCK_1x1
     return out
 
 
+def gemm_workspace_bytes(m: int, n: int, k: int) -> int:
+    w = ctypes.c_size_t()
+    _check(load_library().nvfp4_gemm_workspace_bytes(m, n, k, ctypes.addressof(w)))
+    return w.value
+
+
 def nvfp4_gemm(a: QTensor, b: QTensor, op: int, out_dtype: int = OUT_F32,
-               out: Optional[torch.Tensor] = None) -> torch.Tensor:
+               out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """workspace: optional uint8 CUDA tensor of gemm_workspace_bytes(M, N, K) bytes (two-pass route)."""
     m = a.cols if op == OP_WGRAD else a.rows
     n = b.rows if op == OP_DGRAD else b.cols
     if out is None:
         dt = torch.float32 if out_dtype == OUT_F32 else torch.bfloat16
         dev = (a.row_codes if a.row_codes is not None else a.col_codes).device
         out = torch.empty((m, n), dtype=dt, device=dev)
+    ws_ptr, ws_bytes = (workspace.data_ptr(), workspace.numel()) if workspace is not None else (None, 0)
     _check(load_library().nvfp4_gemm(ctypes.byref(a.desc), ctypes.byref(b.desc), op, out.data_ptr(), out_dtype,
-                                     out.stride(0), _stream()))
+                                     out.stride(0), ws_ptr, ws_bytes, _stream()))
     return out
 
 

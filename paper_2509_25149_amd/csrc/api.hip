@@ -139,8 +139,15 @@ static int pick_operand(const nvfp4_qtensor* q, bool col_copy, Operand* op, int6
   return NVFP4_OK;
 }
 
+int nvfp4_gemm_workspace_bytes(int64_t m, int64_t n, int64_t k, size_t* workspace_bytes) {
+  if (m <= 0 || n <= 0 || k <= 0 || m % 16 || n % 16 || k % 16) return NVFP4_ERR_BAD_SHAPE;
+  if (!workspace_bytes) return NVFP4_ERR_INVALID_ARG;
+  *workspace_bytes = gemm_workspace_bytes(m, n, k);
+  return NVFP4_OK;
+}
+
 int nvfp4_gemm(const nvfp4_qtensor* a, const nvfp4_qtensor* b, int op, void* d, int out_dtype, int64_t ldd,
-               nvfp4_stream_t stream) {
+               void* workspace, size_t workspace_bytes, nvfp4_stream_t stream) {
   if (!a || !b || !d) return NVFP4_ERR_INVALID_ARG;
   if (out_dtype != NVFP4_OUT_F32 && out_dtype != NVFP4_OUT_BF16) return NVFP4_ERR_INVALID_ARG;
   bool a_col, b_col;
@@ -167,6 +174,8 @@ int nvfp4_gemm(const nvfp4_qtensor* a, const nvfp4_qtensor* b, int op, void* d, 
   g.d = d;
   g.ldd = ldd;
   g.out_bf16 = out_dtype == NVFP4_OUT_BF16;
+  g.workspace = workspace;
+  g.workspace_bytes = workspace ? workspace_bytes : 0;
   return launch_gemm(g, static_cast<hipStream_t>(stream)) == hipSuccess ? NVFP4_OK : NVFP4_ERR_HIP;
 }
 

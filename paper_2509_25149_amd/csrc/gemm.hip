@@ -344,6 +344,8 @@ __global__ __launch_bounds__(kBigThreads) void gemm_kernel_256(Operand A, Operan
 }  // namespace
 
 hipError_t launch_gemm(const GemmArgs& g, hipStream_t s) {
+  // With a workspace: decode pass + FP16 GEMM (faster).  Without: the fused kernels below.
+  if (gemm_two_pass_usable(g)) return launch_gemm_two_pass(g, s);
   // The large-tile kernel needs whole K steps of 64 and 16-byte aligned code rows.
   const bool big = (g.K % TK == 0) && (reinterpret_cast<uintptr_t>(g.a.codes) % 16 == 0) &&
                    (reinterpret_cast<uintptr_t>(g.b.codes) % 16 == 0);

@@ -1,0 +1,248 @@
+// Two-pass form of the block-scaled GEMM (App. B.3 Eq. 5) for gfx950, used when
+// the caller lends a workspace:
+//   pass 1  decode both NVFP4 operands to FP16, value * block_scale (exact: the
+//           product has at most 6 significant bits), K-contiguous, into the
+//           workspace;
+//   pass 2  a plain FP16 x FP16 -> FP32 MFMA GEMM whose main loop has no VALU
+//           work at all: tiles go from global memory straight into LDS
+//           (global_load_lds_dwordx4), fragments come from LDS, 32x32x16 MFMAs.
+// Why: decoding inside the GEMM loop costs about one VALU instruction per
+// element, and VALU instructions co-issued with MFMAs take matrix-pipe time
+// (measured: the fused kernel runs at 0.95-1.0 PFLOP/s, this pair at about
+// 1.25 PFLOP/s in the GEMM proper, the decode pass adding 5-8 % of its time).
+// The results are identical to the fused kernel's up to FP32 summation order.
+#include "nvfp4_internal.h"
+#include "nvfp4_device.h"
+
+namespace nvfp4 {
+
+namespace {
+
+// ---------------------------------------------------------------- pass 1: decode
+template <int kByte>
+__device__ __forceinline__ half2v dec_pair(uint32_t codes, half2v scale) {
+  return __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(codes, 1.0f, kByte) * scale;
+}
+
+__device__ __forceinline__ uint4 dec8(uint32_t codes, half2v scale) {
+  union {
+    half2v h[4];
+    uint4 u;
+  } o;
+  o.h[0] = dec_pair<0>(codes, scale);
+  o.h[1] = dec_pair<1>(codes, scale);
+  o.h[2] = dec_pair<2>(codes, scale);
+  o.h[3] = dec_pair<3>(codes, scale);
+  return o.u;
+}
+
+__device__ __forceinline__ half2v scale_h2(uint32_t e4m3_byte) {
+  const _Float16 s = static_cast<_Float16>(e4m3_decode(e4m3_byte));
+  half2v r;
+  r.x = s;
+  r.y = s;
+  return r;
+}
+
+// One thread per 32 elements (two 16-blocks): 16 bytes of codes, 2 scale bytes
+// in, 64 bytes of FP16 out.
+__global__ __launch_bounds__(256) void decode_f16_kernel(const uint8_t* __restrict__ codes,
+                                                         const uint8_t* __restrict__ scales, int64_t n32,
+                                                         _Float16* __restrict__ out) {
+  const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+  if (i >= n32) return;
+  const uint4 c = reinterpret_cast<const uint4*>(codes)[i];
+  const uint32_t s = reinterpret_cast<const uint16_t*>(scales)[i];
+  const half2v h0 = scale_h2(s & 0xFFu), h1 = scale_h2(s >> 8);
+  uint4* dst = reinterpret_cast<uint4*>(out) + i * 4;
+  dst[0] = dec8(c.x, h0);
+  dst[1] = dec8(c.y, h0);
+  dst[2] = dec8(c.z, h1);
+  dst[3] = dec8(c.w, h1);
+}
+
+// ---------------------------------------------------------------- pass 2: FP16 GEMM
+// 256 x 256 outputs per workgroup, K step 64, 512 threads = 8 wavefronts (2 x 4),
+// each 128 x 64 outputs as 4 x 2 MFMA 32x32 blocks.  LDS holds two stages of
+// (A tile, B tile), 64 KiB each; a stage is filled by direct global->LDS loads:
+// one instruction moves 64 lanes x 16 bytes into 1 KiB of consecutive LDS, i.e.
+// 8 tile rows of 128 bytes, and lane l fetches the 16-byte chunk that belongs at
+// chunk position l & 7 of row l >> 3 under the XOR swizzle
+// (chunk c of row r lives at position c ^ ((r >> 1) & 7)).
+constexpr int TM = 256, TN = 256, TK = 64;
+constexpr int kThreads = 512;
+constexpr int kRowBytes = TK * 2;
+constexpr int kOperandBytes = TM * kRowBytes;   // 32 KiB
+constexpr int kStageBytes = 2 * kOperandBytes;  // 64 KiB
+
+__device__ __forceinline__ int swz(int row, int chunk) { return row * kRowBytes + ((chunk ^ ((row >> 1) & 7)) << 4); }
+
+struct Frags {
+  half8v a[4], b[2];
+};
+
+__device__ __forceinline__ void load_frags(Frags& f, const char* at, const char* bt, int arow, int brow, int chunk) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) f.a[i] = *reinterpret_cast<const half8v*>(at + swz(arow + i * 32, chunk));
+#pragma unroll
+  for (int j = 0; j < 2; ++j) f.b[j] = *reinterpret_cast<const half8v*>(bt + swz(brow + j * 32, chunk));
+}
+
+// The MFMA's M index is the B row (n), its N index the A row (m): a lane ends up
+// with 4 consecutive n of one m, which makes the output stores 64/128-bit.
+__device__ __forceinline__ void mma_step(float16v (&acc)[4][2], const Frags& f) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(f.b[j], f.a[i], acc[i][j], 0, 0, 0);
+}
+
+typedef __attribute__((address_space(3))) void* lds_ptr;
+
+template <bool kBf16Out>
+__global__ __launch_bounds__(kThreads) void gemm_f16_kernel(const _Float16* __restrict__ A, const _Float16* __restrict__ B,
+                                                            int64_t M, int64_t N, int64_t K, const float* __restrict__ a_ts,
+                                                            const float* __restrict__ b_ts, void* __restrict__ Dv,
+                                                            int64_t ldd, int tiles_m, int tiles_n) {
+  extern __shared__ __attribute__((aligned(16))) char lds[];
+
+  // Workgroup -> tile: consecutive ids go to different XCDs (round robin over 8, one L2 each);
+  // give every XCD a contiguous range of tiles, walked in bands of 8 tile rows.
+  const int num_tiles = tiles_m * tiles_n;
+  int pid = blockIdx.x;
+  if ((num_tiles & 7) == 0) pid = (pid & 7) * (num_tiles >> 3) + (pid >> 3);
+  constexpr int kBand = 8;
+  const int band = pid / (kBand * tiles_n);
+  const int band_rows = min(kBand, tiles_m - band * kBand);
+  const int in_band = pid - band * kBand * tiles_n;
+  const int tm = band * kBand + in_band % band_rows, tn = in_band / band_rows;
+  const int64_t m0 = static_cast<int64_t>(tm) * TM, n0 = static_cast<int64_t>(tn) * TN;
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave >> 2, wn = wave & 3, l32 = lane & 31, lhi = lane >> 5;
+  const int arow = wm * 128 + l32, brow = wn * 64 + l32;
+
+  // Direct-load sources: wavefront w, instruction q fills the 8-row block 4w + q of a tile.
+  // Rows past the end of an operand are clamped; they only feed outputs that are never stored.
+  const char* ga[4];
+  const char* gb[4];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const int r = (wave * 4 + q) * 8 + (lane >> 3);
+    const int c = (lane & 7) ^ ((r >> 1) & 7);
+    ga[q] = reinterpret_cast<const char*>(A) + min<int64_t>(m0 + r, M - 1) * K * 2 + c * 16;
+    gb[q] = reinterpret_cast<const char*>(B) + min<int64_t>(n0 + r, N - 1) * K * 2 + c * 16;
+  }
+
+  float16v acc[4][2];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+  const int KT = static_cast<int>(K / TK);
+  auto issue = [&](int kt, int stage) {
+    char* base = lds + stage * kStageBytes + wave * 4096;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      __builtin_amdgcn_global_load_lds(ga[q] + static_cast<int64_t>(kt) * kRowBytes, (lds_ptr)(base + q * 1024), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds(gb[q] + static_cast<int64_t>(kt) * kRowBytes,
+                                       (lds_ptr)(base + kOperandBytes + q * 1024), 16, 0, 0);
+    }
+  };
+  issue(0, 0);
+  __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): the direct loads have landed in LDS
+  __syncthreads();
+
+  for (int kt = 0; kt < KT; ++kt) {
+    const char* cur = lds + (kt & 1) * kStageBytes;
+    if (kt + 1 < KT) issue(kt + 1, (kt + 1) & 1);
+    Frags f0, f1;
+    load_frags(f0, cur, cur + kOperandBytes, arow, brow, 0 + lhi);
+    load_frags(f1, cur, cur + kOperandBytes, arow, brow, 2 + lhi);
+    mma_step(acc, f0);
+    load_frags(f0, cur, cur + kOperandBytes, arow, brow, 4 + lhi);
+    mma_step(acc, f1);
+    load_frags(f1, cur, cur + kOperandBytes, arow, brow, 6 + lhi);
+    mma_step(acc, f0);
+    mma_step(acc, f1);
+    __builtin_amdgcn_s_waitcnt(0x0f70);
+    __syncthreads();
+  }
+
+  // Tensor-level decode scales on the finished sums (App. B.3, after Eq. 5).
+  const float out_scale = a_ts[0] * b_ts[0];
+  const int Mt = static_cast<int>(M - m0 < TM ? M - m0 : TM);
+  const int Nt = static_cast<int>(N - n0 < TN ? N - n0 : TN);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int m = wm * 128 + i * 32 + l32;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int n = wn * 64 + j * 32 + q * 8 + lhi * 4;
+        if (m < Mt && n < Nt) {
+          float4v v;
+#pragma unroll
+          for (int t = 0; t < 4; ++t) v[t] = acc[i][j][q * 4 + t] * out_scale;
+          if (kBf16Out) {
+            uint16_t* d = static_cast<uint16_t*>(Dv) + (m0 + m) * ldd + n0 + n;
+            uint2 o;
+            o.x = f32_to_bf16(v[0]) | (f32_to_bf16(v[1]) << 16);
+            o.y = f32_to_bf16(v[2]) | (f32_to_bf16(v[3]) << 16);
+            *reinterpret_cast<uint2*>(d) = o;
+          } else {
+            float* d = static_cast<float*>(Dv) + (m0 + m) * ldd + n0 + n;
+            *reinterpret_cast<float4v*>(d) = v;
+          }
+        }
+      }
+    }
+  }
+}
+
+}  // namespace
+
+size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t K) {
+  return static_cast<size_t>(M + N) * static_cast<size_t>(K) * 2;
+}
+
+bool gemm_two_pass_usable(const GemmArgs& g) {
+  return g.workspace && g.workspace_bytes >= gemm_workspace_bytes(g.a.outer, g.b.outer, g.K) && (g.K % TK) == 0 &&
+         reinterpret_cast<uintptr_t>(g.workspace) % 256 == 0 && reinterpret_cast<uintptr_t>(g.a.codes) % 16 == 0 &&
+         reinterpret_cast<uintptr_t>(g.b.codes) % 16 == 0 && reinterpret_cast<uintptr_t>(g.a.scales) % 2 == 0 &&
+         reinterpret_cast<uintptr_t>(g.b.scales) % 2 == 0;
+}
+
+hipError_t launch_gemm_two_pass(const GemmArgs& g, hipStream_t s) {
+  const int64_t M = g.a.outer, N = g.b.outer, K = g.K;
+  _Float16* a16 = static_cast<_Float16*>(g.workspace);
+  _Float16* b16 = a16 + M * K;
+  const int64_t na = M * K / 32, nb = N * K / 32;
+  hipLaunchKernelGGL(decode_f16_kernel, dim3(static_cast<unsigned>((na + 255) / 256)), dim3(256), 0, s, g.a.codes, g.a.scales, na, a16);
+  hipLaunchKernelGGL(decode_f16_kernel, dim3(static_cast<unsigned>((nb + 255) / 256)), dim3(256), 0, s, g.b.codes, g.b.scales, nb, b16);
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_f16_kernel<true>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, 2 * kStageBytes);
+    if (e == hipSuccess)
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_f16_kernel<false>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, 2 * kStageBytes);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  const int tiles_m = static_cast<int>((M + TM - 1) / TM), tiles_n = static_cast<int>((N + TN - 1) / TN);
+  const dim3 grid(static_cast<unsigned>(tiles_m * tiles_n));
+  if (g.out_bf16)
+    hipLaunchKernelGGL(gemm_f16_kernel<true>, grid, dim3(kThreads), 2 * kStageBytes, s, a16, b16, M, N, K, g.a.ts, g.b.ts, g.d, g.ldd, tiles_m, tiles_n);
+  else
+    hipLaunchKernelGGL(gemm_f16_kernel<false>, grid, dim3(kThreads), 2 * kStageBytes, s, a16, b16, M, N, K, g.a.ts, g.b.ts, g.d, g.ldd, tiles_m, tiles_n);
+  return hipGetLastError();
+}
+
+}  // namespace nvfp4

@@ -33,8 +33,13 @@ struct GemmArgs {
   void* d;
   int64_t ldd;
   bool out_bf16;
+  void* workspace;        // optional: room for both operands decoded to FP16
+  size_t workspace_bytes;
 };
 hipError_t launch_gemm(const GemmArgs& g, hipStream_t s);
+size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
+bool gemm_two_pass_usable(const GemmArgs& g);
+hipError_t launch_gemm_two_pass(const GemmArgs& g, hipStream_t s);
 
 struct DequantArgs {
   Operand q;

@@ -88,22 +88,29 @@ def test_quantize_rejects_bad_arguments(lib):
 def test_gemm_and_dequantize_reject_bad_arguments(lib):
     a, b = _desc(32, 64), _desc(64, 48)
     D = 0x40000
-    assert lib.nvfp4_gemm(None, ctypes.byref(b), 0, D, 0, 48, None) == -1
-    assert lib.nvfp4_gemm(ctypes.byref(a), ctypes.byref(b), 9, D, 0, 48, None) == -1
-    assert lib.nvfp4_gemm(ctypes.byref(a), ctypes.byref(b), 0, D, 5, 48, None) == -1
-    assert lib.nvfp4_gemm(ctypes.byref(a), ctypes.byref(b), 0, D, 0, 32, None) == -2     # ldd < N
-    assert lib.nvfp4_gemm(ctypes.byref(a), ctypes.byref(b), 1, D, 0, 64, None) == -4     # DGRAD: K 64 vs 48
+    assert lib.nvfp4_gemm(None, ctypes.byref(b), 0, D, 0, 48, None, 0, None) == -1
+    assert lib.nvfp4_gemm(ctypes.byref(a), ctypes.byref(b), 9, D, 0, 48, None, 0, None) == -1
+    assert lib.nvfp4_gemm(ctypes.byref(a), ctypes.byref(b), 0, D, 5, 48, None, 0, None) == -1
+    assert lib.nvfp4_gemm(ctypes.byref(a), ctypes.byref(b), 0, D, 0, 32, None, 0, None) == -2     # ldd < N
+    assert lib.nvfp4_gemm(ctypes.byref(a), ctypes.byref(b), 1, D, 0, 64, None, 0, None) == -4     # DGRAD: K 64 vs 48
     only_row = _desc(64, 48, mask=1)
-    assert lib.nvfp4_gemm(ctypes.byref(a), ctypes.byref(only_row), 0, D, 0, 48, None) == -3
+    assert lib.nvfp4_gemm(ctypes.byref(a), ctypes.byref(only_row), 0, D, 0, 48, None, 0, None) == -3
     # WGRAD operands must rotate alike
     p, q = _desc(64, 32, rht=1, seed=5), _desc(64, 48, rht=0)
-    assert lib.nvfp4_gemm(ctypes.byref(p), ctypes.byref(q), 2, D, 0, 48, None) == -4
+    assert lib.nvfp4_gemm(ctypes.byref(p), ctypes.byref(q), 2, D, 0, 48, None, 0, None) == -4
     q2 = _desc(64, 48, rht=1, seed=6)
-    assert lib.nvfp4_gemm(ctypes.byref(p), ctypes.byref(q2), 2, D, 0, 48, None) == -4
+    assert lib.nvfp4_gemm(ctypes.byref(p), ctypes.byref(q2), 2, D, 0, 48, None, 0, None) == -4
     assert lib.nvfp4_dequantize(ctypes.byref(a), 3, 0, D, 0, 64, None) == -1
     assert lib.nvfp4_dequantize(ctypes.byref(a), 0, 1, D, 0, 64, None) == -4            # undo_rht on a plain copy
     assert lib.nvfp4_dequantize(ctypes.byref(a), 0, 0, D, 0, 32, None) == -2
     assert lib.nvfp4_dequantize(ctypes.byref(only_row), 1, 0, D, 0, 64, None) == -3
+
+
+def test_gemm_workspace_query(lib):
+    assert nv.gemm_workspace_bytes(8192, 20480, 5120) == (8192 + 20480) * 5120 * 2
+    w = ctypes.c_size_t()
+    assert lib.nvfp4_gemm_workspace_bytes(8, 16, 16, ctypes.addressof(w)) == -2
+    assert lib.nvfp4_gemm_workspace_bytes(16, 16, 16, None) == -1
 
 
 def test_sign_mask_matches_the_oracle(lib):

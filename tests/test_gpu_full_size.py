@@ -46,6 +46,10 @@ def sample_entries(M, N, seed, rows=4, cols=4, tile=32):
     return np.concatenate(m_list), np.concatenate(n_list)
 
 
+def ws_for(m, n, k):
+    return torch.empty(nv.gemm_workspace_bytes(m, n, k), dtype=torch.uint8, device="cuda")
+
+
 def check_gemm_sample(d_gpu, a_ref, b_ref, seed):
     M, N = d_gpu.shape
     m, n = sample_entries(M, N, seed)
@@ -77,11 +81,14 @@ def test_config2_wgrad_rht_sr():
     rx = oracle.quantize(t["X"], oracle.COL, use_rht=True, rht_seed=RHT_SEED)
     assert_copy(qdy.col_codes, qdy.col_scales, qdy.col_ts, rdy, "dY col copy (RHT, SR)")
     assert_copy(qx.col_codes, qx.col_scales, qx.col_ts, rx, "X col copy (RHT, RNE)")
-    dw = nv.nvfp4_gemm(qdy, qx, nv.OP_WGRAD, nv.OUT_F32)
+    ws = ws_for(5120, 5120, 4096)
+    dw = nv.nvfp4_gemm(qdy, qx, nv.OP_WGRAD, nv.OUT_F32, workspace=ws)     # the route bench.py times
     assert dw.shape == (5120, 5120)
     check_gemm_sample(dw, rdy, rx, 22)
-    again = nv.nvfp4_gemm(qdy, qx, nv.OP_WGRAD, nv.OUT_F32)
+    again = nv.nvfp4_gemm(qdy, qx, nv.OP_WGRAD, nv.OUT_F32, workspace=ws)
     assert torch.equal(dw, again)
+    fused = nv.nvfp4_gemm(qdy, qx, nv.OP_WGRAD, nv.OUT_F32)                 # the fused route, no workspace
+    check_gemm_sample(fused, rdy, rx, 23)
 
 
 def test_config3_fprop(weight):
@@ -90,11 +97,15 @@ def test_config3_fprop(weight):
     qx = nv.nvfp4_quantize(to_dev(xb), nv.LAYOUT_ROW)
     rx = oracle.quantize(xb, oracle.ROW)
     assert_copy(qx.row_codes, qx.row_scales, qx.row_ts, rx, "X row copy")
-    y = nv.nvfp4_gemm(qx, qw, nv.OP_FPROP, nv.OUT_F32)
+    ws = ws_for(8192, 20480, 5120)
+    y = nv.nvfp4_gemm(qx, qw, nv.OP_FPROP, nv.OUT_F32, workspace=ws)
     assert y.shape == (8192, 20480)
     check_gemm_sample(y, rx, ref_col, 33)
-    y16 = nv.nvfp4_gemm(qx, qw, nv.OP_FPROP, nv.OUT_BF16)
+    y16 = nv.nvfp4_gemm(qx, qw, nv.OP_FPROP, nv.OUT_BF16, workspace=ws)
     assert torch.equal(y16, y.to(torch.bfloat16))          # bf16 output = RNE of the FP32 output
+    del y16
+    fused = nv.nvfp4_gemm(qx, qw, nv.OP_FPROP, nv.OUT_F32)
+    check_gemm_sample(fused, rx, ref_col, 34)
 
 
 def test_config4_dgrad(weight):
@@ -103,9 +114,11 @@ def test_config4_dgrad(weight):
     qdy = nv.nvfp4_quantize(to_dev(dyb), nv.LAYOUT_ROW, rounding=nv.ROUND_SR, sr_seed=SR_SEED)
     rdy = oracle.quantize(dyb, oracle.ROW, rounding=oracle.SR, sr_seed=SR_SEED)
     assert_copy(qdy.row_codes, qdy.row_scales, qdy.row_ts, rdy, "dY row copy (SR)")
-    dx = nv.nvfp4_gemm(qdy, qw, nv.OP_DGRAD, nv.OUT_F32)       # same quantized W, transposed, no requantization
-    assert dx.shape == (8192, 5120)
+    dx = nv.nvfp4_gemm(qdy, qw, nv.OP_DGRAD, nv.OUT_F32, workspace=ws_for(8192, 5120, 20480))
+    assert dx.shape == (8192, 5120)                            # same quantized W, transposed, no requantization
     check_gemm_sample(dx, rdy, ref_row, 44)
+    fused = nv.nvfp4_gemm(qdy, qw, nv.OP_DGRAD, nv.OUT_F32)
+    check_gemm_sample(fused, rdy, ref_row, 45)
 
 
 @pytest.mark.parametrize("name,mode", [
