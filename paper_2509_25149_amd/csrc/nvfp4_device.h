@@ -47,6 +47,21 @@ __device__ __forceinline__ float e4m3_decode(uint32_t code) {
   return __builtin_amdgcn_cvt_f32_fp8(static_cast<int>(code), 0);
 }
 
+// x / 6 with IEEE round-to-nearest, for finite x >= 0, mostly without the
+// hardware division sequence: one multiply by the rounded reciprocal, then one
+// Newton-style correction with an exact FMA residual.  That is bit-identical to
+// x / 6.0f for every x >= 2^-124 (below, the residual leaves the normal range);
+// if any lane of the wavefront is below, the whole wavefront divides for real.
+// Checked against IEEE division over all finite non-negative inputs by the
+// self-test.  The result feeds the stored block scale of App. B.2 Eq. 2.
+__device__ __forceinline__ float div_by_6(float x) {
+  if (__builtin_amdgcn_ballot_w64(x < 0x1p-124f) != 0) return x / 6.0f;
+  const float c = 0.16666667163372040f;           // RN(1/6)
+  const float q = x * c;
+  const float r = __builtin_fmaf(-q, 6.0f, x);     // exact residual x - 6q
+  return __builtin_fmaf(r, c, q);
+}
+
 // Stored block scale and the "real" block encode scale (App. B.2):
 //   code    = e4m3(amax_b / 6 * s_enc)
 //   s_enc_b = 1 / (fp32(code) * s_dec), 0 when the stored scale is 0.

@@ -44,19 +44,56 @@ __device__ __forceinline__ void load_patch(const uint16_t* __restrict__ x, int64
     p.raw[r] = *reinterpret_cast<const uint4*>(x + (row0 + r) * ld + col0);
 }
 
-// max |bf16| of a patch, as FP32 bits (also carries Inf/NaN through as the largest pattern)
+typedef unsigned short ushort2v __attribute__((ext_vector_type(2)));
+
+// max |bf16| of a patch, as FP32 bits (also carries Inf/NaN through as the largest
+// pattern): magnitudes of bf16 order like 15-bit integers, two per dword (v_pk_max_u16).
 __device__ __forceinline__ uint32_t patch_amax_bits(const Patch& p) {
-  uint32_t m = 0;
+  union U {
+    uint32_t u;
+    ushort2v v;
+  };
+  U m;
+  m.u = 0u;
 #pragma unroll
   for (int r = 0; r < 16; ++r) {
     const uint32_t w[4] = {p.raw[r].x, p.raw[r].y, p.raw[r].z, p.raw[r].w};
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
-      m = max(m, (w[t] << 16) & 0x7FFFFFFFu);
-      m = max(m, w[t] & 0x7FFF0000u);
+      U a;
+      a.u = w[t] & 0x7FFF7FFFu;
+      m.v = __builtin_elementwise_max(m.v, a.v);
     }
   }
-  return m;
+  return max(m.u & 0xFFFFu, m.u >> 16) << 16;
+}
+
+// The 16 values of column pair t (columns 2t, 2t+1) of a patch, sign diagonal applied:
+// lo[r], hi[r] = +-x[row r][2t], +-x[row r][2t+1] as FP32.  The sign of row r is the same for
+// every column, so it is one XOR on the packed bf16 word.
+__device__ __forceinline__ void signed_column_pair(const Patch& p, int t, uint32_t sign_mask, float lo[16], float hi[16]) {
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    const uint32_t w = (t == 0 ? p.raw[r].x : t == 1 ? p.raw[r].y : t == 2 ? p.raw[r].z : p.raw[r].w) ^
+                       (((sign_mask >> r) & 1u) * 0x80008000u);
+    lo[r] = bf16_lo(w);
+    hi[r] = bf16_hi(w);
+  }
+}
+
+// unnormalised 16-point Walsh-Hadamard butterfly, stages h = 1, 2, 4, 8 (App. C)
+__device__ __forceinline__ void butterfly16(float v[16]) {
+#pragma unroll
+  for (int h = 1; h < 16; h <<= 1) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      if ((i & h) == 0) {
+        const float a = v[i], b = v[i + h];
+        v[i] = a + b;
+        v[i + h] = a - b;
+      }
+    }
+  }
 }
 
 __device__ __forceinline__ uint32_t wave_max_u32(uint32_t m) {
@@ -77,6 +114,7 @@ __global__ __launch_bounds__(kThreads) void amax_kernel(const uint16_t* __restri
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int64_t col0 = static_cast<int64_t>(blockIdx.x) * kWaveCols + lane * 8;
   uint32_t m_raw = 0, m_rot = 0;
+  float f_rot = 0.0f;
 #pragma unroll 1
   for (int gi = 0; gi < kGroupsPerWave; ++gi) {
     const int64_t group = static_cast<int64_t>(blockIdx.y) * kGroupsPerBlock + wave * kGroupsPerWave + gi;
@@ -85,20 +123,22 @@ __global__ __launch_bounds__(kThreads) void amax_kernel(const uint16_t* __restri
       load_patch(x, ld, group * 16, col0, p);
       if (kRaw) m_raw = max(m_raw, patch_amax_bits(p));
       if (kRht) {
+        // The 1/4 normalisation is applied once to the maximum: rounding is monotone, so
+        // max_i fl(0.25 v_i) = fl(0.25 max_i v_i).
 #pragma unroll
-        for (int c = 0; c < 8; ++c) {
-          float v[16];
+        for (int t = 0; t < 4; ++t) {
+          float lo[16], hi[16];
+          signed_column_pair(p, t, sign_mask, lo, hi);
+          butterfly16(lo);
+          butterfly16(hi);
 #pragma unroll
-          for (int r = 0; r < 16; ++r) v[r] = patch_elem(p.raw[r], c);
-          rht16(v, sign_mask);
-#pragma unroll
-          for (int r = 0; r < 16; ++r) m_rot = max(m_rot, __float_as_uint(v[r]) & 0x7FFFFFFFu);
+          for (int r = 0; r < 16; ++r) f_rot = fmaxf(fmaxf(f_rot, fabsf(lo[r])), fabsf(hi[r]));
         }
       }
     }
   }
   if (kRaw) m_raw = wave_max_u32(m_raw);
-  if (kRht) m_rot = wave_max_u32(m_rot);
+  if (kRht) m_rot = wave_max_u32(__float_as_uint(0.25f * f_rot));
   if (lane == 0) {
     red[0][wave] = m_raw;
     red[1][wave] = m_rot;
@@ -186,7 +226,7 @@ constexpr int kColScalesBytes = 8 * kGroupsPerBlock * 64;            // 4096
 constexpr int kRowScalesBytes = 16 * kGroupsPerBlock * 32;           // 4096
 
 template <bool kRow, bool kCol, bool kRht, bool kSR, bool k2D>
-__global__ __launch_bounds__(kThreads) void cast_kernel(
+__global__ __launch_bounds__(kThreads, 2) void cast_kernel(
     const uint16_t* __restrict__ x, int64_t rows, int64_t cols, int64_t ld,
     const uint32_t* __restrict__ ws, uint32_t sign_mask, uint32_t key0, uint32_t key1,
     uint8_t* __restrict__ row_codes, uint8_t* __restrict__ row_scales, float* __restrict__ row_ts,
@@ -245,7 +285,7 @@ __global__ __launch_bounds__(kThreads) void cast_kernel(
     if (k2D) {
       uint32_t m = patch_amax_bits(p);
       m = max(m, static_cast<uint32_t>(__shfl_xor(static_cast<int>(m), 1, 64)));
-      tile_code = e4m3_encode((__uint_as_float(m) / 6.0f) * s_enc_r);   // Eq. 2-3
+      tile_code = e4m3_encode(div_by_6(__uint_as_float(m)) * s_enc_r);   // Eq. 2-3
       s_enc_tile = lut_row[tile_code];
     }
 
@@ -266,7 +306,7 @@ __global__ __launch_bounds__(kThreads) void cast_kernel(
 #pragma unroll
           for (int c = 0; c < 8; ++c) m = fmaxf(m, fabsf(v[c]));
           m = fmaxf(m, __shfl_xor(m, 1, 64));
-          code = e4m3_encode((m / 6.0f) * s_enc_r);                     // Eq. 2-3
+          code = e4m3_encode(div_by_6(m) * s_enc_r);                        // Eq. 2-3
           s_enc_b = lut_row[code];
         }
 #pragma unroll
@@ -278,12 +318,7 @@ __global__ __launch_bounds__(kThreads) void cast_kernel(
     }
 
     if (kCol) {
-#pragma unroll
-      for (int c = 0; c < 8; ++c) {
-        float v[16];
-#pragma unroll
-        for (int r = 0; r < 16; ++r) v[r] = patch_elem(p.raw[r], c);
-        if (kRht) rht16(v, sign_mask);
+      auto emit_column = [&](float (&v)[16], int c) {
         float s_enc_b;
         uint32_t code;
         if (k2D) {
@@ -292,8 +327,8 @@ __global__ __launch_bounds__(kThreads) void cast_kernel(
         } else {
           float m = 0.0f;
 #pragma unroll
-          for (int r = 0; r < 16; ++r) m = fmaxf(m, fabsf(v[r]));
-          code = e4m3_encode((m / 6.0f) * s_enc_c);
+          for (int r = 0; r < 16; r += 2) m = fmaxf(fmaxf(m, fabsf(v[r])), fabsf(v[r + 1]));
+          code = e4m3_encode(div_by_6(m) * s_enc_c);
           s_enc_b = lut_col[code];
         }
 #pragma unroll
@@ -303,6 +338,22 @@ __global__ __launch_bounds__(kThreads) void cast_kernel(
         out.y = encode8_col<kSR>(v + 8, rnd, 8, c);
         *reinterpret_cast<uint2*>(st_col_codes + ((c * kGroupsPerBlock + gl) * kColSlot + lane) * 8) = out;
         st_col_scales[(c * kGroupsPerBlock + gl) * 64 + lane] = static_cast<uint8_t>(code);
+      };
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        float lo[16], hi[16];
+        signed_column_pair(p, t, kRht ? sign_mask : 0u, lo, hi);
+        if (kRht) {
+          butterfly16(lo);
+          butterfly16(hi);
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            lo[r] *= 0.25f;
+            hi[r] *= 0.25f;
+          }
+        }
+        emit_column(lo, 2 * t);
+        emit_column(hi, 2 * t + 1);
       }
     }
   }

@@ -96,6 +96,16 @@ __global__ __launch_bounds__(256) void selftest_e4m3_kernel(unsigned long long* 
   if (local) atomicAdd(bad, local);
 }
 
+__global__ __launch_bounds__(256) void selftest_div6_kernel(unsigned long long* bad) {
+  unsigned long long local = 0;
+  const uint64_t stride = static_cast<uint64_t>(gridDim.x) * blockDim.x;
+  for (uint64_t w = static_cast<uint64_t>(blockIdx.x) * blockDim.x + threadIdx.x; w < 0x7F800000ull; w += stride) {
+    const float x = __uint_as_float(static_cast<uint32_t>(w));
+    local += __float_as_uint(div_by_6(x)) != __float_as_uint(x / 6.0f);
+  }
+  if (local) atomicAdd(bad, local);
+}
+
 }  // namespace
 
 hipError_t run_selftest(uint64_t* mismatches_dev, hipStream_t s) {
@@ -103,6 +113,7 @@ hipError_t run_selftest(uint64_t* mismatches_dev, hipStream_t s) {
   hipLaunchKernelGGL(selftest_rne_kernel, dim3(4096), dim3(256), 0, s, dev + 0);
   hipLaunchKernelGGL(selftest_sr_kernel, dim3(0x40E1u * 5u), dim3(256), 0, s, dev + 1);
   hipLaunchKernelGGL(selftest_e4m3_kernel, dim3(4096), dim3(256), 0, s, dev + 2);
+  hipLaunchKernelGGL(selftest_div6_kernel, dim3(4096), dim3(256), 0, s, dev + 3);
   return hipGetLastError();
 }
 
