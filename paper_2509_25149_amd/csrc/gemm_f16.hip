@@ -77,22 +77,25 @@ constexpr int kStageBytes = 2 * kOperandBytes;  // 64 KiB
 
 __device__ __forceinline__ int swz(int row, int chunk) { return row * kRowBytes + ((chunk ^ ((row >> 1) & 7)) << 4); }
 
+template <int kFragsA>
 struct Frags {
-  half8v a[4], b[2];
+  half8v a[kFragsA], b[2];
 };
 
-__device__ __forceinline__ void load_frags(Frags& f, const char* at, const char* bt, int arow, int brow, int chunk) {
+template <int kFragsA>
+__device__ __forceinline__ void load_frags(Frags<kFragsA>& f, const char* at, const char* bt, int arow, int brow, int chunk) {
 #pragma unroll
-  for (int i = 0; i < 4; ++i) f.a[i] = *reinterpret_cast<const half8v*>(at + swz(arow + i * 32, chunk));
+  for (int i = 0; i < kFragsA; ++i) f.a[i] = *reinterpret_cast<const half8v*>(at + swz(arow + i * 32, chunk));
 #pragma unroll
   for (int j = 0; j < 2; ++j) f.b[j] = *reinterpret_cast<const half8v*>(bt + swz(brow + j * 32, chunk));
 }
 
 // The MFMA's M index is the B row (n), its N index the A row (m): a lane ends up
 // with 4 consecutive n of one m, which makes the output stores 64/128-bit.
-__device__ __forceinline__ void mma_step(float16v (&acc)[4][2], const Frags& f) {
+template <int kFragsA>
+__device__ __forceinline__ void mma_step(float16v (&acc)[kFragsA][2], const Frags<kFragsA>& f) {
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int i = 0; i < kFragsA; ++i)
 #pragma unroll
     for (int j = 0; j < 2; ++j)
       acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(f.b[j], f.a[i], acc[i][j], 0, 0, 0);
@@ -100,45 +103,76 @@ __device__ __forceinline__ void mma_step(float16v (&acc)[4][2], const Frags& f) 
 
 typedef __attribute__((address_space(3))) void* lds_ptr;
 
-template <bool kBf16Out>
+// 64 lanes x 16 bytes from global memory straight into 1 KiB of consecutive LDS starting at the
+// wave-uniform address `lds_dst` (global_load_lds_dwordx4).  The builtin only exists in the device
+// pass; hiding it from the host pass keeps the host stubs of the kernel templates below emitted.
+__device__ __forceinline__ void load_1k_to_lds(const char* src, char* lds_dst) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  __builtin_amdgcn_global_load_lds(src, (lds_ptr)lds_dst, 16, 0, 0);
+#else
+  (void)src;
+  (void)lds_dst;
+#endif
+}
+
+// kTileM = 256: the regular tile.  kTileM = 128: half tiles (the 256-row tile split in two
+// along m), used for the last, partial round of workgroups so that it occupies all CUs for
+// about half a tile time instead of half the CUs for a full one.
+// Tiles [tile_begin, tile_begin + count) of the 256x256 tiling are covered; with half tiles
+// every tile is covered by two workgroups.
+template <bool kBf16Out, int kTileM>
 __global__ __launch_bounds__(kThreads) void gemm_f16_kernel(const _Float16* __restrict__ A, const _Float16* __restrict__ B,
                                                             int64_t M, int64_t N, int64_t K, const float* __restrict__ a_ts,
                                                             const float* __restrict__ b_ts, void* __restrict__ Dv,
-                                                            int64_t ldd, int tiles_m, int tiles_n) {
+                                                            int64_t ldd, int tiles_m, int tiles_n, int tile_begin,
+                                                            int tile_count) {
   extern __shared__ __attribute__((aligned(16))) char lds[];
+  constexpr int kFragsA = kTileM / 64;               // A fragments per wavefront (wave tile kTileM/2 x 64)
+  constexpr int kABytes = kTileM * kRowBytes;
+  constexpr int kStage = kABytes + kOperandBytes;
+  constexpr int kLoadsA = kTileM / 64;               // direct-load instructions per wavefront for the A tile
 
   // Workgroup -> tile: consecutive ids go to different XCDs (round robin over 8, one L2 each);
   // give every XCD a contiguous range of tiles, walked in bands of 8 tile rows.
-  const int num_tiles = tiles_m * tiles_n;
-  int pid = blockIdx.x;
-  if ((num_tiles & 7) == 0) pid = (pid & 7) * (num_tiles >> 3) + (pid >> 3);
+  int wg = blockIdx.x, half = 0;
+  if (kTileM == 128) {
+    half = wg & 1;
+    wg >>= 1;
+  }
+  if ((tile_count & 7) == 0) wg = (wg & 7) * (tile_count >> 3) + (wg >> 3);
+  const int pid = tile_begin + wg;
   constexpr int kBand = 8;
   const int band = pid / (kBand * tiles_n);
   const int band_rows = min(kBand, tiles_m - band * kBand);
   const int in_band = pid - band * kBand * tiles_n;
   const int tm = band * kBand + in_band % band_rows, tn = in_band / band_rows;
-  const int64_t m0 = static_cast<int64_t>(tm) * TM, n0 = static_cast<int64_t>(tn) * TN;
+  const int64_t m0 = static_cast<int64_t>(tm) * TM + half * 128, n0 = static_cast<int64_t>(tn) * TN;
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave >> 2, wn = wave & 3, l32 = lane & 31, lhi = lane >> 5;
-  const int arow = wm * 128 + l32, brow = wn * 64 + l32;
+  const int arow = wm * (kTileM / 2) + l32, brow = wn * 64 + l32;
 
-  // Direct-load sources: wavefront w, instruction q fills the 8-row block 4w + q of a tile.
+  // Direct-load sources: one instruction fills an 8-row block of a tile.
   // Rows past the end of an operand are clamped; they only feed outputs that are never stored.
-  const char* ga[4];
+  const char* ga[kLoadsA];
   const char* gb[4];
+#pragma unroll
+  for (int q = 0; q < kLoadsA; ++q) {
+    const int r = (wave * kLoadsA + q) * 8 + (lane >> 3);
+    const int c = (lane & 7) ^ ((r >> 1) & 7);
+    ga[q] = reinterpret_cast<const char*>(A) + min<int64_t>(m0 + r, M - 1) * K * 2 + c * 16;
+  }
 #pragma unroll
   for (int q = 0; q < 4; ++q) {
     const int r = (wave * 4 + q) * 8 + (lane >> 3);
     const int c = (lane & 7) ^ ((r >> 1) & 7);
-    ga[q] = reinterpret_cast<const char*>(A) + min<int64_t>(m0 + r, M - 1) * K * 2 + c * 16;
     gb[q] = reinterpret_cast<const char*>(B) + min<int64_t>(n0 + r, N - 1) * K * 2 + c * 16;
   }
 
-  float16v acc[4][2];
+  float16v acc[kFragsA][2];
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int i = 0; i < kFragsA; ++i)
 #pragma unroll
     for (int j = 0; j < 2; ++j)
 #pragma unroll
@@ -146,28 +180,28 @@ __global__ __launch_bounds__(kThreads) void gemm_f16_kernel(const _Float16* __re
 
   const int KT = static_cast<int>(K / TK);
   auto issue = [&](int kt, int stage) {
-    char* base = lds + stage * kStageBytes + wave * 4096;
+    char* base = lds + stage * kStage;
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      __builtin_amdgcn_global_load_lds(ga[q] + static_cast<int64_t>(kt) * kRowBytes, (lds_ptr)(base + q * 1024), 16, 0, 0);
-      __builtin_amdgcn_global_load_lds(gb[q] + static_cast<int64_t>(kt) * kRowBytes,
-                                       (lds_ptr)(base + kOperandBytes + q * 1024), 16, 0, 0);
-    }
+    for (int q = 0; q < kLoadsA; ++q)
+      load_1k_to_lds(ga[q] + static_cast<int64_t>(kt) * kRowBytes, base + (wave * kLoadsA + q) * 1024);
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+      load_1k_to_lds(gb[q] + static_cast<int64_t>(kt) * kRowBytes, base + kABytes + (wave * 4 + q) * 1024);
   };
   issue(0, 0);
   __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): the direct loads have landed in LDS
   __syncthreads();
 
   for (int kt = 0; kt < KT; ++kt) {
-    const char* cur = lds + (kt & 1) * kStageBytes;
+    const char* cur = lds + (kt & 1) * kStage;
     if (kt + 1 < KT) issue(kt + 1, (kt + 1) & 1);
-    Frags f0, f1;
-    load_frags(f0, cur, cur + kOperandBytes, arow, brow, 0 + lhi);
-    load_frags(f1, cur, cur + kOperandBytes, arow, brow, 2 + lhi);
+    Frags<kFragsA> f0, f1;
+    load_frags(f0, cur, cur + kABytes, arow, brow, 0 + lhi);
+    load_frags(f1, cur, cur + kABytes, arow, brow, 2 + lhi);
     mma_step(acc, f0);
-    load_frags(f0, cur, cur + kOperandBytes, arow, brow, 4 + lhi);
+    load_frags(f0, cur, cur + kABytes, arow, brow, 4 + lhi);
     mma_step(acc, f1);
-    load_frags(f1, cur, cur + kOperandBytes, arow, brow, 6 + lhi);
+    load_frags(f1, cur, cur + kABytes, arow, brow, 6 + lhi);
     mma_step(acc, f0);
     mma_step(acc, f1);
     __builtin_amdgcn_s_waitcnt(0x0f70);
@@ -176,11 +210,11 @@ __global__ __launch_bounds__(kThreads) void gemm_f16_kernel(const _Float16* __re
 
   // Tensor-level decode scales on the finished sums (App. B.3, after Eq. 5).
   const float out_scale = a_ts[0] * b_ts[0];
-  const int Mt = static_cast<int>(M - m0 < TM ? M - m0 : TM);
+  const int Mt = static_cast<int>(M - m0 < kTileM ? M - m0 : kTileM);
   const int Nt = static_cast<int>(N - n0 < TN ? N - n0 : TN);
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int m = wm * 128 + i * 32 + l32;
+  for (int i = 0; i < kFragsA; ++i) {
+    const int m = wm * (kTileM / 2) + i * 32 + l32;
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
 #pragma unroll
@@ -219,6 +253,33 @@ bool gemm_two_pass_usable(const GemmArgs& g) {
          reinterpret_cast<uintptr_t>(g.b.scales) % 2 == 0;
 }
 
+#define NVFP4_LAUNCH_F16(BF16, TILEM)                                                                              \
+  do {                                                                                                            \
+    constexpr int lds_bytes = 2 * ((TILEM) * kRowBytes + kOperandBytes);                                          \
+    static bool attr_set = false;                                                                                 \
+    if (!attr_set) {                                                                                              \
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_f16_kernel<BF16, TILEM>),            \
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);                  \
+      if (e != hipSuccess) return e;                                                                              \
+      attr_set = true;                                                                                            \
+    }                                                                                                             \
+    hipLaunchKernelGGL((gemm_f16_kernel<BF16, TILEM>), dim3(wgs), dim3(kThreads), lds_bytes, s, a16, b16,         \
+                       g.a.outer, g.b.outer, g.K, g.a.ts, g.b.ts, g.d, g.ldd, tiles_m, tiles_n, tile_begin,       \
+                       tile_count);                                                                               \
+  } while (0)
+
+static hipError_t launch_f16(bool bf16_out, int tile_m, const _Float16* a16, const _Float16* b16, const GemmArgs& g,
+                             int tiles_m, int tiles_n, int tile_begin, int tile_count, hipStream_t s) {
+  const unsigned wgs = static_cast<unsigned>(tile_count) * (tile_m == 128 ? 2u : 1u);
+  if (tile_m == 256) {
+    if (bf16_out) NVFP4_LAUNCH_F16(true, 256); else NVFP4_LAUNCH_F16(false, 256);
+  } else {
+    if (bf16_out) NVFP4_LAUNCH_F16(true, 128); else NVFP4_LAUNCH_F16(false, 128);
+  }
+  return hipGetLastError();
+}
+#undef NVFP4_LAUNCH_F16
+
 hipError_t launch_gemm_two_pass(const GemmArgs& g, hipStream_t s) {
   const int64_t M = g.a.outer, N = g.b.outer, K = g.K;
   _Float16* a16 = static_cast<_Float16*>(g.workspace);
@@ -226,23 +287,19 @@ hipError_t launch_gemm_two_pass(const GemmArgs& g, hipStream_t s) {
   const int64_t na = M * K / 32, nb = N * K / 32;
   hipLaunchKernelGGL(decode_f16_kernel, dim3(static_cast<unsigned>((na + 255) / 256)), dim3(256), 0, s, g.a.codes, g.a.scales, na, a16);
   hipLaunchKernelGGL(decode_f16_kernel, dim3(static_cast<unsigned>((nb + 255) / 256)), dim3(256), 0, s, g.b.codes, g.b.scales, nb, b16);
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_f16_kernel<true>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, 2 * kStageBytes);
-    if (e == hipSuccess)
-      e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_f16_kernel<false>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, 2 * kStageBytes);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
   const int tiles_m = static_cast<int>((M + TM - 1) / TM), tiles_n = static_cast<int>((N + TN - 1) / TN);
-  const dim3 grid(static_cast<unsigned>(tiles_m * tiles_n));
-  if (g.out_bf16)
-    hipLaunchKernelGGL(gemm_f16_kernel<true>, grid, dim3(kThreads), 2 * kStageBytes, s, a16, b16, M, N, K, g.a.ts, g.b.ts, g.d, g.ldd, tiles_m, tiles_n);
-  else
-    hipLaunchKernelGGL(gemm_f16_kernel<false>, grid, dim3(kThreads), 2 * kStageBytes, s, a16, b16, M, N, K, g.a.ts, g.b.ts, g.d, g.ldd, tiles_m, tiles_n);
-  return hipGetLastError();
+  const int tiles = tiles_m * tiles_n;
+  // One 256x256 tile keeps one CU busy (its LDS fits one workgroup).  Whole rounds of kCUs tiles
+  // run as they are; a last partial round of at most kCUs / 2 tiles is split into half tiles so
+  // that it fills the chip.
+  constexpr int kCUs = 256;
+  int tail = tiles % kCUs;
+  if (tail > kCUs / 2 || tiles < kCUs) tail = 0;
+  const int full = tiles - tail;
+  hipError_t e = hipSuccess;
+  if (full > 0) e = launch_f16(g.out_bf16, 256, a16, b16, g, tiles_m, tiles_n, 0, full, s);
+  if (e == hipSuccess && tail > 0) e = launch_f16(g.out_bf16, 128, a16, b16, g, tiles_m, tiles_n, full, tail, s);
+  return e;
 }
 
 }  // namespace nvfp4
