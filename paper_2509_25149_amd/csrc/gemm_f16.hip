@@ -44,21 +44,29 @@ __device__ __forceinline__ half2v scale_h2(uint32_t e4m3_byte) {
   return r;
 }
 
-// One thread per 32 elements (two 16-blocks): 16 bytes of codes, 2 scale bytes
-// in, 64 bytes of FP16 out.
-__global__ __launch_bounds__(256) void decode_f16_kernel(const uint8_t* __restrict__ codes,
-                                                         const uint8_t* __restrict__ scales, int64_t n32,
-                                                         _Float16* __restrict__ out) {
-  const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
-  if (i >= n32) return;
-  const uint4 c = reinterpret_cast<const uint4*>(codes)[i];
-  const uint32_t s = reinterpret_cast<const uint16_t*>(scales)[i];
-  const half2v h0 = scale_h2(s & 0xFFu), h1 = scale_h2(s >> 8);
-  uint4* dst = reinterpret_cast<uint4*>(out) + i * 4;
-  dst[0] = dec8(c.x, h0);
-  dst[1] = dec8(c.y, h0);
-  dst[2] = dec8(c.z, h1);
-  dst[3] = dec8(c.w, h1);
+// One thread per 8 elements (one dword of codes -> 16 bytes of FP16): consecutive lanes read
+// consecutive dwords and write consecutive 16-byte pieces, so every load and store instruction of
+// a wavefront covers one contiguous span.  Both operands are decoded by one launch.
+__global__ __launch_bounds__(256) void decode_f16_kernel(const uint8_t* __restrict__ a_codes,
+                                                         const uint8_t* __restrict__ a_scales, int64_t a_n8,
+                                                         _Float16* __restrict__ a_out,
+                                                         const uint8_t* __restrict__ b_codes,
+                                                         const uint8_t* __restrict__ b_scales, int64_t b_n8,
+                                                         _Float16* __restrict__ b_out) {
+  int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+  const uint8_t* codes = a_codes;
+  const uint8_t* scales = a_scales;
+  _Float16* out = a_out;
+  if (i >= a_n8) {
+    i -= a_n8;
+    if (i >= b_n8) return;
+    codes = b_codes;
+    scales = b_scales;
+    out = b_out;
+  }
+  const uint32_t c = reinterpret_cast<const uint32_t*>(codes)[i];
+  const half2v h = scale_h2(scales[i >> 1]);
+  reinterpret_cast<uint4*>(out)[i] = dec8(c, h);
 }
 
 // ---------------------------------------------------------------- pass 2: FP16 GEMM
@@ -284,9 +292,9 @@ hipError_t launch_gemm_two_pass(const GemmArgs& g, hipStream_t s) {
   const int64_t M = g.a.outer, N = g.b.outer, K = g.K;
   _Float16* a16 = static_cast<_Float16*>(g.workspace);
   _Float16* b16 = a16 + M * K;
-  const int64_t na = M * K / 32, nb = N * K / 32;
-  hipLaunchKernelGGL(decode_f16_kernel, dim3(static_cast<unsigned>((na + 255) / 256)), dim3(256), 0, s, g.a.codes, g.a.scales, na, a16);
-  hipLaunchKernelGGL(decode_f16_kernel, dim3(static_cast<unsigned>((nb + 255) / 256)), dim3(256), 0, s, g.b.codes, g.b.scales, nb, b16);
+  const int64_t na = M * K / 8, nb = N * K / 8;   // a_n8 is a multiple of 256 only if M*K is a multiple of 2048; the kernel does not need it
+  hipLaunchKernelGGL(decode_f16_kernel, dim3(static_cast<unsigned>((na + nb + 255) / 256)), dim3(256), 0, s, g.a.codes,
+                     g.a.scales, na, a16, g.b.codes, g.b.scales, nb, b16);
   const int tiles_m = static_cast<int>((M + TM - 1) / TM), tiles_n = static_cast<int>((N + TN - 1) / TN);
   const int tiles = tiles_m * tiles_n;
   // One 256x256 tile keeps one CU busy (its LDS fits one workgroup).  Whole rounds of kCUs tiles
