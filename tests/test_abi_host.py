@@ -75,6 +75,8 @@ def test_quantize_rejects_bad_arguments(lib):
     assert lib.nvfp4_quantize(X, 16, 16, 16, 3, 16, 0, 1, 0, 0, *ok_tail) == -1     # rotation with 16x16 blocks
     assert lib.nvfp4_quantize(X, 16, 16, 16, 1, 1, 0, 1, 0, 0, *ok_tail) == -1      # rotation without a col copy
     assert lib.nvfp4_quantize(X, 24, 16, 16, 1, 1, 0, 0, 0, 0, *ok_tail) == -2
+    assert lib.nvfp4_quantize(X, 0, 16, 16, 1, 1, 0, 0, 0, 0, *ok_tail) == -2       # empty tensors are rejected
+    assert lib.nvfp4_quantize(X, 16, 0, 16, 1, 1, 0, 0, 0, 0, *ok_tail) == -2
     assert lib.nvfp4_quantize(X, 16, 40, 40, 1, 1, 0, 0, 0, 0, *ok_tail) == -2
     assert lib.nvfp4_quantize(X, 16, 32, 16, 1, 1, 0, 0, 0, 0, *ok_tail) == -2      # ld < cols
     assert lib.nvfp4_quantize(X + 2, 16, 16, 16, 1, 1, 0, 0, 0, 0, *ok_tail) == -1  # misaligned input

@@ -139,3 +139,37 @@ def test_config5_quantize_sweep(name, mode):
     del row
     col = oracle.quantize(xb, oracle.COL, ob, orr, rht, RHT_SEED, SR_SEED)
     assert_copy(q.col_codes, q.col_scales, q.col_ts, col, f"{name} col copy")
+
+
+def test_indexing_beyond_2_31_elements():
+    """A tensor of 2^31 + 2^27 elements (4.5 GB of bf16): the small tensor it is tiled from fixes the expected
+    bytes, since tiling by whole 16-row groups changes neither the amax nor any block (RNE)."""
+    base_rows, cols, reps = 128, 16384, 1088          # 128*1088 = 139264 rows; 139264*16384 = 2^31 + 2^27
+    xb = synth.normal_with_outliers(base_rows, cols, 1.0, 777, frac=0.01)
+    small = nv.nvfp4_quantize(to_dev(xb), nv.LAYOUT_ROW | nv.LAYOUT_COL, rht_on_col=True, rht_seed=RHT_SEED)
+    big_x = to_dev(xb).repeat(reps, 1)
+    assert big_x.numel() > 2 ** 31
+    big = nv.nvfp4_quantize(big_x, nv.LAYOUT_ROW | nv.LAYOUT_COL, rht_on_col=True, rht_seed=RHT_SEED)
+    torch.cuda.synchronize()
+    del big_x
+    assert torch.equal(big.row_ts, small.row_ts) and torch.equal(big.col_ts, small.col_ts)
+    assert torch.equal(big.row_codes.view(reps, base_rows, cols // 2), small.row_codes.expand(reps, -1, -1))
+    assert torch.equal(big.row_scales.view(reps, base_rows, cols // 16), small.row_scales.expand(reps, -1, -1))
+    assert torch.equal(big.col_codes.view(cols, reps, base_rows // 2), small.col_codes.unsqueeze(1).expand(-1, reps, -1))
+    assert torch.equal(big.col_scales.view(cols, reps, base_rows // 16), small.col_scales.unsqueeze(1).expand(-1, reps, -1))
+    # decode goes through the same 64-bit offsets
+    d_small = nv.nvfp4_dequantize(small, nv.COPY_ROW, False, nv.OUT_BF16)
+    d_big = nv.nvfp4_dequantize(big, nv.COPY_ROW, False, nv.OUT_BF16)
+    assert torch.equal(d_big.view(reps, base_rows, cols), d_small.expand(reps, -1, -1))
+    del d_big
+    # GEMM with M = 139264 rows of A (2^31 + 2^27 elements): every block of 128 output rows repeats
+    wq = nv.nvfp4_quantize(to_dev(synth.normal(cols, 256, 0.02, 778)), nv.LAYOUT_COL, nv.BLOCK_16x16)
+    y_small = nv.nvfp4_gemm(small, wq, nv.OP_FPROP, nv.OUT_F32)
+    ws = ws_for(base_rows * reps, 256, cols)
+    y_big = nv.nvfp4_gemm(big, wq, nv.OP_FPROP, nv.OUT_F32, workspace=ws)
+    torch.cuda.synchronize()
+    err = (y_big.view(reps, base_rows, 256) - y_small).double().norm() / (y_small.double().norm() * reps ** 0.5)
+    assert float(err) <= 2e-6      # same products, FP32 summation order may differ between tile positions
+    y_big_fused = nv.nvfp4_gemm(big, wq, nv.OP_FPROP, nv.OUT_F32)
+    err = (y_big_fused.view(reps, base_rows, 256) - y_small).double().norm() / (y_small.double().norm() * reps ** 0.5)
+    assert float(err) <= 2e-6
