@@ -198,8 +198,8 @@ def main() -> int:
                                     "W_5120x20480_2d": {"ms": q_avg[1], "GBps": q_gbps[1]},
                                     "dY_8192x20480_sr_rht": {"ms": q_avg[2], "GBps": q_gbps[2]}},
                      "note": "call time = clear + amax pass + cast pass; bytes = bf16 read once + both copies written"},
-        "roofline": {"kernel": "one nvfp4_gemm call = decode_f16_kernel (A, B) + gemm_f16_kernel (256x256 tiles, plus the "
-                               "half-tile launch for a partial last round)",
+        "roofline": {"kernel": "one nvfp4_gemm call = decode_f16_kernel (A, B) + gemm_f16_kernel (256x256 tiles, plus a "
+                               "split-K launch for a partial last round of tiles)",
                      "bound": "mfma", "achieved": gemm_tflops, "peak": PEAK_MFMA_F16_TFLOPS,
                      "unit": "TFLOP/s", "frac": gemm_tflops / PEAK_MFMA_F16_TFLOPS,
                      "traffic": MEASURED_TRAFFIC_BYTES["gemm_call"],

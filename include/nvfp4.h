@@ -145,7 +145,10 @@ int nvfp4_quantize(const void* x, int64_t rows, int64_t cols, int64_t ld, int la
 int nvfp4_gemm(const nvfp4_qtensor* a, const nvfp4_qtensor* b, int op, void* d, int out_dtype,
                int64_t ldd, void* workspace, size_t workspace_bytes, nvfp4_stream_t stream);
 
-/* Scratch bytes that let nvfp4_gemm take its faster two-pass route: (M + N) * K * 2 (host pointer out). */
+/* Scratch bytes that let nvfp4_gemm take its faster two-pass route (host pointer out):
+ * (M + N) * K * 2 for the FP16 operands, 1 KiB of counters, and up to 64 MiB of FP32 partial
+ * tiles when the last round of 256x256 output tiles is partial and gets split along K.
+ * Two calls that overlap in time on one GPU need a workspace each. */
 int nvfp4_gemm_workspace_bytes(int64_t m, int64_t n, int64_t k, size_t* workspace_bytes);
 
 /*

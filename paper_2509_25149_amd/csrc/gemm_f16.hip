@@ -52,7 +52,10 @@ __global__ __launch_bounds__(256) void decode_f16_kernel(const uint8_t* __restri
                                                          _Float16* __restrict__ a_out,
                                                          const uint8_t* __restrict__ b_codes,
                                                          const uint8_t* __restrict__ b_scales, int64_t b_n8,
-                                                         _Float16* __restrict__ b_out) {
+                                                         _Float16* __restrict__ b_out,
+                                                         unsigned int* __restrict__ tickets) {
+  // The split-K tickets of the GEMM launches that follow start at zero (256 of them at most).
+  if (blockIdx.x == 0 && tickets) tickets[threadIdx.x] = 0u;
   int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
   const uint8_t* codes = a_codes;
   const uint8_t* scales = a_scales;
@@ -123,43 +126,49 @@ __device__ __forceinline__ void load_1k_to_lds(const char* src, char* lds_dst) {
 #endif
 }
 
-// kTileM = 256: the regular tile.  kTileM = 128: half tiles (the 256-row tile split in two
-// along m), used for the last, partial round of workgroups so that it occupies all CUs for
-// about half a tile time instead of half the CUs for a full one.
-// Tiles [tile_begin, tile_begin + count) of the 256x256 tiling are covered; with half tiles
-// every tile is covered by two workgroups.
-template <bool kBf16Out, int kTileM>
+// Tiles [tile_begin, tile_begin + count) of the 256x256 tiling are covered.
+//
+// k_splits > 1 fills the chip during a last, partial round of tiles: a tile is shared by
+// k_splits workgroups, each summing one contiguous range of K steps.  Every one of
+// them stores its FP32 partial tile to `partials`, then takes a ticket from the tile's counter
+// (zeroed by the decode pass of the same call); the workgroup that draws the last ticket adds the
+// partials in split order - a fixed order, so the result does not depend on which workgroup
+// finishes last - and stores the tile.  Nobody waits for anybody, so the scheme cannot deadlock
+// whatever else shares the GPU.
+template <bool kBf16Out>
 __global__ __launch_bounds__(kThreads) void gemm_f16_kernel(const _Float16* __restrict__ A, const _Float16* __restrict__ B,
                                                             int64_t M, int64_t N, int64_t K, const float* __restrict__ a_ts,
                                                             const float* __restrict__ b_ts, void* __restrict__ Dv,
                                                             int64_t ldd, int tiles_m, int tiles_n, int tile_begin,
-                                                            int tile_count) {
+                                                            int tile_count, int k_splits, float* partials,
+                                                            unsigned int* tickets) {
   extern __shared__ __attribute__((aligned(16))) char lds[];
-  constexpr int kFragsA = kTileM / 64;               // A fragments per wavefront (wave tile kTileM/2 x 64)
-  constexpr int kABytes = kTileM * kRowBytes;
-  constexpr int kStage = kABytes + kOperandBytes;
-  constexpr int kLoadsA = kTileM / 64;               // direct-load instructions per wavefront for the A tile
+  constexpr int kFragsA = 4;                         // A fragments per wavefront (wave tile 128 x 64)
+  constexpr int kABytes = kOperandBytes;
+  constexpr int kStage = kStageBytes;
+  constexpr int kLoadsA = 4;                         // direct-load instructions per wavefront for the A tile
 
   // Workgroup -> tile: consecutive ids go to different XCDs (round robin over 8, one L2 each);
   // give every XCD a contiguous range of tiles, walked in bands of 8 tile rows.
-  int wg = blockIdx.x, half = 0;
-  if (kTileM == 128) {
-    half = wg & 1;
-    wg >>= 1;
+  int wg = blockIdx.x, split = 0;
+  if (k_splits > 1) {
+    split = wg % k_splits;
+    wg /= k_splits;
   }
   if ((tile_count & 7) == 0) wg = (wg & 7) * (tile_count >> 3) + (wg >> 3);
+  const int tile_local = wg;
   const int pid = tile_begin + wg;
   constexpr int kBand = 8;
   const int band = pid / (kBand * tiles_n);
   const int band_rows = min(kBand, tiles_m - band * kBand);
   const int in_band = pid - band * kBand * tiles_n;
   const int tm = band * kBand + in_band % band_rows, tn = in_band / band_rows;
-  const int64_t m0 = static_cast<int64_t>(tm) * TM + half * 128, n0 = static_cast<int64_t>(tn) * TN;
+  const int64_t m0 = static_cast<int64_t>(tm) * TM, n0 = static_cast<int64_t>(tn) * TN;
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave >> 2, wn = wave & 3, l32 = lane & 31, lhi = lane >> 5;
-  const int arow = wm * (kTileM / 2) + l32, brow = wn * 64 + l32;
+  const int arow = wm * 128 + l32, brow = wn * 64 + l32;
 
   // Direct-load sources: one instruction fills an 8-row block of a tile.
   // Rows past the end of an operand are clamped; they only feed outputs that are never stored.
@@ -187,6 +196,8 @@ __global__ __launch_bounds__(kThreads) void gemm_f16_kernel(const _Float16* __re
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
   const int KT = static_cast<int>(K / TK);
+  const int kt_begin = static_cast<int>(static_cast<int64_t>(KT) * split / k_splits);
+  const int kt_end = static_cast<int>(static_cast<int64_t>(KT) * (split + 1) / k_splits);
   auto issue = [&](int kt, int stage) {
     char* base = lds + stage * kStage;
 #pragma unroll
@@ -196,13 +207,14 @@ __global__ __launch_bounds__(kThreads) void gemm_f16_kernel(const _Float16* __re
     for (int q = 0; q < 4; ++q)
       load_1k_to_lds(gb[q] + static_cast<int64_t>(kt) * kRowBytes, base + kABytes + (wave * 4 + q) * 1024);
   };
-  issue(0, 0);
+  issue(kt_begin, 0);
   __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): the direct loads have landed in LDS
   __syncthreads();
 
-  for (int kt = 0; kt < KT; ++kt) {
-    const char* cur = lds + (kt & 1) * kStage;
-    if (kt + 1 < KT) issue(kt + 1, (kt + 1) & 1);
+  for (int kt = kt_begin; kt < kt_end; ++kt) {
+    const int stage = (kt - kt_begin) & 1;
+    const char* cur = lds + stage * kStage;
+    if (kt + 1 < kt_end) issue(kt + 1, stage ^ 1);
     Frags<kFragsA> f0, f1;
     load_frags(f0, cur, cur + kABytes, arow, brow, 0 + lhi);
     load_frags(f1, cur, cur + kABytes, arow, brow, 2 + lhi);
@@ -216,13 +228,51 @@ __global__ __launch_bounds__(kThreads) void gemm_f16_kernel(const _Float16* __re
     __syncthreads();
   }
 
+  if (k_splits > 1) {
+    // Partial tile in fragment order: float4 number ((i*2+j)*4+q)*512 + tid.
+    float4v* mine = reinterpret_cast<float4v*>(partials) +
+                    (static_cast<int64_t>(tile_local) * k_splits + split) * (TM * TN / 4) + tid;
+#pragma unroll
+    for (int i = 0; i < kFragsA; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          float4v v;
+#pragma unroll
+          for (int t = 0; t < 4; ++t) v[t] = acc[i][j][q * 4 + t];
+          mine[((i * 2 + j) * 4 + q) * kThreads] = v;
+        }
+    __threadfence();   // the partial is visible device-wide before the ticket is drawn
+    __syncthreads();
+    unsigned int* flag = reinterpret_cast<unsigned int*>(lds);   // LDS is free: the loop ended with a barrier
+    if (tid == 0) *flag = atomicAdd(tickets + tile_local, 1u);
+    __syncthreads();
+    if (*flag != static_cast<unsigned int>(k_splits - 1)) return;
+    __threadfence();   // the other workgroups' partials are visible before they are read
+    const float4v* all = reinterpret_cast<const float4v*>(partials) +
+                         static_cast<int64_t>(tile_local) * k_splits * (TM * TN / 4) + tid;
+#pragma unroll
+    for (int i = 0; i < kFragsA; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          float4v v = all[((i * 2 + j) * 4 + q) * kThreads];
+          for (int sp = 1; sp < k_splits; ++sp)
+            v += all[static_cast<int64_t>(sp) * (TM * TN / 4) + ((i * 2 + j) * 4 + q) * kThreads];
+#pragma unroll
+          for (int t = 0; t < 4; ++t) acc[i][j][q * 4 + t] = v[t];
+        }
+  }
+
   // Tensor-level decode scales on the finished sums (App. B.3, after Eq. 5).
   const float out_scale = a_ts[0] * b_ts[0];
-  const int Mt = static_cast<int>(M - m0 < kTileM ? M - m0 : kTileM);
+  const int Mt = static_cast<int>(M - m0 < TM ? M - m0 : TM);
   const int Nt = static_cast<int>(N - n0 < TN ? N - n0 : TN);
 #pragma unroll
   for (int i = 0; i < kFragsA; ++i) {
-    const int m = wm * (kTileM / 2) + i * 32 + l32;
+    const int m = wm * 128 + i * 32 + l32;
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
 #pragma unroll
@@ -250,8 +300,35 @@ __global__ __launch_bounds__(kThreads) void gemm_f16_kernel(const _Float16* __re
 
 }  // namespace
 
+// Workspace: [A as FP16][B as FP16][256 tickets][split-K partial tiles], each part 256-byte aligned.
+constexpr int kCUs = 256;
+constexpr size_t kTicketBytes = kCUs * sizeof(unsigned int);
+constexpr size_t kPartialTileBytes = static_cast<size_t>(TM) * TN * sizeof(float);
+
+// How the last, partial round of 256x256 tiles is run: `tail` tiles (0 = there is none to treat
+// specially) shared by `splits` workgroups each.
+struct TailPlan {
+  int tail, splits;
+};
+
+static TailPlan plan_tail(int64_t M, int64_t N, int64_t K) {
+  const int64_t tiles = ((M + TM - 1) / TM) * ((N + TN - 1) / TN);
+  TailPlan p{static_cast<int>(tiles % kCUs), 1};
+  if (tiles < kCUs || p.tail == 0) return TailPlan{0, 1};
+  const int64_t KT = K / TK;
+  while (p.splits < 8 && p.tail * (p.splits * 2) <= kCUs && KT / (p.splits * 2) >= 8) p.splits *= 2;
+  if (p.splits == 1) p.tail = 0;
+  return p;
+}
+
+static size_t operand_bytes(int64_t M, int64_t N, int64_t K) {
+  const size_t b = static_cast<size_t>(M + N) * static_cast<size_t>(K) * 2;
+  return (b + 255) & ~static_cast<size_t>(255);
+}
+
 size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t K) {
-  return static_cast<size_t>(M + N) * static_cast<size_t>(K) * 2;
+  const TailPlan p = plan_tail(M, N, K);
+  return operand_bytes(M, N, K) + kTicketBytes + static_cast<size_t>(p.tail) * p.splits * kPartialTileBytes;
 }
 
 bool gemm_two_pass_usable(const GemmArgs& g) {
@@ -261,52 +338,49 @@ bool gemm_two_pass_usable(const GemmArgs& g) {
          reinterpret_cast<uintptr_t>(g.b.scales) % 2 == 0;
 }
 
-#define NVFP4_LAUNCH_F16(BF16, TILEM)                                                                              \
+#define NVFP4_LAUNCH_F16(BF16)                                                                                    \
   do {                                                                                                            \
-    constexpr int lds_bytes = 2 * ((TILEM) * kRowBytes + kOperandBytes);                                          \
     static bool attr_set = false;                                                                                 \
     if (!attr_set) {                                                                                              \
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_f16_kernel<BF16, TILEM>),            \
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);                  \
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_f16_kernel<BF16>),                   \
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, 2 * kStageBytes);            \
       if (e != hipSuccess) return e;                                                                              \
       attr_set = true;                                                                                            \
     }                                                                                                             \
-    hipLaunchKernelGGL((gemm_f16_kernel<BF16, TILEM>), dim3(wgs), dim3(kThreads), lds_bytes, s, a16, b16,         \
+    hipLaunchKernelGGL((gemm_f16_kernel<BF16>), dim3(wgs), dim3(kThreads), 2 * kStageBytes, s, a16, b16,          \
                        g.a.outer, g.b.outer, g.K, g.a.ts, g.b.ts, g.d, g.ldd, tiles_m, tiles_n, tile_begin,       \
-                       tile_count);                                                                               \
+                       tile_count, k_splits, partials, tickets);                                                  \
   } while (0)
 
-static hipError_t launch_f16(bool bf16_out, int tile_m, const _Float16* a16, const _Float16* b16, const GemmArgs& g,
-                             int tiles_m, int tiles_n, int tile_begin, int tile_count, hipStream_t s) {
-  const unsigned wgs = static_cast<unsigned>(tile_count) * (tile_m == 128 ? 2u : 1u);
-  if (tile_m == 256) {
-    if (bf16_out) NVFP4_LAUNCH_F16(true, 256); else NVFP4_LAUNCH_F16(false, 256);
-  } else {
-    if (bf16_out) NVFP4_LAUNCH_F16(true, 128); else NVFP4_LAUNCH_F16(false, 128);
-  }
+static hipError_t launch_f16(bool bf16_out, const _Float16* a16, const _Float16* b16, const GemmArgs& g, int tiles_m,
+                             int tiles_n, int tile_begin, int tile_count, int k_splits, float* partials,
+                             unsigned int* tickets, hipStream_t s) {
+  const unsigned wgs = static_cast<unsigned>(tile_count) * static_cast<unsigned>(k_splits);
+  if (bf16_out) NVFP4_LAUNCH_F16(true); else NVFP4_LAUNCH_F16(false);
   return hipGetLastError();
 }
 #undef NVFP4_LAUNCH_F16
 
 hipError_t launch_gemm_two_pass(const GemmArgs& g, hipStream_t s) {
   const int64_t M = g.a.outer, N = g.b.outer, K = g.K;
-  _Float16* a16 = static_cast<_Float16*>(g.workspace);
+  char* ws = static_cast<char*>(g.workspace);
+  _Float16* a16 = reinterpret_cast<_Float16*>(ws);
   _Float16* b16 = a16 + M * K;
+  unsigned int* tickets = reinterpret_cast<unsigned int*>(ws + operand_bytes(M, N, K));
+  float* partials = reinterpret_cast<float*>(ws + operand_bytes(M, N, K) + kTicketBytes);
   const int64_t na = M * K / 8, nb = N * K / 8;   // a_n8 is a multiple of 256 only if M*K is a multiple of 2048; the kernel does not need it
   hipLaunchKernelGGL(decode_f16_kernel, dim3(static_cast<unsigned>((na + nb + 255) / 256)), dim3(256), 0, s, g.a.codes,
-                     g.a.scales, na, a16, g.b.codes, g.b.scales, nb, b16);
+                     g.a.scales, na, a16, g.b.codes, g.b.scales, nb, b16, tickets);
   const int tiles_m = static_cast<int>((M + TM - 1) / TM), tiles_n = static_cast<int>((N + TN - 1) / TN);
   const int tiles = tiles_m * tiles_n;
   // One 256x256 tile keeps one CU busy (its LDS fits one workgroup).  Whole rounds of kCUs tiles
-  // run as they are; a last partial round of at most kCUs / 2 tiles is split into half tiles so
-  // that it fills the chip.
-  constexpr int kCUs = 256;
-  int tail = tiles % kCUs;
-  if (tail > kCUs / 2 || tiles < kCUs) tail = 0;
-  const int full = tiles - tail;
+  // run as they are; a last partial round that fills at most half the chip is split along K.
+  const TailPlan p = plan_tail(M, N, K);
+  const int full = tiles - p.tail;
   hipError_t e = hipSuccess;
-  if (full > 0) e = launch_f16(g.out_bf16, 256, a16, b16, g, tiles_m, tiles_n, 0, full, s);
-  if (e == hipSuccess && tail > 0) e = launch_f16(g.out_bf16, 128, a16, b16, g, tiles_m, tiles_n, full, tail, s);
+  if (full > 0) e = launch_f16(g.out_bf16, a16, b16, g, tiles_m, tiles_n, 0, full, 1, nullptr, nullptr, s);
+  if (e == hipSuccess && p.tail > 0)
+    e = launch_f16(g.out_bf16, a16, b16, g, tiles_m, tiles_n, full, p.tail, p.splits, partials, tickets, s);
   return e;
 }
 

@@ -109,7 +109,11 @@ def test_gemm_and_dequantize_reject_bad_arguments(lib):
 
 
 def test_gemm_workspace_query(lib):
-    assert nv.gemm_workspace_bytes(8192, 20480, 5120) == (8192 + 20480) * 5120 * 2
+    # FP16 copies of both operands + 256 split-K tickets (+ FP32 partial tiles when the last round of 256x256
+    # tiles is partial: 640 tiles -> 128 tiles x 2 splits, 1600 tiles -> 64 tiles x 4 splits)
+    assert nv.gemm_workspace_bytes(8192, 20480, 5120) == (8192 + 20480) * 5120 * 2 + 1024
+    assert nv.gemm_workspace_bytes(8192, 5120, 20480) == (8192 + 5120) * 20480 * 2 + 1024 + 256 * 256 * 256 * 4
+    assert nv.gemm_workspace_bytes(20480, 5120, 8192) == (20480 + 5120) * 8192 * 2 + 1024 + 256 * 256 * 256 * 4
     w = ctypes.c_size_t()
     assert lib.nvfp4_gemm_workspace_bytes(8, 16, 16, ctypes.addressof(w)) == -2
     assert lib.nvfp4_gemm_workspace_bytes(16, 16, 16, None) == -1

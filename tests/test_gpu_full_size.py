@@ -119,6 +119,8 @@ def test_config4_dgrad(weight):
     check_gemm_sample(dx, rdy, ref_row, 44)
     fused = nv.nvfp4_gemm(qdy, qw, nv.OP_DGRAD, nv.OUT_F32)
     check_gemm_sample(fused, rdy, ref_row, 45)
+    # 640 tiles of 256x256: the last 128 run split in two along K; every entry must agree with the fused route
+    assert float((dx - fused).double().norm() / fused.double().norm()) <= 2e-6
 
 
 @pytest.mark.parametrize("name,mode", [
@@ -173,3 +175,29 @@ def test_indexing_beyond_2_31_elements():
     y_big_fused = nv.nvfp4_gemm(big, wq, nv.OP_FPROP, nv.OUT_F32)
     err = (y_big_fused.view(reps, base_rows, 256) - y_small).double().norm() / (y_small.double().norm() * reps ** 0.5)
     assert float(err) <= 2e-6
+
+
+@pytest.mark.parametrize("M,N,K,splits", [(4352, 4096, 4096, 8), (4208, 4304, 2048, 4), (8192, 5120, 1024, 2)])
+def test_split_k_last_round(M, N, K, splits):
+    """Shapes whose last round of 256x256 tiles is partial (272, 289 and 640 tiles), ragged edges included: the
+    split-K launch against the oracle on a sample, against the fused route everywhere, and bit-for-bit against
+    itself (the partial sums are added in a fixed order)."""
+    assert nv.gemm_workspace_bytes(M, N, K) > (M + N) * K * 2 + 1024           # partial tiles are in the workspace
+    tiles = -(-M // 256) * -(-N // 256)
+    assert nv.gemm_workspace_bytes(M, N, K) == (((M + N) * K * 2 + 255) // 256) * 256 + 1024 + (tiles % 256) * splits * 2 ** 18
+    ab = synth.normal_with_outliers(M, K, 1.0, 901)
+    bb = synth.normal(N, K, 0.05, 902)
+    qa = nv.nvfp4_quantize(to_dev(ab), nv.LAYOUT_ROW)
+    qb = nv.nvfp4_quantize(to_dev(bb), nv.LAYOUT_ROW)
+    ra, rb = oracle.quantize(ab, oracle.ROW), oracle.quantize(bb, oracle.ROW)
+    ws = ws_for(M, N, K)
+    ws.fill_(0xA5)                                                              # the call must not rely on its contents
+    d = nv.nvfp4_gemm(qa, qb, nv.OP_DGRAD, nv.OUT_F32, workspace=ws)
+    check_gemm_sample(d, ra, rb, 91)
+    fused = nv.nvfp4_gemm(qa, qb, nv.OP_DGRAD, nv.OUT_F32)
+    assert float((d - fused).double().norm() / fused.double().norm()) <= 2e-6
+    for _ in range(3):
+        again = nv.nvfp4_gemm(qa, qb, nv.OP_DGRAD, nv.OUT_F32, workspace=ws)
+        assert torch.equal(again, d)
+    d16 = nv.nvfp4_gemm(qa, qb, nv.OP_DGRAD, nv.OUT_BF16, workspace=ws)
+    assert torch.equal(d16, d.to(torch.bfloat16))
