@@ -66,7 +66,9 @@ enum { NVFP4_LAYOUT_ROW = 1, NVFP4_LAYOUT_COL = 2 };       /* layout mask bits *
 enum { NVFP4_BLOCK_1x16 = 1, NVFP4_BLOCK_16x16 = 16 };     /* block_dim */
 enum { NVFP4_ROUND_RNE = 0, NVFP4_ROUND_SR = 1 };          /* rounding */
 enum { NVFP4_OP_FPROP = 0, NVFP4_OP_DGRAD = 1, NVFP4_OP_WGRAD = 2 };
-enum { NVFP4_OUT_F32 = 0, NVFP4_OUT_BF16 = 1 };
+/* NVFP4_OUT_F32_ACCUMULATE (nvfp4_gemm only): D <- D + result in FP32, for weight gradients that are
+ * accumulated over micro-batches in FP32 (Sec. 4.1, last paragraph). */
+enum { NVFP4_OUT_F32 = 0, NVFP4_OUT_BF16 = 1, NVFP4_OUT_F32_ACCUMULATE = 2 };
 enum { NVFP4_COPY_ROW = 0, NVFP4_COPY_COL = 1 };
 
 /*
@@ -132,7 +134,9 @@ int nvfp4_quantize(const void* x, int64_t rows, int64_t cols, int64_t ld, int la
  *                        B = col copy of the second [K,N] (-> [N,K]); both must
  *                        agree on rotation flag and seed (App. C)
  * D is device memory, [M, N] row-major with leading dimension ldd (a multiple
- * of 4), FP32 or bf16 (bf16 = round-to-nearest-even of the FP32 result).
+ * of 4), FP32 or bf16 (bf16 = round-to-nearest-even of the FP32 result).  With
+ * NVFP4_OUT_F32_ACCUMULATE, D is FP32 and is read: every element becomes
+ * fp32(D_old + result), one FP32 addition after the FP32 result is formed.
  * workspace: optional device scratch, 256-byte aligned.  With at least
  * nvfp4_gemm_workspace_bytes(M, N, K) bytes (and K a multiple of 64) the call
  * first decodes both operands to FP16 (value * block scale, exact) into it and

@@ -185,10 +185,15 @@ def _gemm_head(a: QCopy, b: QCopy):
     return [_p(a.codes), _p(a.scales), float(a.s_dec), _p(b.codes), _p(b.scales), float(b.s_dec)]
 
 
-def gemm_f64(a: QCopy, b: QCopy) -> np.ndarray:
+def gemm_f64(a: QCopy, b: QCopy, d_prev=None) -> np.ndarray:
+    """Eq. 5 on the dequantized operands in binary64.  With d_prev (the FP32 gradient buffer of Sec. 4.1's
+    micro-batch accumulation) the result is d_prev + product, still in binary64."""
     out = np.zeros((a.outer, b.outer), dtype=np.float64)
     rc = lib().orc_gemm_f64(*_gemm_head(a, b), a.outer, b.outer, a.inner, _p(out))
     assert rc == 0
+    if d_prev is not None:
+        assert d_prev.shape == out.shape and d_prev.dtype == np.float32
+        out = d_prev.astype(np.float64) + out
     return out
 
 

@@ -20,7 +20,7 @@ LAYOUT_ROW, LAYOUT_COL = 1, 2
 BLOCK_1x16, BLOCK_16x16 = 1, 16
 ROUND_RNE, ROUND_SR = 0, 1
 OP_FPROP, OP_DGRAD, OP_WGRAD = 0, 1, 2
-OUT_F32, OUT_BF16 = 0, 1
+OUT_F32, OUT_BF16, OUT_F32_ACCUMULATE = 0, 1, 2
 COPY_ROW, COPY_COL = 0, 1
 
 EXPORTS = ["nvfp4_quantized_sizes", "nvfp4_quantize", "nvfp4_gemm", "nvfp4_gemm_workspace_bytes", "nvfp4_dequantize",
@@ -167,9 +167,12 @@ def gemm_workspace_bytes(m: int, n: int, k: int) -> int:
 
 def nvfp4_gemm(a: QTensor, b: QTensor, op: int, out_dtype: int = OUT_F32,
                out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
-    """workspace: optional uint8 CUDA tensor of gemm_workspace_bytes(M, N, K) bytes (two-pass route)."""
+    """workspace: optional uint8 CUDA tensor of gemm_workspace_bytes(M, N, K) bytes (two-pass route).
+    OUT_F32_ACCUMULATE adds into `out` (required, float32)."""
     m = a.cols if op == OP_WGRAD else a.rows
     n = b.rows if op == OP_DGRAD else b.cols
+    if out_dtype == OUT_F32_ACCUMULATE and (out is None or out.dtype != torch.float32 or out.shape != (m, n)):
+        raise ValueError("OUT_F32_ACCUMULATE needs a float32 `out` of shape (M, N)")
     if out is None:
         dt = torch.float32 if out_dtype == OUT_F32 else torch.bfloat16
         dev = (a.row_codes if a.row_codes is not None else a.col_codes).device

@@ -149,7 +149,8 @@ int nvfp4_gemm_workspace_bytes(int64_t m, int64_t n, int64_t k, size_t* workspac
 int nvfp4_gemm(const nvfp4_qtensor* a, const nvfp4_qtensor* b, int op, void* d, int out_dtype, int64_t ldd,
                void* workspace, size_t workspace_bytes, nvfp4_stream_t stream) {
   if (!a || !b || !d) return NVFP4_ERR_INVALID_ARG;
-  if (out_dtype != NVFP4_OUT_F32 && out_dtype != NVFP4_OUT_BF16) return NVFP4_ERR_INVALID_ARG;
+  if (out_dtype != NVFP4_OUT_F32 && out_dtype != NVFP4_OUT_BF16 && out_dtype != NVFP4_OUT_F32_ACCUMULATE)
+    return NVFP4_ERR_INVALID_ARG;
   bool a_col, b_col;
   switch (op) {
     case NVFP4_OP_FPROP: a_col = false; b_col = true; break;
@@ -174,6 +175,7 @@ int nvfp4_gemm(const nvfp4_qtensor* a, const nvfp4_qtensor* b, int op, void* d, 
   g.d = d;
   g.ldd = ldd;
   g.out_bf16 = out_dtype == NVFP4_OUT_BF16;
+  g.accumulate = out_dtype == NVFP4_OUT_F32_ACCUMULATE;
   g.workspace = workspace;
   g.workspace_bytes = workspace ? workspace_bytes : 0;
   return launch_gemm(g, static_cast<hipStream_t>(stream)) == hipSuccess ? NVFP4_OK : NVFP4_ERR_HIP;

@@ -77,7 +77,7 @@ __device__ __forceinline__ void stage_row(const Operand& op, int64_t K, int64_t 
 
 template <bool kBf16Out>
 __global__ __launch_bounds__(kGemmThreads) void gemm_kernel(Operand A, Operand B, int64_t K,
-                                                            void* __restrict__ Dv, int64_t ldd) {
+                                                            void* __restrict__ Dv, int64_t ldd, bool accumulate) {
   __shared__ __attribute__((aligned(16))) _Float16 As[BM * LDS_LD];
   __shared__ __attribute__((aligned(16))) _Float16 Bs[BN * LDS_LD];
 
@@ -143,6 +143,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_kernel(Operand A, Operand B
             *reinterpret_cast<uint2*>(d) = o;
           } else {
             float* d = static_cast<float*>(Dv) + (m0 + m) * ldd + n0 + n;
+            if (accumulate) v += *reinterpret_cast<const float4v*>(d);
             *reinterpret_cast<float4v*>(d) = v;
           }
         }
@@ -244,7 +245,7 @@ __device__ __forceinline__ void mma_tile(float16v (&acc)[4][2], const char* at, 
 
 template <bool kBf16Out>
 __global__ __launch_bounds__(kBigThreads) void gemm_kernel_256(Operand A, Operand B, int64_t K,
-                                                               void* __restrict__ Dv, int64_t ldd,
+                                                               void* __restrict__ Dv, int64_t ldd, bool accumulate,
                                                                int tiles_m, int tiles_n) {
   extern __shared__ __attribute__((aligned(16))) char lds[];
 
@@ -333,6 +334,7 @@ __global__ __launch_bounds__(kBigThreads) void gemm_kernel_256(Operand A, Operan
             *reinterpret_cast<uint2*>(d) = o;
           } else {
             float* d = static_cast<float*>(Dv) + (m0 + m) * ldd + n0 + n;
+            if (accumulate) v += *reinterpret_cast<const float4v*>(d);
             *reinterpret_cast<float4v*>(d) = v;
           }
         }
@@ -363,16 +365,16 @@ hipError_t launch_gemm(const GemmArgs& g, hipStream_t s) {
     const int tiles_m = static_cast<int>((g.a.outer + TM - 1) / TM), tiles_n = static_cast<int>((g.b.outer + TN - 1) / TN);
     const dim3 grid(static_cast<unsigned>(tiles_m * tiles_n));
     if (g.out_bf16)
-      hipLaunchKernelGGL(gemm_kernel_256<true>, grid, dim3(kBigThreads), 2 * kStageBytes, s, g.a, g.b, g.K, g.d, g.ldd, tiles_m, tiles_n);
+      hipLaunchKernelGGL(gemm_kernel_256<true>, grid, dim3(kBigThreads), 2 * kStageBytes, s, g.a, g.b, g.K, g.d, g.ldd, g.accumulate, tiles_m, tiles_n);
     else
-      hipLaunchKernelGGL(gemm_kernel_256<false>, grid, dim3(kBigThreads), 2 * kStageBytes, s, g.a, g.b, g.K, g.d, g.ldd, tiles_m, tiles_n);
+      hipLaunchKernelGGL(gemm_kernel_256<false>, grid, dim3(kBigThreads), 2 * kStageBytes, s, g.a, g.b, g.K, g.d, g.ldd, g.accumulate, tiles_m, tiles_n);
     return hipGetLastError();
   }
   const dim3 grid(static_cast<unsigned>((g.b.outer + BN - 1) / BN), static_cast<unsigned>((g.a.outer + BM - 1) / BM));
   if (g.out_bf16)
-    hipLaunchKernelGGL(gemm_kernel<true>, grid, dim3(kGemmThreads), 0, s, g.a, g.b, g.K, g.d, g.ldd);
+    hipLaunchKernelGGL(gemm_kernel<true>, grid, dim3(kGemmThreads), 0, s, g.a, g.b, g.K, g.d, g.ldd, g.accumulate);
   else
-    hipLaunchKernelGGL(gemm_kernel<false>, grid, dim3(kGemmThreads), 0, s, g.a, g.b, g.K, g.d, g.ldd);
+    hipLaunchKernelGGL(gemm_kernel<false>, grid, dim3(kGemmThreads), 0, s, g.a, g.b, g.K, g.d, g.ldd, g.accumulate);
   return hipGetLastError();
 }
 

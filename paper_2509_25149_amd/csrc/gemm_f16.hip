@@ -139,8 +139,8 @@ template <bool kBf16Out>
 __global__ __launch_bounds__(kThreads) void gemm_f16_kernel(const _Float16* __restrict__ A, const _Float16* __restrict__ B,
                                                             int64_t M, int64_t N, int64_t K, const float* __restrict__ a_ts,
                                                             const float* __restrict__ b_ts, void* __restrict__ Dv,
-                                                            int64_t ldd, int tiles_m, int tiles_n, int tile_begin,
-                                                            int tile_count, int k_splits, float* partials,
+                                                            int64_t ldd, bool accumulate, int tiles_m, int tiles_n,
+                                                            int tile_begin, int tile_count, int k_splits, float* partials,
                                                             unsigned int* tickets) {
   extern __shared__ __attribute__((aligned(16))) char lds[];
   constexpr int kFragsA = 4;                         // A fragments per wavefront (wave tile 128 x 64)
@@ -290,6 +290,7 @@ __global__ __launch_bounds__(kThreads) void gemm_f16_kernel(const _Float16* __re
             *reinterpret_cast<uint2*>(d) = o;
           } else {
             float* d = static_cast<float*>(Dv) + (m0 + m) * ldd + n0 + n;
+            if (accumulate) v += *reinterpret_cast<const float4v*>(d);
             *reinterpret_cast<float4v*>(d) = v;
           }
         }
@@ -348,8 +349,8 @@ bool gemm_two_pass_usable(const GemmArgs& g) {
       attr_set = true;                                                                                            \
     }                                                                                                             \
     hipLaunchKernelGGL((gemm_f16_kernel<BF16>), dim3(wgs), dim3(kThreads), 2 * kStageBytes, s, a16, b16,          \
-                       g.a.outer, g.b.outer, g.K, g.a.ts, g.b.ts, g.d, g.ldd, tiles_m, tiles_n, tile_begin,       \
-                       tile_count, k_splits, partials, tickets);                                                  \
+                       g.a.outer, g.b.outer, g.K, g.a.ts, g.b.ts, g.d, g.ldd, g.accumulate, tiles_m, tiles_n,     \
+                       tile_begin, tile_count, k_splits, partials, tickets);                                      \
   } while (0)
 
 static hipError_t launch_f16(bool bf16_out, const _Float16* a16, const _Float16* b16, const GemmArgs& g, int tiles_m,

@@ -33,6 +33,7 @@ struct GemmArgs {
   void* d;
   int64_t ldd;
   bool out_bf16;
+  bool accumulate;   // FP32 output only: D <- D + result
   void* workspace;        // optional: room for both operands decoded to FP16
   size_t workspace_bytes;
 };

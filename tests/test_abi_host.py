@@ -93,6 +93,8 @@ def test_gemm_and_dequantize_reject_bad_arguments(lib):
     assert lib.nvfp4_gemm(None, ctypes.byref(b), 0, D, 0, 48, None, 0, None) == -1
     assert lib.nvfp4_gemm(ctypes.byref(a), ctypes.byref(b), 9, D, 0, 48, None, 0, None) == -1
     assert lib.nvfp4_gemm(ctypes.byref(a), ctypes.byref(b), 0, D, 5, 48, None, 0, None) == -1
+    assert lib.nvfp4_gemm(ctypes.byref(a), ctypes.byref(b), 0, D, 3, 48, None, 0, None) == -1     # 2 = accumulate is the last mode
+    assert lib.nvfp4_gemm(ctypes.byref(a), ctypes.byref(b), 0, D, 2, 32, None, 0, None) == -2     # accumulate mode is validated like the others
     assert lib.nvfp4_gemm(ctypes.byref(a), ctypes.byref(b), 0, D, 0, 32, None, 0, None) == -2     # ldd < N
     assert lib.nvfp4_gemm(ctypes.byref(a), ctypes.byref(b), 1, D, 0, 64, None, 0, None) == -4     # DGRAD: K 64 vs 48
     only_row = _desc(64, 48, mask=1)

@@ -89,6 +89,12 @@ def test_config2_wgrad_rht_sr():
     assert torch.equal(dw, again)
     fused = nv.nvfp4_gemm(qdy, qx, nv.OP_WGRAD, nv.OUT_F32)                 # the fused route, no workspace
     check_gemm_sample(fused, rdy, rx, 23)
+    # gradient accumulation over micro-batches (Sec. 4.1): the same micro-batch added twice into an FP32 buffer
+    acc = torch.zeros_like(dw)
+    nv.nvfp4_gemm(qdy, qx, nv.OP_WGRAD, nv.OUT_F32_ACCUMULATE, out=acc, workspace=ws)
+    assert torch.equal(acc, dw)
+    nv.nvfp4_gemm(qdy, qx, nv.OP_WGRAD, nv.OUT_F32_ACCUMULATE, out=acc, workspace=ws)
+    assert torch.equal(acc, dw + dw)
 
 
 def test_config3_fprop(weight):

@@ -189,6 +189,16 @@ def gemm_both_routes(a, b, op, ref):
     assert rel_fro(two.cpu().numpy(), ref) <= GEMM_TOL
     two16 = nv.nvfp4_gemm(a, b, op, nv.OUT_BF16, workspace=gemm_ws(m, n, k))
     assert torch.equal(two16, two.to(torch.bfloat16))
+    # FP32 accumulate-into (Sec. 4.1): D <- D + result, against the oracle's binary64 sum, and exactly one
+    # FP32 addition on top of the plain result
+    g = torch.Generator(device="cuda").manual_seed(1000 + m + n)
+    d_prev = torch.randn((m, n), generator=g, device="cuda") * float(np.abs(ref).mean())
+    want = d_prev.cpu().numpy().astype(np.float64) + ref
+    for ws, plain in ((None, fused), (gemm_ws(m, n, k), two)):
+        d = d_prev.clone()
+        nv.nvfp4_gemm(a, b, op, nv.OUT_F32_ACCUMULATE, out=d, workspace=ws)
+        assert rel_fro(d.cpu().numpy(), want) <= GEMM_TOL
+        assert torch.equal(d, d_prev + plain)
     return fused
 
 

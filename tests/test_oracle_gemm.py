@@ -118,3 +118,24 @@ def test_wgrad_with_rotation_approximates_the_plain_product():
     B2 = oracle.quantize(xb, oracle.COL, use_rht=True, rht_seed=seed + 1)
     if oracle.rht_sign_mask(seed) != oracle.rht_sign_mask(seed + 1):
         assert np.linalg.norm(oracle.gemm_f64(A, B2) - ref) > 0.5 * np.linalg.norm(ref)
+
+
+def test_accumulate_into_is_a_plain_sum():
+    """Sec. 4.1 gradient accumulation: the K range split into two micro-batches and accumulated equals the GEMM
+    over the whole K range (the tensor scales are shared by construction: both halves are cut from one
+    quantized tensor), and adding into zeros is the product itself."""
+    xb = synth.normal(32, 64, 1.0, 71)
+    wb = synth.normal(48, 64, 0.02, 72)
+    qa, qb = oracle.quantize(xb, oracle.ROW), oracle.quantize(wb, oracle.ROW)
+    whole = oracle.gemm_f64(qa, qb)
+    assert np.array_equal(oracle.gemm_f64(qa, qb, d_prev=np.zeros((32, 48), np.float32)), whole)
+
+    def half(q, lo, hi):
+        return oracle.QCopy(np.ascontiguousarray(q.codes[:, lo // 2:hi // 2]), np.ascontiguousarray(q.scales[:, lo // 16:hi // 16]),
+                            q.s_dec, q.amax, q.outer, hi - lo)
+    first = oracle.gemm_f64(half(qa, 0, 32), half(qb, 0, 32))
+    d32 = first.astype(np.float32)
+    both = oracle.gemm_f64(half(qa, 32, 64), half(qb, 32, 64), d_prev=d32)
+    # d32 carries one FP32 rounding of the first half: error at most 2^-24 relative to it
+    assert np.all(np.abs(both - whole) <= np.abs(first) * 2.0 ** -24 + 1e-300)
+    assert np.linalg.norm(both - whole) / np.linalg.norm(whole) < 1e-7
