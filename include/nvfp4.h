@@ -156,6 +156,39 @@ int nvfp4_gemm(const nvfp4_qtensor* a, const nvfp4_qtensor* b, int op, void* d, 
 int nvfp4_gemm_workspace_bytes(int64_t m, int64_t n, int64_t k, size_t* workspace_bytes);
 
 /*
+ * One linear layer, forward and backward, as the sequence of calls above
+ * (Sec. 4.1 and its compute-flow figure; Sec. 4.2-4.4 for which operand gets
+ * which treatment).  W [d_in, d_out] is quantized by the caller, once per
+ * optimizer step, with nvfp4_quantize(ROW | COL, 16x16 blocks) and reused by
+ * both calls.  All checks of every step run before anything is enqueued.
+ *
+ * nvfp4_linear_forward: quantize X [tokens, d_in] (bf16, leading dimension
+ *   ldx) with RNE -- row copy for Fprop and, if keep_for_backward, the rotated
+ *   col copy Wgrad will need (sign diagonal from rht_seed) -- then
+ *   Y [tokens, d_out] = X W (out_dtype FP32 or bf16, leading dimension ldy).
+ *   qx: host descriptor with the copy pointers set (nvfp4_quantized_sizes);
+ *   it is filled in and must stay alive until nvfp4_linear_backward.
+ * nvfp4_linear_backward: quantize dY [tokens, d_out] with stochastic rounding
+ *   (key sr_seed), row copy for Dgrad and col copy rotated like qx's, then
+ *   dX [tokens, d_in] = dY W^T (dx_dtype FP32 or bf16) and
+ *   dW [d_in, d_out] = X^T dY in FP32, added into dw if accumulate_dw
+ *   (micro-batch gradient accumulation), stored otherwise.
+ *   qdy: host descriptor with both copies' pointers set; scratch for the call.
+ * workspace: device, 256-byte aligned, shared by all steps of a call.  At least
+ *   the quantizer's need (nvfp4_quantized_sizes) is required; with
+ *   nvfp4_linear_workspace_bytes(tokens, d_in, d_out) bytes every GEMM takes
+ *   its faster two-pass route.
+ */
+int nvfp4_linear_workspace_bytes(int64_t tokens, int64_t d_in, int64_t d_out, size_t* workspace_bytes);
+int nvfp4_linear_forward(const void* x, int64_t tokens, int64_t d_in, int64_t ldx, const nvfp4_qtensor* qw,
+                         int keep_for_backward, uint64_t rht_seed, nvfp4_qtensor* qx, void* y, int out_dtype,
+                         int64_t ldy, void* workspace, size_t workspace_bytes, nvfp4_stream_t stream);
+int nvfp4_linear_backward(const void* dy, int64_t tokens, int64_t d_out, int64_t lddy, const nvfp4_qtensor* qx,
+                          const nvfp4_qtensor* qw, uint64_t sr_seed, nvfp4_qtensor* qdy, void* dx, int dx_dtype,
+                          int64_t lddx, float* dw, int64_t lddw, int accumulate_dw, void* workspace,
+                          size_t workspace_bytes, nvfp4_stream_t stream);
+
+/*
  * Decode one copy back to FP32 or bf16: value(code) * block scale * s_dec
  * (Sec. 2; App. B.2).  The output has the copy's own orientation: [rows, cols]
  * for the row copy, [cols, rows] for the col copy, leading dimension ld_out.

@@ -24,7 +24,8 @@ OUT_F32, OUT_BF16, OUT_F32_ACCUMULATE = 0, 1, 2
 COPY_ROW, COPY_COL = 0, 1
 
 EXPORTS = ["nvfp4_quantized_sizes", "nvfp4_quantize", "nvfp4_gemm", "nvfp4_gemm_workspace_bytes", "nvfp4_dequantize",
-           "nvfp4_rht_sign_mask", "nvfp4_selftest_conversions", "nvfp4_status_string", "nvfp4_version"]
+           "nvfp4_rht_sign_mask", "nvfp4_selftest_conversions", "nvfp4_status_string", "nvfp4_version",
+           "nvfp4_linear_workspace_bytes", "nvfp4_linear_forward", "nvfp4_linear_backward"]
 
 
 class QTensorStruct(ctypes.Structure):
@@ -60,6 +61,14 @@ def load_library() -> ctypes.CDLL:
                                  vp, ctypes.c_size_t, vp]
         L.nvfp4_gemm_workspace_bytes.restype = ci
         L.nvfp4_gemm_workspace_bytes.argtypes = [i64, i64, i64, vp]
+        qp = ctypes.POINTER(QTensorStruct)
+        L.nvfp4_linear_workspace_bytes.restype = ci
+        L.nvfp4_linear_workspace_bytes.argtypes = [i64, i64, i64, vp]
+        L.nvfp4_linear_forward.restype = ci
+        L.nvfp4_linear_forward.argtypes = [vp, i64, i64, i64, qp, ci, u64, qp, vp, ci, i64, vp, ctypes.c_size_t, vp]
+        L.nvfp4_linear_backward.restype = ci
+        L.nvfp4_linear_backward.argtypes = [vp, i64, i64, i64, qp, qp, u64, qp, vp, ci, i64, vp, i64, ci,
+                                            vp, ctypes.c_size_t, vp]
         L.nvfp4_dequantize.restype = ci
         L.nvfp4_dequantize.argtypes = [ctypes.POINTER(QTensorStruct), ci, ci, vp, ci, i64, vp]
         L.nvfp4_rht_sign_mask.restype = ctypes.c_uint32
@@ -181,6 +190,55 @@ def nvfp4_gemm(a: QTensor, b: QTensor, op: int, out_dtype: int = OUT_F32,
     _check(load_library().nvfp4_gemm(ctypes.byref(a.desc), ctypes.byref(b.desc), op, out.data_ptr(), out_dtype,
                                      out.stride(0), ws_ptr, ws_bytes, _stream()))
     return out
+
+
+def linear_workspace_bytes(tokens: int, d_in: int, d_out: int) -> int:
+    w = ctypes.c_size_t()
+    _check(load_library().nvfp4_linear_workspace_bytes(tokens, d_in, d_out, ctypes.addressof(w)))
+    return w.value
+
+
+def _check_bf16_2d(t: torch.Tensor, what: str) -> None:
+    if not t.is_cuda or t.dtype != torch.bfloat16 or t.dim() != 2 or t.stride(1) != 1:
+        raise ValueError(f"{what} must be a 2-D bf16 CUDA tensor with unit inner stride")
+
+
+def nvfp4_linear_forward(x: torch.Tensor, qw: QTensor, workspace: torch.Tensor, keep_for_backward: bool = True,
+                         rht_seed: int = 0, out_dtype: int = OUT_BF16, qx: Optional[QTensor] = None,
+                         y: Optional[torch.Tensor] = None):
+    """Returns (y, qx); qx feeds nvfp4_linear_backward."""
+    _check_bf16_2d(x, "x")
+    tokens, d_in = x.shape
+    if qx is None:
+        qx = alloc_qtensor(tokens, d_in, LAYOUT_ROW | (LAYOUT_COL if keep_for_backward else 0), x.device)
+    if y is None:
+        y = torch.empty((tokens, qw.cols), dtype=torch.float32 if out_dtype == OUT_F32 else torch.bfloat16,
+                        device=x.device)
+    _check(load_library().nvfp4_linear_forward(x.data_ptr(), tokens, d_in, x.stride(0), ctypes.byref(qw.desc),
+                                               int(keep_for_backward), rht_seed, ctypes.byref(qx.desc), y.data_ptr(),
+                                               out_dtype, y.stride(0), workspace.data_ptr(), workspace.numel(),
+                                               _stream()))
+    return y, qx
+
+
+def nvfp4_linear_backward(dy: torch.Tensor, qx: QTensor, qw: QTensor, dw: torch.Tensor, workspace: torch.Tensor,
+                          accumulate_dw: bool = True, sr_seed: int = 0, dx_dtype: int = OUT_BF16,
+                          qdy: Optional[QTensor] = None, dx: Optional[torch.Tensor] = None):
+    """dw: float32 [d_in, d_out], added into when accumulate_dw.  Returns (dx, qdy)."""
+    _check_bf16_2d(dy, "dy")
+    tokens, d_out = dy.shape
+    if dw.dtype != torch.float32 or dw.shape != (qx.cols, d_out) or dw.stride(1) != 1:
+        raise ValueError("dw must be float32 [d_in, d_out] with unit inner stride")
+    if qdy is None:
+        qdy = alloc_qtensor(tokens, d_out, LAYOUT_ROW | LAYOUT_COL, dy.device)
+    if dx is None:
+        dx = torch.empty((tokens, qx.cols), dtype=torch.float32 if dx_dtype == OUT_F32 else torch.bfloat16,
+                         device=dy.device)
+    _check(load_library().nvfp4_linear_backward(dy.data_ptr(), tokens, d_out, dy.stride(0), ctypes.byref(qx.desc),
+                                                ctypes.byref(qw.desc), sr_seed, ctypes.byref(qdy.desc), dx.data_ptr(),
+                                                dx_dtype, dx.stride(0), dw.data_ptr(), dw.stride(0),
+                                                int(accumulate_dw), workspace.data_ptr(), workspace.numel(), _stream()))
+    return dx, qdy
 
 
 def nvfp4_dequantize(q: QTensor, which_copy: int, undo_rht: bool = False, out_dtype: int = OUT_F32,

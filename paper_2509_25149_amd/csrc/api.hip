@@ -69,9 +69,17 @@ int nvfp4_quantized_sizes(int64_t rows, int64_t cols, size_t* codes_bytes, size_
   return NVFP4_OK;
 }
 
-int nvfp4_quantize(const void* x, int64_t rows, int64_t cols, int64_t ld, int layout_mask, int block_dim,
-                   int rounding, int rht_on_col, uint64_t rht_seed, uint64_t sr_seed, nvfp4_qtensor* out,
-                   void* workspace, size_t workspace_bytes, nvfp4_stream_t stream) {
+namespace {
+
+// A validated nvfp4_quantize call: kernel arguments plus the descriptor as it will read afterwards.
+struct QuantPlan {
+  QuantizeArgs a;
+  nvfp4_qtensor desc;
+};
+
+int plan_quantize(const void* x, int64_t rows, int64_t cols, int64_t ld, int layout_mask, int block_dim, int rounding,
+                  int rht_on_col, uint64_t rht_seed, uint64_t sr_seed, const nvfp4_qtensor* out, void* workspace,
+                  size_t workspace_bytes, QuantPlan* p) {
   if (!x || !out) return NVFP4_ERR_INVALID_ARG;
   if (layout_mask <= 0 || (layout_mask & ~(NVFP4_LAYOUT_ROW | NVFP4_LAYOUT_COL))) return NVFP4_ERR_INVALID_ARG;
   if (block_dim != NVFP4_BLOCK_1x16 && block_dim != NVFP4_BLOCK_16x16) return NVFP4_ERR_INVALID_ARG;
@@ -86,7 +94,7 @@ int nvfp4_quantize(const void* x, int64_t rows, int64_t cols, int64_t ld, int la
   if (want_col && (!aligned(out->col_codes, 16) || !aligned(out->col_scales, 16))) return NVFP4_ERR_INVALID_ARG;
   if (!workspace || workspace_bytes < quantize_workspace_bytes(rows, cols) || !aligned(workspace, 16)) return NVFP4_ERR_WORKSPACE;
 
-  QuantizeArgs a;
+  QuantizeArgs& a = p->a;
   a.x = x;
   a.rows = rows;
   a.cols = cols;
@@ -106,15 +114,29 @@ int nvfp4_quantize(const void* x, int64_t rows, int64_t cols, int64_t ld, int la
   a.col_codes = static_cast<uint8_t*>(out->col_codes);
   a.col_scales = static_cast<uint8_t*>(out->col_scales);
   a.col_ts = out->col_tensor_scale;
-  if (launch_quantize(a, static_cast<hipStream_t>(stream)) != hipSuccess) return NVFP4_ERR_HIP;
 
-  out->rows = rows;
-  out->cols = cols;
-  out->layout_mask = layout_mask;
-  out->block_dim = block_dim;
-  out->rounding = rounding;
-  out->col_has_rht = a.rht ? 1 : 0;
-  out->rht_seed = a.rht ? rht_seed : 0;
+  p->desc = *out;
+  p->desc.rows = rows;
+  p->desc.cols = cols;
+  p->desc.layout_mask = layout_mask;
+  p->desc.block_dim = block_dim;
+  p->desc.rounding = rounding;
+  p->desc.col_has_rht = a.rht ? 1 : 0;
+  p->desc.rht_seed = a.rht ? rht_seed : 0;
+  return NVFP4_OK;
+}
+
+}  // namespace
+
+int nvfp4_quantize(const void* x, int64_t rows, int64_t cols, int64_t ld, int layout_mask, int block_dim,
+                   int rounding, int rht_on_col, uint64_t rht_seed, uint64_t sr_seed, nvfp4_qtensor* out,
+                   void* workspace, size_t workspace_bytes, nvfp4_stream_t stream) {
+  QuantPlan p;
+  const int rc = plan_quantize(x, rows, cols, ld, layout_mask, block_dim, rounding, rht_on_col, rht_seed, sr_seed, out,
+                               workspace, workspace_bytes, &p);
+  if (rc != NVFP4_OK) return rc;
+  if (launch_quantize(p.a, static_cast<hipStream_t>(stream)) != hipSuccess) return NVFP4_ERR_HIP;
+  *out = p.desc;
   return NVFP4_OK;
 }
 
@@ -146,8 +168,8 @@ int nvfp4_gemm_workspace_bytes(int64_t m, int64_t n, int64_t k, size_t* workspac
   return NVFP4_OK;
 }
 
-int nvfp4_gemm(const nvfp4_qtensor* a, const nvfp4_qtensor* b, int op, void* d, int out_dtype, int64_t ldd,
-               void* workspace, size_t workspace_bytes, nvfp4_stream_t stream) {
+static int plan_gemm(const nvfp4_qtensor* a, const nvfp4_qtensor* b, int op, void* d, int out_dtype, int64_t ldd,
+                     void* workspace, size_t workspace_bytes, GemmArgs* gp) {
   if (!a || !b || !d) return NVFP4_ERR_INVALID_ARG;
   if (out_dtype != NVFP4_OUT_F32 && out_dtype != NVFP4_OUT_BF16 && out_dtype != NVFP4_OUT_F32_ACCUMULATE)
     return NVFP4_ERR_INVALID_ARG;
@@ -158,7 +180,7 @@ int nvfp4_gemm(const nvfp4_qtensor* a, const nvfp4_qtensor* b, int op, void* d, 
     case NVFP4_OP_WGRAD: a_col = true; b_col = true; break;
     default: return NVFP4_ERR_INVALID_ARG;
   }
-  GemmArgs g;
+  GemmArgs& g = *gp;
   int64_t ka = 0, kb = 0;
   int rc = pick_operand(a, a_col, &g.a, &ka);
   if (rc != NVFP4_OK) return rc;
@@ -178,7 +200,70 @@ int nvfp4_gemm(const nvfp4_qtensor* a, const nvfp4_qtensor* b, int op, void* d, 
   g.accumulate = out_dtype == NVFP4_OUT_F32_ACCUMULATE;
   g.workspace = workspace;
   g.workspace_bytes = workspace ? workspace_bytes : 0;
+  return NVFP4_OK;
+}
+
+int nvfp4_gemm(const nvfp4_qtensor* a, const nvfp4_qtensor* b, int op, void* d, int out_dtype, int64_t ldd,
+               void* workspace, size_t workspace_bytes, nvfp4_stream_t stream) {
+  GemmArgs g;
+  const int rc = plan_gemm(a, b, op, d, out_dtype, ldd, workspace, workspace_bytes, &g);
+  if (rc != NVFP4_OK) return rc;
   return launch_gemm(g, static_cast<hipStream_t>(stream)) == hipSuccess ? NVFP4_OK : NVFP4_ERR_HIP;
+}
+
+// ---------------------------------------------------------------- one linear layer (Sec. 4.1, Fig. 3)
+
+int nvfp4_linear_workspace_bytes(int64_t tokens, int64_t d_in, int64_t d_out, size_t* workspace_bytes) {
+  if (tokens <= 0 || d_in <= 0 || d_out <= 0 || tokens % 16 || d_in % 16 || d_out % 16) return NVFP4_ERR_BAD_SHAPE;
+  if (!workspace_bytes) return NVFP4_ERR_INVALID_ARG;
+  size_t need = quantize_workspace_bytes(tokens, d_in);
+  const size_t parts[4] = {quantize_workspace_bytes(tokens, d_out), gemm_workspace_bytes(tokens, d_out, d_in),
+                           gemm_workspace_bytes(tokens, d_in, d_out), gemm_workspace_bytes(d_in, d_out, tokens)};
+  for (size_t b : parts) need = b > need ? b : need;
+  *workspace_bytes = need;
+  return NVFP4_OK;
+}
+
+int nvfp4_linear_forward(const void* x, int64_t tokens, int64_t d_in, int64_t ldx, const nvfp4_qtensor* qw,
+                         int keep_for_backward, uint64_t rht_seed, nvfp4_qtensor* qx, void* y, int out_dtype,
+                         int64_t ldy, void* workspace, size_t workspace_bytes, nvfp4_stream_t stream) {
+  if (!qw || !qx || !y) return NVFP4_ERR_INVALID_ARG;
+  QuantPlan px;
+  const int layouts = keep_for_backward ? (NVFP4_LAYOUT_ROW | NVFP4_LAYOUT_COL) : NVFP4_LAYOUT_ROW;
+  int rc = plan_quantize(x, tokens, d_in, ldx, layouts, NVFP4_BLOCK_1x16, NVFP4_ROUND_RNE, keep_for_backward ? 1 : 0,
+                         rht_seed, 0, qx, workspace, workspace_bytes, &px);
+  if (rc != NVFP4_OK) return rc;
+  GemmArgs g;
+  rc = plan_gemm(&px.desc, qw, NVFP4_OP_FPROP, y, out_dtype, ldy, workspace, workspace_bytes, &g);
+  if (rc != NVFP4_OK) return rc;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (launch_quantize(px.a, s) != hipSuccess) return NVFP4_ERR_HIP;
+  *qx = px.desc;
+  return launch_gemm(g, s) == hipSuccess ? NVFP4_OK : NVFP4_ERR_HIP;
+}
+
+int nvfp4_linear_backward(const void* dy, int64_t tokens, int64_t d_out, int64_t lddy, const nvfp4_qtensor* qx,
+                          const nvfp4_qtensor* qw, uint64_t sr_seed, nvfp4_qtensor* qdy, void* dx, int dx_dtype,
+                          int64_t lddx, float* dw, int64_t lddw, int accumulate_dw, void* workspace,
+                          size_t workspace_bytes, nvfp4_stream_t stream) {
+  if (!qx || !qw || !qdy || !dx || !dw) return NVFP4_ERR_INVALID_ARG;
+  if (dx_dtype != NVFP4_OUT_F32 && dx_dtype != NVFP4_OUT_BF16) return NVFP4_ERR_INVALID_ARG;
+  if (!(qx->layout_mask & NVFP4_LAYOUT_COL) || !qx->col_has_rht) return NVFP4_ERR_MISSING_COPY;
+  QuantPlan pdy;
+  int rc = plan_quantize(dy, tokens, d_out, lddy, NVFP4_LAYOUT_ROW | NVFP4_LAYOUT_COL, NVFP4_BLOCK_1x16,
+                         NVFP4_ROUND_SR, 1, qx->rht_seed, sr_seed, qdy, workspace, workspace_bytes, &pdy);
+  if (rc != NVFP4_OK) return rc;
+  GemmArgs dgrad, wgrad;
+  rc = plan_gemm(&pdy.desc, qw, NVFP4_OP_DGRAD, dx, dx_dtype, lddx, workspace, workspace_bytes, &dgrad);
+  if (rc != NVFP4_OK) return rc;
+  rc = plan_gemm(qx, &pdy.desc, NVFP4_OP_WGRAD, dw, accumulate_dw ? NVFP4_OUT_F32_ACCUMULATE : NVFP4_OUT_F32, lddw,
+                 workspace, workspace_bytes, &wgrad);
+  if (rc != NVFP4_OK) return rc;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (launch_quantize(pdy.a, s) != hipSuccess) return NVFP4_ERR_HIP;
+  *qdy = pdy.desc;
+  if (launch_gemm(dgrad, s) != hipSuccess) return NVFP4_ERR_HIP;
+  return launch_gemm(wgrad, s) == hipSuccess ? NVFP4_OK : NVFP4_ERR_HIP;
 }
 
 int nvfp4_dequantize(const nvfp4_qtensor* q, int which_copy, int undo_rht, void* out, int out_dtype,

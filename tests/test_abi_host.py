@@ -125,3 +125,37 @@ def test_sign_mask_matches_the_oracle(lib):
     import oracle
     for seed in (0, 1, 2025, 0xDEADBEEFCAFE, 2 ** 64 - 1):
         assert nv.rht_sign_mask(seed) == oracle.rht_sign_mask(seed)
+
+
+def test_linear_layer_calls_reject_before_enqueueing(lib):
+    """The per-layer entry points validate every step first: all of these fail on the host (no GPU here)."""
+    w = ctypes.c_size_t()
+    assert lib.nvfp4_linear_workspace_bytes(8192, 5120, 20480, ctypes.addressof(w)) == 0
+    assert w.value == max(nv.gemm_workspace_bytes(8192, 20480, 5120), nv.gemm_workspace_bytes(8192, 5120, 20480),
+                          nv.gemm_workspace_bytes(5120, 20480, 8192))
+    assert lib.nvfp4_linear_workspace_bytes(8192, 5120, 20481, ctypes.addressof(w)) == -2
+    assert lib.nvfp4_linear_workspace_bytes(16, 16, 16, None) == -1
+    qw, qx, qdy = nv.QTensorStruct(), nv.QTensorStruct(), nv.QTensorStruct()
+    fake = 0x10000
+    for q in (qw, qx, qdy):
+        q.row_codes = q.row_scales = q.row_tensor_scale = fake
+        q.col_codes = q.col_scales = q.col_tensor_scale = fake
+    qw.rows, qw.cols, qw.layout_mask, qw.block_dim = 64, 48, 3, 16
+    fwd = lambda *a: lib.nvfp4_linear_forward(*a)
+    ok_ws = (fake, 1 << 20, None)
+    assert fwd(fake, 32, 64, 64, None, 1, 0, ctypes.byref(qx), fake, 1, 48, *ok_ws) == -1
+    assert fwd(fake, 32, 64, 64, ctypes.byref(qw), 1, 0, ctypes.byref(qx), None, 1, 48, *ok_ws) == -1
+    assert fwd(fake, 32, 72, 72, ctypes.byref(qw), 1, 0, ctypes.byref(qx), fake, 1, 48, *ok_ws) == -2   # d_in % 16
+    assert fwd(fake, 32, 80, 80, ctypes.byref(qw), 1, 0, ctypes.byref(qx), fake, 1, 48, *ok_ws) == -4   # K: 80 vs W's 64
+    assert fwd(fake, 32, 64, 64, ctypes.byref(qw), 1, 0, ctypes.byref(qx), fake, 1, 32, *ok_ws) == -2   # ldy < d_out
+    assert fwd(fake, 32, 64, 64, ctypes.byref(qw), 1, 0, ctypes.byref(qx), fake, 1, 48, fake, 8, None) == -6
+    assert qx.layout_mask == 0                                   # a rejected call leaves the descriptor alone
+    bwd = lambda *a: lib.nvfp4_linear_backward(*a)
+    qx.rows, qx.cols, qx.layout_mask, qx.block_dim, qx.col_has_rht, qx.rht_seed = 32, 64, 3, 1, 1, 5
+    assert bwd(fake, 32, 48, 48, ctypes.byref(qx), ctypes.byref(qw), 0, ctypes.byref(qdy), fake, 7, 64, fake, 48, 1, *ok_ws) == -1
+    assert bwd(fake, 32, 48, 48, ctypes.byref(qx), ctypes.byref(qw), 0, ctypes.byref(qdy), fake, 1, 48, fake, 48, 1, *ok_ws) == -2  # lddx < d_in
+    assert bwd(fake, 32, 48, 48, ctypes.byref(qx), ctypes.byref(qw), 0, ctypes.byref(qdy), fake, 1, 64, fake, 32, 1, *ok_ws) == -2  # lddw < d_out
+    assert bwd(fake, 48, 48, 48, ctypes.byref(qx), ctypes.byref(qw), 0, ctypes.byref(qdy), fake, 1, 64, fake, 48, 1, *ok_ws) == -4  # tokens differ
+    qx.col_has_rht = 0
+    assert bwd(fake, 32, 48, 48, ctypes.byref(qx), ctypes.byref(qw), 0, ctypes.byref(qdy), fake, 1, 64, fake, 48, 1, *ok_ws) == -3  # no rotated copy kept
+    assert qdy.layout_mask == 0

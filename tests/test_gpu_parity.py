@@ -248,3 +248,50 @@ def test_gemm_output_with_leading_dimension():
     got = buf.cpu().numpy()
     assert np.all(got[:, 48:] == 7.0)
     assert rel_fro(got[:, :48], oracle.gemm_f64(rx["row"], rw["col"])) <= GEMM_TOL
+
+
+def test_linear_layer_calls_equal_the_call_sequence():
+    """nvfp4_linear_forward / nvfp4_linear_backward (Sec. 4.1 flow) against the oracle and, bit for bit, against
+    the same steps issued one by one; two micro-batches accumulate into one FP32 dW."""
+    tokens, d_in, d_out = 384, 512, 640
+    rht_seed, sr_seed = 77, 4242
+    wb = synth.normal(d_in, d_out, 0.02, 801)
+    qw = nv.nvfp4_quantize(to_dev(wb), nv.LAYOUT_ROW | nv.LAYOUT_COL, nv.BLOCK_16x16)
+    rw_col = oracle.quantize(wb, oracle.COL, oracle.BLOCK_16x16)
+    rw_row = oracle.quantize(wb, oracle.ROW, oracle.BLOCK_16x16)
+    ws = torch.empty(nv.linear_workspace_bytes(tokens, d_in, d_out), dtype=torch.uint8, device="cuda")
+    dw = torch.zeros((d_in, d_out), dtype=torch.float32, device="cuda")
+    dw_ref = np.zeros((d_in, d_out), dtype=np.float64)
+    for mb in range(2):
+        xb = synth.normal_with_outliers(tokens, d_in, 1.0, 810 + mb)
+        dyb = synth.student_t3(tokens, d_out, 1e-3, 820 + mb)
+        y, qx = nv.nvfp4_linear_forward(to_dev(xb), qw, ws, True, rht_seed, nv.OUT_F32)
+        rx_row = oracle.quantize(xb, oracle.ROW)
+        rx_col = oracle.quantize(xb, oracle.COL, use_rht=True, rht_seed=rht_seed)
+        assert_copy_equal(qx.row_codes, qx.row_scales, qx.row_ts, rx_row, "X row")
+        assert_copy_equal(qx.col_codes, qx.col_scales, qx.col_ts, rx_col, "X col (RHT)")
+        assert rel_fro(y.cpu().numpy(), oracle.gemm_f64(rx_row, rw_col)) <= GEMM_TOL
+        dw_before = dw.clone()
+        dx, qdy = nv.nvfp4_linear_backward(to_dev(dyb), qx, qw, dw, ws, True, sr_seed + mb, nv.OUT_F32)
+        rdy_row = oracle.quantize(dyb, oracle.ROW, rounding=oracle.SR, sr_seed=sr_seed + mb)
+        rdy_col = oracle.quantize(dyb, oracle.COL, rounding=oracle.SR, use_rht=True, rht_seed=rht_seed, sr_seed=sr_seed + mb)
+        assert_copy_equal(qdy.row_codes, qdy.row_scales, qdy.row_ts, rdy_row, "dY row (SR)")
+        assert_copy_equal(qdy.col_codes, qdy.col_scales, qdy.col_ts, rdy_col, "dY col (RHT, SR)")
+        assert rel_fro(dx.cpu().numpy(), oracle.gemm_f64(rdy_row, rw_row)) <= GEMM_TOL
+        dw_ref = oracle.gemm_f64(rx_col, rdy_col, d_prev=dw_before.cpu().numpy())
+        assert rel_fro(dw.cpu().numpy(), dw_ref) <= GEMM_TOL
+        # the same steps one by one give the same bits
+        qx2 = nv.nvfp4_quantize(to_dev(xb), nv.LAYOUT_ROW | nv.LAYOUT_COL, rht_on_col=True, rht_seed=rht_seed)
+        y2 = nv.nvfp4_gemm(qx2, qw, nv.OP_FPROP, nv.OUT_F32, workspace=ws)
+        qdy2 = nv.nvfp4_quantize(to_dev(dyb), nv.LAYOUT_ROW | nv.LAYOUT_COL, rounding=nv.ROUND_SR, rht_on_col=True,
+                                 rht_seed=rht_seed, sr_seed=sr_seed + mb)
+        dx2 = nv.nvfp4_gemm(qdy2, qw, nv.OP_DGRAD, nv.OUT_F32, workspace=ws)
+        dw2 = dw_before.clone()
+        nv.nvfp4_gemm(qx2, qdy2, nv.OP_WGRAD, nv.OUT_F32_ACCUMULATE, out=dw2, workspace=ws)
+        assert torch.equal(y, y2) and torch.equal(dx, dx2) and torch.equal(dw, dw2)
+    # inference-style forward keeps no column copy, and backward refuses such a descriptor
+    y3, qx3 = nv.nvfp4_linear_forward(to_dev(xb), qw, ws, False, 0, nv.OUT_BF16)
+    assert qx3.col_codes is None and torch.equal(y3, y.to(torch.bfloat16))
+    with pytest.raises(nv.NVFP4Error) as e:
+        nv.nvfp4_linear_backward(to_dev(dyb), qx3, qw, dw, ws)
+    assert e.value.status == -3
