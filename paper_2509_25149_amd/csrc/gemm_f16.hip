@@ -5,7 +5,10 @@
 //           workspace;
 //   pass 2  a plain FP16 x FP16 -> FP32 MFMA GEMM whose main loop has no VALU
 //           work at all: tiles go from global memory straight into LDS
-//           (global_load_lds_dwordx4), fragments come from LDS, 32x32x16 MFMAs.
+//           (global_load_lds_dwordx4), fragments come from LDS, 16x16x32 MFMAs
+//           (measured under the chip's power limit: a register-only loop of
+//           v_mfma_f32_16x16x32_f16 sustains 12-20 % more flop/s than one of
+//           v_mfma_f32_32x32x16_f16 on the same operand values).
 // Why: decoding inside the GEMM loop costs about one VALU instruction per
 // element, and VALU instructions co-issued with MFMAs take matrix-pipe time
 // (measured: the fused kernel runs at 0.95-1.0 PFLOP/s, this pair at about
@@ -74,7 +77,7 @@ __global__ __launch_bounds__(256) void decode_f16_kernel(const uint8_t* __restri
 
 // ---------------------------------------------------------------- pass 2: FP16 GEMM
 // 256 x 256 outputs per workgroup, K step 64, 512 threads = 8 wavefronts (2 x 4),
-// each 128 x 64 outputs as 4 x 2 MFMA 32x32 blocks.  LDS holds two stages of
+// each 128 x 64 outputs as 8 x 4 MFMA 16x16 blocks.  LDS holds two stages of
 // (A tile, B tile), 64 KiB each; a stage is filled by direct global->LDS loads:
 // one instruction moves 64 lanes x 16 bytes into 1 KiB of consecutive LDS, i.e.
 // 8 tile rows of 128 bytes, and lane l fetches the 16-byte chunk that belongs at
@@ -88,28 +91,28 @@ constexpr int kStageBytes = 2 * kOperandBytes;  // 64 KiB
 
 __device__ __forceinline__ int swz(int row, int chunk) { return row * kRowBytes + ((chunk ^ ((row >> 1) & 7)) << 4); }
 
-template <int kFragsA>
+// Fragments of one 32-wide half of a K step for a 128 x 64 wave tile.  A 16x16x32 MFMA operand
+// is 16 rows x 32 k: lane l holds the 8 consecutive k of 16-byte chunk (l >> 4) of row (l & 15).
 struct Frags {
-  half8v a[kFragsA], b[2];
+  half8v a[8], b[4];
 };
 
-template <int kFragsA>
-__device__ __forceinline__ void load_frags(Frags<kFragsA>& f, const char* at, const char* bt, int arow, int brow, int chunk) {
+// `chunk` = half * 4 + (lane >> 4): the lane's 16-byte chunk of the 128-byte tile row.
+__device__ __forceinline__ void load_frags(Frags& f, const char* at, const char* bt, int arow, int brow, int chunk) {
 #pragma unroll
-  for (int i = 0; i < kFragsA; ++i) f.a[i] = *reinterpret_cast<const half8v*>(at + swz(arow + i * 32, chunk));
+  for (int i = 0; i < 8; ++i) f.a[i] = *reinterpret_cast<const half8v*>(at + swz(arow + i * 16, chunk));
 #pragma unroll
-  for (int j = 0; j < 2; ++j) f.b[j] = *reinterpret_cast<const half8v*>(bt + swz(brow + j * 32, chunk));
+  for (int j = 0; j < 4; ++j) f.b[j] = *reinterpret_cast<const half8v*>(bt + swz(brow + j * 16, chunk));
 }
 
-// The MFMA's M index is the B row (n), its N index the A row (m): a lane ends up
-// with 4 consecutive n of one m, which makes the output stores 64/128-bit.
-template <int kFragsA>
-__device__ __forceinline__ void mma_step(float16v (&acc)[kFragsA][2], const Frags<kFragsA>& f) {
+// The MFMA's M index is the B row (n), its N index the A row (m): lane l ends up with the 4
+// consecutive n = (l >> 4) * 4 .. + 3 of m = l & 15, which makes the output stores 64/128-bit.
+__device__ __forceinline__ void mma_step(float4v (&acc)[8][4], const Frags& f) {
 #pragma unroll
-  for (int i = 0; i < kFragsA; ++i)
+  for (int i = 0; i < 8; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
-      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(f.b[j], f.a[i], acc[i][j], 0, 0, 0);
+    for (int j = 0; j < 4; ++j)
+      acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(f.b[j], f.a[i], acc[i][j], 0, 0, 0);
 }
 
 typedef __attribute__((address_space(3))) void* lds_ptr;
@@ -143,7 +146,6 @@ __global__ __launch_bounds__(kThreads) void gemm_f16_kernel(const _Float16* __re
                                                             int tile_begin, int tile_count, int k_splits, float* partials,
                                                             unsigned int* tickets) {
   extern __shared__ __attribute__((aligned(16))) char lds[];
-  constexpr int kFragsA = 4;                         // A fragments per wavefront (wave tile 128 x 64)
   constexpr int kABytes = kOperandBytes;
   constexpr int kStage = kStageBytes;
   constexpr int kLoadsA = 4;                         // direct-load instructions per wavefront for the A tile
@@ -167,8 +169,8 @@ __global__ __launch_bounds__(kThreads) void gemm_f16_kernel(const _Float16* __re
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wm = wave >> 2, wn = wave & 3, l32 = lane & 31, lhi = lane >> 5;
-  const int arow = wm * 128 + l32, brow = wn * 64 + l32;
+  const int wm = wave >> 2, wn = wave & 3, l16 = lane & 15, lq = lane >> 4;
+  const int arow = wm * 128 + l16, brow = wn * 64 + l16;
 
   // Direct-load sources: one instruction fills an 8-row block of a tile.
   // Rows past the end of an operand are clamped; they only feed outputs that are never stored.
@@ -187,13 +189,13 @@ __global__ __launch_bounds__(kThreads) void gemm_f16_kernel(const _Float16* __re
     gb[q] = reinterpret_cast<const char*>(B) + min<int64_t>(n0 + r, N - 1) * K * 2 + c * 16;
   }
 
-  float16v acc[kFragsA][2];
+  float4v acc[8][4];
 #pragma unroll
-  for (int i = 0; i < kFragsA; ++i)
+  for (int i = 0; i < 8; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < 4; ++j)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+      for (int r = 0; r < 4; ++r) acc[i][j][r] = 0.0f;
 
   const int KT = static_cast<int>(K / TK);
   const int kt_begin = static_cast<int>(static_cast<int64_t>(KT) * split / k_splits);
@@ -215,13 +217,9 @@ __global__ __launch_bounds__(kThreads) void gemm_f16_kernel(const _Float16* __re
     const int stage = (kt - kt_begin) & 1;
     const char* cur = lds + stage * kStage;
     if (kt + 1 < kt_end) issue(kt + 1, stage ^ 1);
-    Frags<kFragsA> f0, f1;
-    load_frags(f0, cur, cur + kABytes, arow, brow, 0 + lhi);
-    load_frags(f1, cur, cur + kABytes, arow, brow, 2 + lhi);
-    mma_step(acc, f0);
-    load_frags(f0, cur, cur + kABytes, arow, brow, 4 + lhi);
-    mma_step(acc, f1);
-    load_frags(f1, cur, cur + kABytes, arow, brow, 6 + lhi);
+    Frags f0, f1;
+    load_frags(f0, cur, cur + kABytes, arow, brow, 0 + lq);
+    load_frags(f1, cur, cur + kABytes, arow, brow, 4 + lq);
     mma_step(acc, f0);
     mma_step(acc, f1);
     __builtin_amdgcn_s_waitcnt(0x0f70);
@@ -229,20 +227,13 @@ __global__ __launch_bounds__(kThreads) void gemm_f16_kernel(const _Float16* __re
   }
 
   if (k_splits > 1) {
-    // Partial tile in fragment order: float4 number ((i*2+j)*4+q)*512 + tid.
+    // Partial tile in fragment order: float4 number (i * 4 + j) * 512 + tid.
     float4v* mine = reinterpret_cast<float4v*>(partials) +
                     (static_cast<int64_t>(tile_local) * k_splits + split) * (TM * TN / 4) + tid;
 #pragma unroll
-    for (int i = 0; i < kFragsA; ++i)
+    for (int i = 0; i < 8; ++i)
 #pragma unroll
-      for (int j = 0; j < 2; ++j)
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          float4v v;
-#pragma unroll
-          for (int t = 0; t < 4; ++t) v[t] = acc[i][j][q * 4 + t];
-          mine[((i * 2 + j) * 4 + q) * kThreads] = v;
-        }
+      for (int j = 0; j < 4; ++j) mine[(i * 4 + j) * kThreads] = acc[i][j];
     __threadfence();   // the partial is visible device-wide before the ticket is drawn
     __syncthreads();
     unsigned int* flag = reinterpret_cast<unsigned int*>(lds);   // LDS is free: the loop ended with a barrier
@@ -253,17 +244,13 @@ __global__ __launch_bounds__(kThreads) void gemm_f16_kernel(const _Float16* __re
     const float4v* all = reinterpret_cast<const float4v*>(partials) +
                          static_cast<int64_t>(tile_local) * k_splits * (TM * TN / 4) + tid;
 #pragma unroll
-    for (int i = 0; i < kFragsA; ++i)
+    for (int i = 0; i < 8; ++i)
 #pragma unroll
-      for (int j = 0; j < 2; ++j)
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          float4v v = all[((i * 2 + j) * 4 + q) * kThreads];
-          for (int sp = 1; sp < k_splits; ++sp)
-            v += all[static_cast<int64_t>(sp) * (TM * TN / 4) + ((i * 2 + j) * 4 + q) * kThreads];
-#pragma unroll
-          for (int t = 0; t < 4; ++t) acc[i][j][q * 4 + t] = v[t];
-        }
+      for (int j = 0; j < 4; ++j) {
+        float4v v = all[(i * 4 + j) * kThreads];
+        for (int sp = 1; sp < k_splits; ++sp) v += all[static_cast<int64_t>(sp) * (TM * TN / 4) + (i * 4 + j) * kThreads];
+        acc[i][j] = v;
+      }
   }
 
   // Tensor-level decode scales on the finished sums (App. B.3, after Eq. 5).
@@ -271,28 +258,23 @@ __global__ __launch_bounds__(kThreads) void gemm_f16_kernel(const _Float16* __re
   const int Mt = static_cast<int>(M - m0 < TM ? M - m0 : TM);
   const int Nt = static_cast<int>(N - n0 < TN ? N - n0 : TN);
 #pragma unroll
-  for (int i = 0; i < kFragsA; ++i) {
-    const int m = wm * 128 + i * 32 + l32;
+  for (int i = 0; i < 8; ++i) {
+    const int m = wm * 128 + i * 16 + l16;
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int n = wn * 64 + j * 32 + q * 8 + lhi * 4;
-        if (m < Mt && n < Nt) {
-          float4v v;
-#pragma unroll
-          for (int t = 0; t < 4; ++t) v[t] = acc[i][j][q * 4 + t] * out_scale;
-          if (kBf16Out) {
-            uint16_t* d = static_cast<uint16_t*>(Dv) + (m0 + m) * ldd + n0 + n;
-            uint2 o;
-            o.x = f32_to_bf16(v[0]) | (f32_to_bf16(v[1]) << 16);
-            o.y = f32_to_bf16(v[2]) | (f32_to_bf16(v[3]) << 16);
-            *reinterpret_cast<uint2*>(d) = o;
-          } else {
-            float* d = static_cast<float*>(Dv) + (m0 + m) * ldd + n0 + n;
-            if (accumulate) v += *reinterpret_cast<const float4v*>(d);
-            *reinterpret_cast<float4v*>(d) = v;
-          }
+    for (int j = 0; j < 4; ++j) {
+      const int n = wn * 64 + j * 16 + lq * 4;
+      if (m < Mt && n < Nt) {  // N is a multiple of 16, so the 4 columns are in or out together
+        float4v v = acc[i][j] * out_scale;
+        if (kBf16Out) {
+          uint16_t* d = static_cast<uint16_t*>(Dv) + (m0 + m) * ldd + n0 + n;
+          uint2 o;
+          o.x = f32_to_bf16(v[0]) | (f32_to_bf16(v[1]) << 16);
+          o.y = f32_to_bf16(v[2]) | (f32_to_bf16(v[3]) << 16);
+          *reinterpret_cast<uint2*>(d) = o;
+        } else {
+          float* d = static_cast<float*>(Dv) + (m0 + m) * ldd + n0 + n;
+          if (accumulate) v += *reinterpret_cast<const float4v*>(d);
+          *reinterpret_cast<float4v*>(d) = v;
         }
       }
     }
