@@ -234,23 +234,37 @@ __global__ __launch_bounds__(kThreads) void gemm_f16_kernel(const _Float16* __re
     for (int i = 0; i < 8; ++i)
 #pragma unroll
       for (int j = 0; j < 4; ++j) mine[(i * 4 + j) * kThreads] = acc[i][j];
-    __threadfence();   // the partial is visible device-wide before the ticket is drawn
+    // Publish: the barrier waits for every wavefront's stores to reach L2; then one thread makes
+    // them visible device-wide (one L2 write-back per workgroup instead of one per wavefront),
+    // draws the ticket and, if it is the last one, discards stale cached lines before anyone reads.
     __syncthreads();
     unsigned int* flag = reinterpret_cast<unsigned int*>(lds);   // LDS is free: the loop ended with a barrier
-    if (tid == 0) *flag = atomicAdd(tickets + tile_local, 1u);
+    if (tid == 0) {
+      __threadfence();
+      const unsigned int ticket = atomicAdd(tickets + tile_local, 1u);
+      if (ticket == static_cast<unsigned int>(k_splits - 1)) __threadfence();
+      *flag = ticket;
+    }
     __syncthreads();
     if (*flag != static_cast<unsigned int>(k_splits - 1)) return;
-    __threadfence();   // the other workgroups' partials are visible before they are read
     const float4v* all = reinterpret_cast<const float4v*>(partials) +
                          static_cast<int64_t>(tile_local) * k_splits * (TM * TN / 4) + tid;
+    // acc = ((p0 + p1) + p2) + ...: every partial is fetched with 16 independent loads in flight.
+    for (int sp = 0; sp < k_splits; ++sp) {
+      const float4v* part = all + static_cast<int64_t>(sp) * (TM * TN / 4);
 #pragma unroll
-    for (int i = 0; i < 8; ++i)
+      for (int h = 0; h < 2; ++h) {
+        float4v t[4][4];
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        float4v v = all[(i * 4 + j) * kThreads];
-        for (int sp = 1; sp < k_splits; ++sp) v += all[static_cast<int64_t>(sp) * (TM * TN / 4) + (i * 4 + j) * kThreads];
-        acc[i][j] = v;
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int j = 0; j < 4; ++j) t[i][j] = part[((h * 4 + i) * 4 + j) * kThreads];
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int j = 0; j < 4; ++j) acc[h * 4 + i][j] = sp == 0 ? t[i][j] : acc[h * 4 + i][j] + t[i][j];
       }
+    }
   }
 
   // Tensor-level decode scales on the finished sums (App. B.3, after Eq. 5).
