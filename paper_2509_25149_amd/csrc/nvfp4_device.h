@@ -92,22 +92,31 @@ __device__ __forceinline__ uint32_t cvt_rne_pair(uint32_t old, float v0, float v
 // through it and are merged with merge_bytes() instead.
 template <int kSel>
 __device__ __forceinline__ uint32_t cvt_sr_single(float v, uint32_t rand_hi16) {
-  float2v p;
+  float2v p;   // the pair's second value is never looked at: it stays undefined so that no register move is spent on it
   p.x = v;
-  p.y = v;
   return __builtin_amdgcn_cvt_scalef32_sr_pk_fp4_f32(0u, p, rand_hi16, 1.0f, kSel);
+}
+
+// (a & mask) | (b & ~mask) in one v_bitop3_b32 (truth table: the expression evaluated on
+// a = 0xF0, b = 0xCC, mask = 0xAA).  Spelled with the builtin so that the compiler keeps it one
+// instruction instead of re-deriving the nibble masks term by term.
+__device__ __forceinline__ uint32_t bit_select(uint32_t mask, uint32_t a, uint32_t b) {
+  return __builtin_amdgcn_bitop3_b32(a, b, mask, 0xE4);
+}
+
+// a ^ b ^ c in one instruction
+__device__ __forceinline__ uint32_t xor3(uint32_t a, uint32_t b, uint32_t c) {
+  return __builtin_amdgcn_bitop3_b32(a, b, c, 0x96);
 }
 
 // byte t of the result is byte t of b[t]
 __device__ __forceinline__ uint32_t merge_bytes(uint32_t b0, uint32_t b1, uint32_t b2, uint32_t b3) {
-  const uint32_t hi = (b2 & 0x00FF0000u) | (b3 & ~0x00FF0000u);
-  const uint32_t lo = (b0 & 0x000000FFu) | (b1 & ~0x000000FFu);
-  return (lo & 0x0000FFFFu) | (hi & ~0x0000FFFFu);
+  return bit_select(0x0000FFFFu, bit_select(0x000000FFu, b0, b1), bit_select(0x00FF0000u, b2, b3));
 }
 
 // low nibbles of `even` and of `odd` interleaved: byte t = odd.nibble(2t) << 4 | even.nibble(2t)
 __device__ __forceinline__ uint32_t interleave_nibbles(uint32_t even, uint32_t odd) {
-  return (even & 0x0F0F0F0Fu) | ((odd << 4) & ~0x0F0F0F0Fu);
+  return bit_select(0x0F0F0F0Fu, even, odd << 4);
 }
 
 // Philox4x32-10 (Salmon et al., SC'11).
@@ -117,8 +126,8 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
   for (int r = 0; r < 10; ++r) {
     const uint64_t p0 = static_cast<uint64_t>(c0) * 0xD2511F53ull;
     const uint64_t p1 = static_cast<uint64_t>(c2) * 0xCD9E8D57ull;
-    const uint32_t n0 = static_cast<uint32_t>(p1 >> 32) ^ c1 ^ k0;
-    const uint32_t n2 = static_cast<uint32_t>(p0 >> 32) ^ c3 ^ k1;
+    const uint32_t n0 = xor3(static_cast<uint32_t>(p1 >> 32), c1, k0);
+    const uint32_t n2 = xor3(static_cast<uint32_t>(p0 >> 32), c3, k1);
     c1 = static_cast<uint32_t>(p1);
     c3 = static_cast<uint32_t>(p0);
     c0 = n0;
