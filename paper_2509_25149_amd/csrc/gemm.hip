@@ -210,35 +210,37 @@ __device__ __forceinline__ void stage_decoded(const Prefetch& p, char* tile, int
   *reinterpret_cast<uint4*>(tile + swz(row, 7)) = decode8(p.hi.w, h3);
 }
 
+// Fragments of one 32-wide half of a K step for a 128 x 64 wave tile.  A 16x16x32 MFMA operand is
+// 16 rows x 32 k: lane l holds the 8 consecutive k of 16-byte chunk (l >> 4) of row (l & 15).
+// (16x16x32 rather than 32x32x16: more flop/s under the chip's power limit on the same operands.)
 struct Frags {
-  half8v a[4], b[2];
+  half8v a[8], b[4];
 };
 
+// `chunk` = half * 4 + (lane >> 4): the lane's 16-byte chunk of the 128-byte tile row.
 __device__ __forceinline__ void load_frags(Frags& f, const char* at, const char* bt, int arow, int brow, int chunk) {
 #pragma unroll
-  for (int i = 0; i < 4; ++i) f.a[i] = *reinterpret_cast<const half8v*>(at + swz(arow + i * 32, chunk));
+  for (int i = 0; i < 8; ++i) f.a[i] = *reinterpret_cast<const half8v*>(at + swz(arow + i * 16, chunk));
 #pragma unroll
-  for (int j = 0; j < 2; ++j) f.b[j] = *reinterpret_cast<const half8v*>(bt + swz(brow + j * 32, chunk));
+  for (int j = 0; j < 4; ++j) f.b[j] = *reinterpret_cast<const half8v*>(bt + swz(brow + j * 16, chunk));
 }
 
-__device__ __forceinline__ void mma_step(float16v (&acc)[4][2], const Frags& f) {
+// The MFMA's M index is the B row (n), its N index the A row (m): lane l ends up with the 4
+// consecutive n = (l >> 4) * 4 .. + 3 of m = l & 15.
+__device__ __forceinline__ void mma_step(float4v (&acc)[8][4], const Frags& f) {
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int i = 0; i < 8; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
-      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(f.b[j], f.a[i], acc[i][j], 0, 0, 0);
+    for (int j = 0; j < 4; ++j)
+      acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(f.b[j], f.a[i], acc[i][j], 0, 0, 0);
 }
 
-// The 32 MFMAs of one K step, fragments prefetched one sub-step ahead.
-__device__ __forceinline__ void mma_tile(float16v (&acc)[4][2], const char* at, const char* bt, int arow, int brow,
-                                         int lhi) {
+// The 64 MFMAs of one K step.
+__device__ __forceinline__ void mma_tile(float4v (&acc)[8][4], const char* at, const char* bt, int arow, int brow,
+                                         int lq) {
   Frags f0, f1;
-  load_frags(f0, at, bt, arow, brow, 0 + lhi);
-  load_frags(f1, at, bt, arow, brow, 2 + lhi);
-  mma_step(acc, f0);
-  load_frags(f0, at, bt, arow, brow, 4 + lhi);
-  mma_step(acc, f1);
-  load_frags(f1, at, bt, arow, brow, 6 + lhi);
+  load_frags(f0, at, bt, arow, brow, 0 + lq);
+  load_frags(f1, at, bt, arow, brow, 4 + lq);
   mma_step(acc, f0);
   mma_step(acc, f1);
 }
@@ -268,17 +270,17 @@ __global__ __launch_bounds__(kBigThreads) void gemm_kernel_256(Operand A, Operan
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int group = wave >> 2;           // 0: stages A, MFMA first; 1: stages B, decode first
   const int wm = wave >> 2, wn = wave & 3;
-  const int l32 = lane & 31, lhi = lane >> 5;
+  const int l16 = lane & 15, lq = lane >> 4;
   const int srow = tid & 255;            // the operand-tile row this thread stages
-  const int arow = wm * 128 + l32, brow = wn * 64 + l32;
+  const int arow = wm * 128 + l16, brow = wn * 64 + l16;
 
-  float16v acc[4][2];
+  float4v acc[8][4];
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int i = 0; i < 8; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < 4; ++j)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+      for (int r = 0; r < 4; ++r) acc[i][j][r] = 0.0f;
 
   const Operand& mine = group == 0 ? A : B;
   const int64_t my_row = (group == 0 ? m0 : n0) + srow;
@@ -304,7 +306,7 @@ __global__ __launch_bounds__(kBigThreads) void gemm_kernel_256(Operand A, Operan
     const char* tile = lds + (kt & 1) * kStageBytes;
     const int ahead = kt + 1 + group;    // the K step this wavefront stages during step kt
     if (ahead + 1 < KT) fetch_row(nxt, mine, K, my_row, static_cast<int64_t>(ahead + 1) * TK);
-    mma_tile(acc, tile, tile + kOperandBytes, arow, brow, lhi);
+    mma_tile(acc, tile, tile + kOperandBytes, arow, brow, lq);
     if (group == 0 && ahead < KT) stage_decoded(cur, lds + (ahead & 1) * kStageBytes + my_off, srow);
     __syncthreads();
     if (group == 1 && ahead < KT) stage_decoded(cur, lds + (ahead & 1) * kStageBytes + my_off, srow);
@@ -315,28 +317,23 @@ __global__ __launch_bounds__(kBigThreads) void gemm_kernel_256(Operand A, Operan
   const int M = static_cast<int>(A.outer - m0 < TM ? A.outer - m0 : TM);
   const int N = static_cast<int>(B.outer - n0 < TN ? B.outer - n0 : TN);
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int m = wm * 128 + i * 32 + l32;
+  for (int i = 0; i < 8; ++i) {
+    const int m = wm * 128 + i * 16 + l16;
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int n = wn * 64 + j * 32 + q * 8 + lhi * 4;
-        if (m < M && n < N) {
-          float4v v;
-#pragma unroll
-          for (int t = 0; t < 4; ++t) v[t] = acc[i][j][q * 4 + t] * out_scale;
-          if (kBf16Out) {
-            uint16_t* d = static_cast<uint16_t*>(Dv) + (m0 + m) * ldd + n0 + n;
-            uint2 o;
-            o.x = f32_to_bf16(v[0]) | (f32_to_bf16(v[1]) << 16);
-            o.y = f32_to_bf16(v[2]) | (f32_to_bf16(v[3]) << 16);
-            *reinterpret_cast<uint2*>(d) = o;
-          } else {
-            float* d = static_cast<float*>(Dv) + (m0 + m) * ldd + n0 + n;
-            if (accumulate) v += *reinterpret_cast<const float4v*>(d);
-            *reinterpret_cast<float4v*>(d) = v;
-          }
+    for (int j = 0; j < 4; ++j) {
+      const int n = wn * 64 + j * 16 + lq * 4;
+      if (m < M && n < N) {  // N is a multiple of 16, so the 4 columns are in or out together
+        float4v v = acc[i][j] * out_scale;
+        if (kBf16Out) {
+          uint16_t* d = static_cast<uint16_t*>(Dv) + (m0 + m) * ldd + n0 + n;
+          uint2 o;
+          o.x = f32_to_bf16(v[0]) | (f32_to_bf16(v[1]) << 16);
+          o.y = f32_to_bf16(v[2]) | (f32_to_bf16(v[3]) << 16);
+          *reinterpret_cast<uint2*>(d) = o;
+        } else {
+          float* d = static_cast<float*>(Dv) + (m0 + m) * ldd + n0 + n;
+          if (accumulate) v += *reinterpret_cast<const float4v*>(d);
+          *reinterpret_cast<float4v*>(d) = v;
         }
       }
     }
