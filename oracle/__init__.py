@@ -76,6 +76,25 @@ def lib() -> ctypes.CDLL:
         L.orc_gemm_f64_entries.argtypes = gemm_head + [i64, i64, vp, vp, vp]
         L.orc_gemm_f32_blockscaled.restype = ctypes.c_int
         L.orc_gemm_f32_blockscaled.argtypes = gemm_head + [i64, i64, i64, vp]
+        # MXFP4 (comparison format)
+        L.orc_rht_sign_mask32.restype = u32
+        L.orc_rht_sign_mask32.argtypes = [u64]
+        L.orc_rht32_forward.restype = None
+        L.orc_rht32_forward.argtypes = [vp, u32]
+        L.orc_rht32_inverse.restype = None
+        L.orc_rht32_inverse.argtypes = [vp, u32]
+        L.orc_ue8m0_exponent_round_up.restype = ctypes.c_int
+        L.orc_ue8m0_exponent_round_up.argtypes = [f32]
+        L.orc_mx_col_random16.restype = u32
+        L.orc_mx_col_random16.argtypes = [u64, u64, u64]
+        L.orc_mx_quantize.restype = ctypes.c_int
+        L.orc_mx_quantize.argtypes = [vp, i64, i64, i64, ctypes.c_int, ctypes.c_int, ctypes.c_int, u64, u64, vp, vp, vp]
+        L.orc_mx_dequantize.restype = ctypes.c_int
+        L.orc_mx_dequantize.argtypes = [vp, vp, i64, i64, ctypes.c_int, u64, vp]
+        L.orc_mx_gemm_f64.restype = ctypes.c_int
+        L.orc_mx_gemm_f64.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp]
+        L.orc_mx_gemm_f64_entries.restype = ctypes.c_int
+        L.orc_mx_gemm_f64_entries.argtypes = [vp, vp, vp, vp, i64, i64, vp, vp, vp]
         _lib = L
     return _lib
 
@@ -212,3 +231,72 @@ def gemm_f32_blockscaled(a: QCopy, b: QCopy) -> np.ndarray:
     rc = lib().orc_gemm_f32_blockscaled(*_gemm_head(a, b), a.outer, b.outer, a.inner, _p(out))
     assert rc == 0
     return out
+
+
+# ------------------------------------------------------------------ MXFP4 (comparison format, Sec. 2 / App. B.4)
+
+def rht_sign_mask32(seed: int) -> int:
+    return int(lib().orc_rht_sign_mask32(seed))
+
+
+def rht32_forward(v, mask: int) -> np.ndarray:
+    a = np.ascontiguousarray(v, dtype=np.float32).copy()
+    assert a.size == 32
+    lib().orc_rht32_forward(_p(a), mask)
+    return a
+
+
+def rht32_inverse(v, mask: int) -> np.ndarray:
+    a = np.ascontiguousarray(v, dtype=np.float32).copy()
+    assert a.size == 32
+    lib().orc_rht32_inverse(_p(a), mask)
+    return a
+
+
+def ue8m0_exponent_round_up(s: float) -> int:
+    return int(lib().orc_ue8m0_exponent_round_up(s))
+
+
+def mx_col_random16(seed: int, i: int, j: int) -> int:
+    return int(lib().orc_mx_col_random16(seed, i, j))
+
+
+def mx_quantize(x_bf16_bits: np.ndarray, copy: int, rounding: int = RNE, use_rht: bool = False, rht_seed: int = 0,
+                sr_seed: int = 0) -> QCopy:
+    """MXFP4: codes [outer, inner/2], UE8M0 scales [outer, inner/32]; s_dec is 1 (there is no tensor scale)."""
+    x = np.ascontiguousarray(x_bf16_bits, dtype=np.uint16)
+    rows, cols = x.shape
+    outer, inner = (cols, rows) if copy == COL else (rows, cols)
+    codes = np.zeros((outer, inner // 2), dtype=np.uint8)
+    scales = np.zeros((outer, max(inner // 32, 1)), dtype=np.uint8)
+    amax = np.zeros(1, dtype=np.float32)
+    rc = lib().orc_mx_quantize(_p(x), rows, cols, cols, copy, rounding, int(use_rht), rht_seed, sr_seed, _p(codes),
+                               _p(scales), _p(amax))
+    if rc != 0:
+        raise ValueError(f"orc_mx_quantize rejected its arguments (rc={rc})")
+    return QCopy(codes, scales, np.float32(1.0), np.float32(amax[0]), outer, inner)
+
+
+def mx_dequantize(q: QCopy, undo_rht: bool = False, rht_seed: int = 0) -> np.ndarray:
+    out = np.zeros((q.outer, q.inner), dtype=np.float32)
+    rc = lib().orc_mx_dequantize(_p(q.codes), _p(q.scales), q.outer, q.inner, int(undo_rht), rht_seed, _p(out))
+    assert rc == 0
+    return out
+
+
+def mx_gemm_f64(a: QCopy, b: QCopy) -> np.ndarray:
+    assert a.inner == b.inner
+    out = np.zeros((a.outer, b.outer), dtype=np.float64)
+    rc = lib().orc_mx_gemm_f64(_p(a.codes), _p(a.scales), _p(b.codes), _p(b.scales), a.outer, b.outer, a.inner, _p(out))
+    assert rc == 0
+    return out
+
+
+def mx_gemm_f64_entries(a: QCopy, b: QCopy, m_idx, n_idx) -> np.ndarray:
+    m = np.ascontiguousarray(m_idx, dtype=np.int64)
+    n = np.ascontiguousarray(n_idx, dtype=np.int64)
+    out = np.zeros(m.size, dtype=np.float64)
+    rc = lib().orc_mx_gemm_f64_entries(_p(a.codes), _p(a.scales), _p(b.codes), _p(b.scales), a.inner, m.size, _p(m),
+                                       _p(n), _p(out))
+    assert rc == 0
+    return out.reshape(m.shape)

@@ -60,6 +60,13 @@
 // derivation, nibble order and sign-of-zero rule are conventions of this
 // repository: parity unpinned against the paper (it states none), pinned
 // oracle <-> GPU only.
+// The MXFP4 section at the end of this file (the paper's comparison format) has
+// its own header and pins (tests/test_oracle_mxfp4.py): the power-of-two
+// round-up rule by exact rationals, the worked example of App. B.4, an
+// independent numpy formulation, the no-saturation / lost-binade invariants,
+// the 32-point Sylvester form, SR draws and unbiasedness.  Its draw counters
+// for the col copy and its 32-bit sign vector are conventions of this
+// repository (parity unpinned against the paper).
 
 #include <cmath>
 #include <cstdint>
@@ -478,6 +485,200 @@ int orc_gemm_f32_blockscaled(const uint8_t* a_codes, const uint8_t* a_scales, fl
       }
       D[m * N + n] = acc * (a_sdec * b_sdec);
     }
+  return 0;
+}
+
+
+// ======================================================================
+// MXFP4, the comparison format (Sec. 2 second and third paragraphs; App. B.4
+// "Remarks on MXFP4 and NVFP4 scale factor"; Sec. 5 for its 32-point rotation).
+//   * blocks of 32 consecutive elements along the copy's contiguous dimension
+//   * one unsigned E8M0 scale per block: a power of two 2^e, stored as e + 127
+//   * the scale is amax_b / 6 rounded UP to the next power of two (App. B.4:
+//     decode scales are rounded up so that nothing saturates); no tensor scale
+//   * elements are E2M1 codes of x / 2^e, same rounding rules as above
+//   * Wgrad operands are rotated with a 32-point transform (Sec. 5)
+// Conventions fixed here: amax_b / 6 is one binary32 division; an all-zero
+// block stores e = -127; e is clamped to [-127, 127]; the 32-point transform
+// is y = H32 (s .* v), butterfly stages h = 1, 2, 4, 8, 16, then one multiply
+// by fl(1/sqrt(32)); its sign vector is all 32 bits of word 0 of the Philox
+// call that gives the 16-point mask; stochastic rounding of the row copy
+// uses the draws above, the col copy draws its own: element (i, j) of the
+// logical tensor uses counter (i / 8, j, 1, 0), word (i % 8) / 2, low half
+// for even i (eight consecutive rows of a column share one call).
+// ======================================================================
+
+namespace {
+
+const float kInvSqrt32 = 0.176776695296636893f;   // nearest binary32 to 1/sqrt(32)
+
+uint32_t rht_sign_mask32(uint64_t seed) {
+  const uint32_t ctr[4] = {0u, 0u, 0u, 0xFFFFFFFFu};
+  const uint32_t key[2] = {static_cast<uint32_t>(seed), static_cast<uint32_t>(seed >> 32)};
+  uint32_t w[4];
+  philox4x32_10(ctr, key, w);
+  return w[0];
+}
+
+void hadamard32(float v[32]) {
+  for (int h = 1; h < 32; h <<= 1)
+    for (int i = 0; i < 32; ++i)
+      if ((i & h) == 0) {
+        const float a = v[i], b = v[i + h];
+        v[i] = a + b;
+        v[i + h] = a - b;
+      }
+  for (int i = 0; i < 32; ++i) v[i] = kInvSqrt32 * v[i];
+}
+
+void rht32_forward(float v[32], uint32_t mask) {
+  for (int i = 0; i < 32; ++i) if ((mask >> i) & 1u) v[i] = -v[i];
+  hadamard32(v);
+}
+
+void rht32_inverse(float y[32], uint32_t mask) {
+  hadamard32(y);
+  for (int i = 0; i < 32; ++i) if ((mask >> i) & 1u) y[i] = -y[i];
+}
+
+// smallest e with 2^e >= s (s >= 0), clamped to the UE8M0 range
+int ue8m0_exponent_round_up(float s) {
+  if (!(s > 0.0f)) return -127;
+  int ex;
+  const float m = std::frexp(s, &ex);        // s = m * 2^ex, 0.5 <= m < 1
+  int e = (m == 0.5f) ? ex - 1 : ex;
+  if (e < -127) e = -127;
+  if (e > 127) e = 127;
+  return e;
+}
+
+uint32_t mx_col_random16(uint64_t seed, uint64_t i, uint64_t j) {
+  const uint32_t ctr[4] = {static_cast<uint32_t>(i >> 3), static_cast<uint32_t>(j), 1u, 0u};
+  const uint32_t key[2] = {static_cast<uint32_t>(seed), static_cast<uint32_t>(seed >> 32)};
+  uint32_t w[4];
+  philox4x32_10(ctr, key, w);
+  const uint32_t e = static_cast<uint32_t>(i & 7u);
+  const uint32_t word = w[e >> 1];
+  return (e & 1u) ? (word >> 16) : (word & 0xFFFFu);
+}
+
+inline double mx_deq_f64(const uint8_t* codes, const uint8_t* scales, int64_t K, int64_t o, int64_t k) {
+  const uint8_t byte = codes[o * (K / 2) + k / 2];
+  const uint32_t c = (k & 1) ? (byte >> 4) : (byte & 15u);
+  return std::ldexp(static_cast<double>(e2m1_decode(c)), static_cast<int>(scales[o * (K / 32) + k / 32]) - 127);
+}
+
+}  // namespace
+
+uint32_t orc_rht_sign_mask32(uint64_t seed) { return rht_sign_mask32(seed); }
+void     orc_rht32_forward(float* v, uint32_t mask) { rht32_forward(v, mask); }
+void     orc_rht32_inverse(float* v, uint32_t mask) { rht32_inverse(v, mask); }
+int      orc_ue8m0_exponent_round_up(float s) { return ue8m0_exponent_round_up(s); }
+uint32_t orc_mx_col_random16(uint64_t seed, uint64_t i, uint64_t j) { return mx_col_random16(seed, i, j); }
+
+// Quantize one copy of a bf16 [rows, cols] tensor to MXFP4.  Arguments as for
+// orc_quantize; scales [outer, inner/32] UE8M0 bytes; amax_out (may be null)
+// receives the largest magnitude seen (rotated space for a rotated copy).
+int orc_mx_quantize(const uint16_t* x, int64_t rows, int64_t cols, int64_t ld, int copy, int rounding,
+                    int use_rht, uint64_t rht_seed, uint64_t sr_seed, uint8_t* codes, uint8_t* scales,
+                    float* amax_out) {
+  if (!x || !codes || !scales) return -1;
+  if (rows < 0 || cols < 0 || ld < cols) return -1;
+  if (copy != 0 && copy != 1) return -1;
+  if ((copy == 0 ? cols : rows) % 32) return -1;
+  const View view{x, ld, copy == 1};
+  const int64_t outer = copy == 1 ? cols : rows;
+  const int64_t inner = copy == 1 ? rows : cols;
+  const int64_t nblk = inner / 32;
+  const uint32_t mask = use_rht ? rht_sign_mask32(rht_seed) : 0u;
+  float amax_all = 0.0f;
+#pragma omp parallel for schedule(static) reduction(max : amax_all)
+  for (int64_t o = 0; o < outer; ++o) {
+    for (int64_t b = 0; b < nblk; ++b) {
+      float w[32];
+      for (int k = 0; k < 32; ++k) w[k] = view.at(o, 32 * b + k);
+      if (use_rht) rht32_forward(w, mask);
+      float amax_b = 0.0f;
+      for (int k = 0; k < 32; ++k) {
+        const float a = std::fabs(w[k]);
+        if (a > amax_b) amax_b = a;
+      }
+      if (amax_b > amax_all) amax_all = amax_b;
+      const int e = ue8m0_exponent_round_up(amax_b / 6.0f);
+      scales[o * nblk + b] = static_cast<uint8_t>(e + 127);
+      const float inv = std::ldexp(1.0f, -e);              // 2^-e, exact (subnormal for e = 127)
+      for (int k = 0; k < 32; k += 2) {
+        uint32_t c[2];
+        for (int t = 0; t < 2; ++t) {
+          const int64_t kk = 32 * b + k + t;
+          const float v = w[k + t] * inv;
+          if (rounding == 0) {
+            c[t] = e2m1_encode_rne(v);
+          } else if (copy == 0) {
+            c[t] = e2m1_encode_sr(v, sr_random16(sr_seed, static_cast<uint64_t>(o), static_cast<uint64_t>(kk)));
+          } else {
+            c[t] = e2m1_encode_sr(v, mx_col_random16(sr_seed, static_cast<uint64_t>(kk), static_cast<uint64_t>(o)));
+          }
+        }
+        codes[o * (inner / 2) + (32 * b + k) / 2] = static_cast<uint8_t>(c[0] | (c[1] << 4));
+      }
+    }
+  }
+  if (amax_out) *amax_out = amax_all;
+  return 0;
+}
+
+int orc_mx_dequantize(const uint8_t* codes, const uint8_t* scales, int64_t outer, int64_t inner, int undo_rht,
+                      uint64_t rht_seed, float* out) {
+  if (!codes || !scales || !out || inner % 32) return -1;
+  const uint32_t mask = undo_rht ? rht_sign_mask32(rht_seed) : 0u;
+#pragma omp parallel for schedule(static)
+  for (int64_t o = 0; o < outer; ++o)
+    for (int64_t b = 0; b < inner / 32; ++b) {
+      const int e = static_cast<int>(scales[o * (inner / 32) + b]) - 127;
+      float g[32];
+      for (int k = 0; k < 32; ++k) {
+        const uint8_t byte = codes[o * (inner / 2) + (32 * b + k) / 2];
+        g[k] = std::ldexp(e2m1_decode((k & 1) ? (byte >> 4) : (byte & 15u)), e);
+      }
+      if (undo_rht) rht32_inverse(g, mask);
+      for (int k = 0; k < 32; ++k) out[o * inner + 32 * b + k] = g[k];
+    }
+  return 0;
+}
+
+// binary64 reference GEMM on MXFP4 operands, whole matrix or listed entries
+int orc_mx_gemm_f64(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* b_codes, const uint8_t* b_scales,
+                    int64_t M, int64_t N, int64_t K, double* D) {
+  if (K % 32) return -1;
+  std::vector<double> A(static_cast<size_t>(M) * K), B(static_cast<size_t>(N) * K);
+#pragma omp parallel for schedule(static)
+  for (int64_t m = 0; m < M; ++m)
+    for (int64_t k = 0; k < K; ++k) A[m * K + k] = mx_deq_f64(a_codes, a_scales, K, m, k);
+#pragma omp parallel for schedule(static)
+  for (int64_t n = 0; n < N; ++n)
+    for (int64_t k = 0; k < K; ++k) B[n * K + k] = mx_deq_f64(b_codes, b_scales, K, n, k);
+#pragma omp parallel for schedule(static)
+  for (int64_t m = 0; m < M; ++m)
+    for (int64_t n = 0; n < N; ++n) {
+      double acc = 0.0;
+      for (int64_t k = 0; k < K; ++k) acc += A[m * K + k] * B[n * K + k];
+      D[m * N + n] = acc;
+    }
+  return 0;
+}
+
+int orc_mx_gemm_f64_entries(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* b_codes,
+                            const uint8_t* b_scales, int64_t K, int64_t count, const int64_t* m_idx,
+                            const int64_t* n_idx, double* out) {
+  if (K % 32) return -1;
+#pragma omp parallel for schedule(static)
+  for (int64_t t = 0; t < count; ++t) {
+    double acc = 0.0;
+    for (int64_t k = 0; k < K; ++k)
+      acc += mx_deq_f64(a_codes, a_scales, K, m_idx[t], k) * mx_deq_f64(b_codes, b_scales, K, n_idx[t], k);
+    out[t] = acc;
+  }
   return 0;
 }
 
