@@ -63,7 +63,13 @@ typedef enum nvfp4_status {
 } nvfp4_status;
 
 enum { NVFP4_LAYOUT_ROW = 1, NVFP4_LAYOUT_COL = 2 };       /* layout mask bits */
-enum { NVFP4_BLOCK_1x16 = 1, NVFP4_BLOCK_16x16 = 16 };     /* block_dim */
+/* block_dim.  NVFP4_BLOCK_MX32 selects the paper's comparison format MXFP4 instead of NVFP4 (Sec. 2, App. B.4,
+ * Sec. 5): blocks of 32 along the copy's contiguous dimension, one UE8M0 byte per block (2^(byte - 127), amax_b / 6
+ * rounded up to a power of two), no tensor-level scale (tensor_scale = {1, 0}), scales [.., ../32] bytes, a 32-point
+ * rotation (all 32 bits of the sign word) when rht_on_col is set, rows and cols multiples of 32, no workspace.  The
+ * col copy draws its own random numbers: element (i, j) uses counter (i / 8, j, 1, 0), word (i % 8) / 2.
+ * nvfp4_gemm on two MXFP4 tensors runs on the chip's block-scaled FP4 matrix instruction (K a multiple of 128). */
+enum { NVFP4_BLOCK_1x16 = 1, NVFP4_BLOCK_16x16 = 16, NVFP4_BLOCK_MX32 = 32 };
 enum { NVFP4_ROUND_RNE = 0, NVFP4_ROUND_SR = 1 };          /* rounding */
 enum { NVFP4_OP_FPROP = 0, NVFP4_OP_DGRAD = 1, NVFP4_OP_WGRAD = 2 };
 /* NVFP4_OUT_F32_ACCUMULATE (nvfp4_gemm only): D <- D + result in FP32, for weight gradients that are

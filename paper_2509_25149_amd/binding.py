@@ -17,7 +17,7 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libnvfp4_hip.so")
 
 LAYOUT_ROW, LAYOUT_COL = 1, 2
-BLOCK_1x16, BLOCK_16x16 = 1, 16
+BLOCK_1x16, BLOCK_16x16, BLOCK_MX32 = 1, 16, 32
 ROUND_RNE, ROUND_SR = 0, 1
 OP_FPROP, OP_DGRAD, OP_WGRAD = 0, 1, 2
 OUT_F32, OUT_BF16, OUT_F32_ACCUMULATE = 0, 1, 2
@@ -123,19 +123,20 @@ class QTensor:
     col_ts: Optional[torch.Tensor] = None
 
 
-def alloc_qtensor(rows: int, cols: int, layout_mask: int, device="cuda") -> QTensor:
-    codes_b, scales_b, _ = quantized_sizes(rows, cols)
+def alloc_qtensor(rows: int, cols: int, layout_mask: int, device="cuda", block_dim: int = BLOCK_1x16) -> QTensor:
+    quantized_sizes(rows, cols)                       # shape check
+    blk = 32 if block_dim == BLOCK_MX32 else 16     # elements per scale byte
     q = QTensor(QTensorStruct(), rows, cols)
     q.desc.rows, q.desc.cols = rows, cols
     if layout_mask & LAYOUT_ROW:
         q.row_codes = torch.empty((rows, cols // 2), dtype=torch.uint8, device=device)
-        q.row_scales = torch.empty((rows, cols // 16), dtype=torch.uint8, device=device)
+        q.row_scales = torch.empty((rows, cols // blk), dtype=torch.uint8, device=device)
         q.row_ts = torch.empty(2, dtype=torch.float32, device=device)
         q.desc.row_codes, q.desc.row_scales = q.row_codes.data_ptr(), q.row_scales.data_ptr()
         q.desc.row_tensor_scale = q.row_ts.data_ptr()
     if layout_mask & LAYOUT_COL:
         q.col_codes = torch.empty((cols, rows // 2), dtype=torch.uint8, device=device)
-        q.col_scales = torch.empty((cols, rows // 16), dtype=torch.uint8, device=device)
+        q.col_scales = torch.empty((cols, rows // blk), dtype=torch.uint8, device=device)
         q.col_ts = torch.empty(2, dtype=torch.float32, device=device)
         q.desc.col_codes, q.desc.col_scales = q.col_codes.data_ptr(), q.col_scales.data_ptr()
         q.desc.col_tensor_scale = q.col_ts.data_ptr()
@@ -160,7 +161,7 @@ def nvfp4_quantize(x: torch.Tensor, layout_mask: int, block_dim: int = BLOCK_1x1
         raise ValueError("x must be a 2-D bf16 CUDA tensor with unit inner stride")
     rows, cols = x.shape
     if out is None:
-        out = alloc_qtensor(rows, cols, layout_mask, x.device)
+        out = alloc_qtensor(rows, cols, layout_mask, x.device, block_dim)
     ws = workspace if workspace is not None else _workspace(x.device, quantized_sizes(rows, cols)[2])
     _check(load_library().nvfp4_quantize(x.data_ptr(), rows, cols, x.stride(0), layout_mask, block_dim, rounding,
                                          int(rht_on_col), rht_seed, sr_seed, ctypes.byref(out.desc),

@@ -29,13 +29,15 @@ bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) %
 
 }  // namespace
 
-uint32_t host_rht_sign_mask(uint64_t seed) {
+uint32_t host_rht_sign_mask32(uint64_t seed) {
   const uint32_t ctr[4] = {0u, 0u, 0u, 0xFFFFFFFFu};
   const uint32_t key[2] = {static_cast<uint32_t>(seed), static_cast<uint32_t>(seed >> 32)};
   uint32_t out[4];
   host_philox4x32_10(ctr, key, out);
-  return out[0] & 0xFFFFu;
+  return out[0];
 }
+
+uint32_t host_rht_sign_mask(uint64_t seed) { return host_rht_sign_mask32(seed) & 0xFFFFu; }
 
 }  // namespace nvfp4
 
@@ -82,17 +84,22 @@ int plan_quantize(const void* x, int64_t rows, int64_t cols, int64_t ld, int lay
                   size_t workspace_bytes, QuantPlan* p) {
   if (!x || !out) return NVFP4_ERR_INVALID_ARG;
   if (layout_mask <= 0 || (layout_mask & ~(NVFP4_LAYOUT_ROW | NVFP4_LAYOUT_COL))) return NVFP4_ERR_INVALID_ARG;
-  if (block_dim != NVFP4_BLOCK_1x16 && block_dim != NVFP4_BLOCK_16x16) return NVFP4_ERR_INVALID_ARG;
+  if (block_dim != NVFP4_BLOCK_1x16 && block_dim != NVFP4_BLOCK_16x16 && block_dim != NVFP4_BLOCK_MX32)
+    return NVFP4_ERR_INVALID_ARG;
   if (rounding != NVFP4_ROUND_RNE && rounding != NVFP4_ROUND_SR) return NVFP4_ERR_INVALID_ARG;
   const bool want_row = layout_mask & NVFP4_LAYOUT_ROW, want_col = layout_mask & NVFP4_LAYOUT_COL;
+  const bool mx = block_dim == NVFP4_BLOCK_MX32;
   if (rht_on_col && (block_dim == NVFP4_BLOCK_16x16 || !want_col)) return NVFP4_ERR_INVALID_ARG;
   if (rows <= 0 || cols <= 0 || rows % 16 || cols % 16 || ld < cols || ld % 8) return NVFP4_ERR_BAD_SHAPE;
+  if (mx && (rows % 32 || cols % 32)) return NVFP4_ERR_BAD_SHAPE;
   if (!aligned(x, 16)) return NVFP4_ERR_INVALID_ARG;
   if (want_row && (!out->row_codes || !out->row_scales || !out->row_tensor_scale)) return NVFP4_ERR_INVALID_ARG;
   if (want_col && (!out->col_codes || !out->col_scales || !out->col_tensor_scale)) return NVFP4_ERR_INVALID_ARG;
   if (want_row && (!aligned(out->row_codes, 16) || !aligned(out->row_scales, 16))) return NVFP4_ERR_INVALID_ARG;
   if (want_col && (!aligned(out->col_codes, 16) || !aligned(out->col_scales, 16))) return NVFP4_ERR_INVALID_ARG;
-  if (!workspace || workspace_bytes < quantize_workspace_bytes(rows, cols) || !aligned(workspace, 16)) return NVFP4_ERR_WORKSPACE;
+  // the MXFP4 mode is a single pass and needs no workspace
+  if (!mx && (!workspace || workspace_bytes < quantize_workspace_bytes(rows, cols) || !aligned(workspace, 16)))
+    return NVFP4_ERR_WORKSPACE;
 
   QuantizeArgs& a = p->a;
   a.x = x;
@@ -104,7 +111,7 @@ int plan_quantize(const void* x, int64_t rows, int64_t cols, int64_t ld, int lay
   a.rht = rht_on_col != 0;
   a.sr = rounding == NVFP4_ROUND_SR;
   a.block2d = block_dim == NVFP4_BLOCK_16x16;
-  a.sign_mask = a.rht ? host_rht_sign_mask(rht_seed) : 0u;
+  a.sign_mask = !a.rht ? 0u : mx ? host_rht_sign_mask32(rht_seed) : host_rht_sign_mask(rht_seed);
   a.key0 = static_cast<uint32_t>(sr_seed);
   a.key1 = static_cast<uint32_t>(sr_seed >> 32);
   a.ws = static_cast<uint32_t*>(workspace);
@@ -135,7 +142,9 @@ int nvfp4_quantize(const void* x, int64_t rows, int64_t cols, int64_t ld, int la
   const int rc = plan_quantize(x, rows, cols, ld, layout_mask, block_dim, rounding, rht_on_col, rht_seed, sr_seed, out,
                                workspace, workspace_bytes, &p);
   if (rc != NVFP4_OK) return rc;
-  if (launch_quantize(p.a, static_cast<hipStream_t>(stream)) != hipSuccess) return NVFP4_ERR_HIP;
+  const hipError_t e = block_dim == NVFP4_BLOCK_MX32 ? launch_quantize_mx(p.a, static_cast<hipStream_t>(stream))
+                                                     : launch_quantize(p.a, static_cast<hipStream_t>(stream));
+  if (e != hipSuccess) return NVFP4_ERR_HIP;
   *out = p.desc;
   return NVFP4_OK;
 }
@@ -187,6 +196,13 @@ static int plan_gemm(const nvfp4_qtensor* a, const nvfp4_qtensor* b, int op, voi
   rc = pick_operand(b, b_col, &g.b, &kb);
   if (rc != NVFP4_OK) return rc;
   if (ka != kb) return NVFP4_ERR_MISMATCH;
+  // Both operands in the same format: NVFP4 (E4M3 scale per 16) or MXFP4 (UE8M0 scale per 32).
+  const bool a_mx = a->block_dim == NVFP4_BLOCK_MX32, b_mx = b->block_dim == NVFP4_BLOCK_MX32;
+  if (a_mx != b_mx) return NVFP4_ERR_MISMATCH;
+  if (a_mx && (ka % 128 || g.a.outer % 32 || g.b.outer % 32)) return NVFP4_ERR_BAD_SHAPE;   // one scaled MFMA is 128 deep
+  if (a_mx && (!aligned(g.a.codes, 16) || !aligned(g.b.codes, 16) || !aligned(g.a.scales, 4) || !aligned(g.b.scales, 4)))
+    return NVFP4_ERR_INVALID_ARG;
+  g.mx = a_mx;
   // Rotated operands only make sense in pairs that rotate the same way (App. C).
   const bool a_rot = a_col && a->col_has_rht, b_rot = b_col && b->col_has_rht;
   if (a_rot != b_rot || (a_rot && a->rht_seed != b->rht_seed)) return NVFP4_ERR_MISMATCH;
@@ -208,7 +224,8 @@ int nvfp4_gemm(const nvfp4_qtensor* a, const nvfp4_qtensor* b, int op, void* d, 
   GemmArgs g;
   const int rc = plan_gemm(a, b, op, d, out_dtype, ldd, workspace, workspace_bytes, &g);
   if (rc != NVFP4_OK) return rc;
-  return launch_gemm(g, static_cast<hipStream_t>(stream)) == hipSuccess ? NVFP4_OK : NVFP4_ERR_HIP;
+  const hipError_t e = g.mx ? launch_gemm_mx(g, static_cast<hipStream_t>(stream)) : launch_gemm(g, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? NVFP4_OK : NVFP4_ERR_HIP;
 }
 
 // ---------------------------------------------------------------- one linear layer (Sec. 4.1, Fig. 3)
@@ -275,14 +292,16 @@ int nvfp4_dequantize(const nvfp4_qtensor* q, int which_copy, int undo_rht, void*
   int rc = pick_operand(q, which_copy == NVFP4_COPY_COL, &d.q, &d.K);
   if (rc != NVFP4_OK) return rc;
   if (undo_rht && !(which_copy == NVFP4_COPY_COL && q->col_has_rht)) return NVFP4_ERR_MISMATCH;
-  if (d.K <= 0 || d.K % 16 || ld_out < d.K || ld_out % 8) return NVFP4_ERR_BAD_SHAPE;
-  if (!aligned(out, 16) || !aligned(d.q.codes, 8)) return NVFP4_ERR_INVALID_ARG;
+  const bool mx = q->block_dim == NVFP4_BLOCK_MX32;
+  if (d.K <= 0 || d.K % (mx ? 32 : 16) || ld_out < d.K || ld_out % 8) return NVFP4_ERR_BAD_SHAPE;
+  if (!aligned(out, 16) || !aligned(d.q.codes, mx ? 16 : 8)) return NVFP4_ERR_INVALID_ARG;
   d.undo_rht = undo_rht != 0;
-  d.sign_mask = d.undo_rht ? host_rht_sign_mask(q->rht_seed) : 0u;
+  d.sign_mask = !d.undo_rht ? 0u : mx ? host_rht_sign_mask32(q->rht_seed) : host_rht_sign_mask(q->rht_seed);
   d.out = out;
   d.ld_out = ld_out;
   d.out_bf16 = out_dtype == NVFP4_OUT_BF16;
-  return launch_dequantize(d, static_cast<hipStream_t>(stream)) == hipSuccess ? NVFP4_OK : NVFP4_ERR_HIP;
+  const hipError_t e = mx ? launch_dequantize_mx(d, static_cast<hipStream_t>(stream)) : launch_dequantize(d, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? NVFP4_OK : NVFP4_ERR_HIP;
 }
 
 int nvfp4_selftest_conversions(uint64_t* mismatches, nvfp4_stream_t stream) {

@@ -62,7 +62,63 @@ __global__ __launch_bounds__(256) void dequantize_kernel(Operand q, int64_t K, b
   }
 }
 
+// MXFP4: one thread per 32-block, value(code) * 2^e (Sec. 2), optional inverse 32-point rotation.
+template <bool kBf16Out>
+__global__ __launch_bounds__(256) void dequantize_mx_kernel(Operand q, int64_t K, bool undo_rht, uint32_t sign_mask,
+                                                            void* __restrict__ outv, int64_t ld_out) {
+  const int64_t nblk = K / 32;
+  const int64_t idx = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+  if (idx >= q.outer * nblk) return;
+  const int64_t o = idx / nblk, b = idx % nblk;
+  const uint4 c = *reinterpret_cast<const uint4*>(q.codes + o * (K / 2) + b * 16);
+  const float sd = ue8m0_decode(q.scales[o * nblk + b]);
+  const uint32_t cw[4] = {c.x, c.y, c.z, c.w};
+  float v[32];
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+    decode_pair_f32<0>(cw[t], v + 8 * t + 0);
+    decode_pair_f32<1>(cw[t], v + 8 * t + 2);
+    decode_pair_f32<2>(cw[t], v + 8 * t + 4);
+    decode_pair_f32<3>(cw[t], v + 8 * t + 6);
+  }
+#pragma unroll
+  for (int k = 0; k < 32; ++k) v[k] = v[k] * sd;
+  if (undo_rht) rht32_inverse(v, sign_mask);
+  if (kBf16Out) {
+    uint4* dst = reinterpret_cast<uint4*>(static_cast<uint16_t*>(outv) + o * ld_out + b * 32);
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      uint32_t w[4];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) w[k] = f32_to_bf16(v[8 * t + 2 * k]) | (f32_to_bf16(v[8 * t + 2 * k + 1]) << 16);
+      dst[t] = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+  } else {
+    float4v* dst = reinterpret_cast<float4v*>(static_cast<float*>(outv) + o * ld_out + b * 32);
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+      float4v f;
+      f[0] = v[4 * t];
+      f[1] = v[4 * t + 1];
+      f[2] = v[4 * t + 2];
+      f[3] = v[4 * t + 3];
+      dst[t] = f;
+    }
+  }
+}
+
 }  // namespace
+
+hipError_t launch_dequantize_mx(const DequantArgs& d, hipStream_t s) {
+  const int64_t total = d.q.outer * (d.K / 32);
+  if (total == 0) return hipSuccess;
+  const dim3 grid(static_cast<unsigned>((total + 255) / 256));
+  if (d.out_bf16)
+    hipLaunchKernelGGL(dequantize_mx_kernel<true>, grid, dim3(256), 0, s, d.q, d.K, d.undo_rht, d.sign_mask, d.out, d.ld_out);
+  else
+    hipLaunchKernelGGL(dequantize_mx_kernel<false>, grid, dim3(256), 0, s, d.q, d.K, d.undo_rht, d.sign_mask, d.out, d.ld_out);
+  return hipGetLastError();
+}
 
 hipError_t launch_dequantize(const DequantArgs& d, hipStream_t s) {
   const int64_t total = d.q.outer * (d.K / 16);

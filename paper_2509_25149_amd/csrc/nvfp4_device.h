@@ -176,4 +176,43 @@ __device__ __forceinline__ float wave_max(float v) {
   return v;
 }
 
+// 32-point transform of the MXFP4 mode (Sec. 5: rotation size 32 to match the block size; App. C):
+// y = H32 (s .* v), butterfly stages h = 1, 2, 4, 8, 16, then one multiply by fl(1/sqrt(32)).
+__device__ __forceinline__ void hadamard32(float v[32]) {
+#pragma unroll
+  for (int h = 1; h < 32; h <<= 1) {
+#pragma unroll
+    for (int i = 0; i < 32; ++i) {
+      if ((i & h) == 0) {
+        const float a = v[i], b = v[i + h];
+        v[i] = a + b;
+        v[i + h] = a - b;
+      }
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < 32; ++i) v[i] = 0.176776695296636893f * v[i];
+}
+
+__device__ __forceinline__ void flip_signs32(float v[32], uint32_t sign_mask) {
+#pragma unroll
+  for (int i = 0; i < 32; ++i) v[i] = __uint_as_float(__float_as_uint(v[i]) ^ (((sign_mask >> i) & 1u) << 31));
+}
+
+__device__ __forceinline__ void rht32(float v[32], uint32_t sign_mask) {
+  flip_signs32(v, sign_mask);
+  hadamard32(v);
+}
+
+// H32 is symmetric and orthogonal: x = s .* (H32 y)
+__device__ __forceinline__ void rht32_inverse(float y[32], uint32_t sign_mask) {
+  hadamard32(y);
+  flip_signs32(y, sign_mask);
+}
+
+// 2^(byte - 127) for a UE8M0 scale byte (Sec. 2), exact (byte 0 is the subnormal 2^-127)
+__device__ __forceinline__ float ue8m0_decode(uint32_t byte) {
+  return __uint_as_float(byte == 0u ? 0x00400000u : byte << 23);
+}
+
 }  // namespace nvfp4

@@ -18,6 +18,8 @@ struct QuantizeArgs {
   float* col_ts;
 };
 hipError_t launch_quantize(const QuantizeArgs& a, hipStream_t s);
+// MXFP4 mode (1x32 blocks, UE8M0 scales, one pass, no workspace); sign_mask holds 32 bits
+hipError_t launch_quantize_mx(const QuantizeArgs& a, hipStream_t s);
 size_t quantize_workspace_bytes(int64_t rows, int64_t cols);
 
 // One K-contiguous operand: codes [outer, K/2], scales [outer, K/16], ts = {s_dec, amax}.
@@ -34,6 +36,7 @@ struct GemmArgs {
   int64_t ldd;
   bool out_bf16;
   bool accumulate;   // FP32 output only: D <- D + result
+  bool mx = false;   // operands are MXFP4 (UE8M0 scale per 32) instead of NVFP4
   void* workspace;        // optional: room for both operands decoded to FP16
   size_t workspace_bytes;
 };
@@ -52,10 +55,15 @@ struct DequantArgs {
   bool out_bf16;
 };
 hipError_t launch_dequantize(const DequantArgs& d, hipStream_t s);
+hipError_t launch_dequantize_mx(const DequantArgs& d, hipStream_t s);   // scales are UE8M0 per 32
 
 hipError_t run_selftest(uint64_t* mismatches_dev, hipStream_t s);
 
-// Host Philox4x32-10, used only to derive the 16-bit sign diagonal from a seed.
+// Host Philox4x32-10, used only to derive the sign diagonal from a seed (16 bits, or 32 for the MXFP4 mode).
 uint32_t host_rht_sign_mask(uint64_t seed);
+uint32_t host_rht_sign_mask32(uint64_t seed);
+
+// MXFP4 GEMM on the scaled FP4 MFMA (scales per 32 are UE8M0); K must be a multiple of 128.
+hipError_t launch_gemm_mx(const GemmArgs& g, hipStream_t s);
 
 }  // namespace nvfp4
