@@ -30,6 +30,7 @@ TOKENS, D_MODEL, D_FFN = 8192, 5120, 20480
 PEAK_HBM_GBPS = 8000.0
 PEAK_MFMA_F16_TFLOPS = 2500.0
 PEAK_MFMA_F8_TFLOPS = 5000.0
+PEAK_MFMA_F4_TFLOPS = 10100.0
 
 # HBM-side bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by the 1 GiB calibration
 # copy below (profiles/bench_linear_layer_12B_hbm_traffic_pmc.txt).  They cannot be measured from inside
@@ -91,12 +92,55 @@ def cpu_baseline(torch, nv, x, w):
     }
 
 
+def mxfp4_comparison(torch, nv, x, w, dy, iters: int = 5):
+    """The same layer step in the paper's comparison format MXFP4 (Sec. 2, Sec. 5), which this chip's block-scaled
+    FP4 matrix instruction consumes natively: no decode pass, no workspace.  Outside the timed region of `value`."""
+    RC = nv.LAYOUT_ROW | nv.LAYOUT_COL
+    qx = nv.alloc_qtensor(TOKENS, D_MODEL, RC, block_dim=nv.BLOCK_MX32)
+    qw = nv.alloc_qtensor(D_MODEL, D_FFN, RC, block_dim=nv.BLOCK_MX32)
+    qdy = nv.alloc_qtensor(TOKENS, D_FFN, RC, block_dim=nv.BLOCK_MX32)
+    y = torch.empty((TOKENS, D_FFN), dtype=torch.bfloat16, device="cuda")
+    dx = torch.empty((TOKENS, D_MODEL), dtype=torch.bfloat16, device="cuda")
+    dw = torch.empty((D_MODEL, D_FFN), dtype=torch.float32, device="cuda")
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    q_ms, g_ms, total = 0.0, 0.0, 0.0
+    for it in range(iters + 1):
+        m = [ev() for _ in range(7)]
+        m[0].record()
+        nv.nvfp4_quantize(x, RC, nv.BLOCK_MX32, nv.ROUND_RNE, True, 2025, 0, out=qx)
+        m[1].record()
+        nv.nvfp4_quantize(w, RC, nv.BLOCK_MX32, nv.ROUND_RNE, False, 0, 0, out=qw)
+        m[2].record()
+        nv.nvfp4_gemm(qx, qw, nv.OP_FPROP, nv.OUT_BF16, out=y)
+        m[3].record()
+        nv.nvfp4_quantize(dy, RC, nv.BLOCK_MX32, nv.ROUND_SR, True, 2025, 77 + it, out=qdy)
+        m[4].record()
+        nv.nvfp4_gemm(qdy, qw, nv.OP_DGRAD, nv.OUT_BF16, out=dx)
+        m[5].record()
+        nv.nvfp4_gemm(qx, qdy, nv.OP_WGRAD, nv.OUT_F32, out=dw)
+        m[6].record()
+        torch.cuda.synchronize()
+        if it == 0:
+            continue                                  # warm-up
+        q_ms += m[0].elapsed_time(m[2]) + m[3].elapsed_time(m[4])
+        g_ms += m[2].elapsed_time(m[3]) + m[4].elapsed_time(m[6])
+        total += m[0].elapsed_time(m[6])
+    flops = 2.0 * TOKENS * D_MODEL * D_FFN
+    gemm_tflops = 3 * flops / (g_ms / iters * 1e-3) / 1e12
+    return {"note": "comparison format, not part of `value`: quantize X, W, dY to MXFP4 (1x32 blocks, UE8M0 scales, one pass, "
+                    "32-point RHT, SR on dY) and the three GEMMs on the block-scaled FP4 MFMA",
+            "ms_per_step": total / iters, "TFLOPs_step": 3 * flops / (total / iters * 1e-3) / 1e12,
+            "gemm_TFLOPs_per_launch_avg": gemm_tflops, "gemm_frac_of_fp4_mfma_peak": gemm_tflops / PEAK_MFMA_F4_TFLOPS,
+            "quantize_ms_per_step": q_ms / iters}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-mxfp4", action="store_true", help="skip the MXFP4 comparison block")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1",
@@ -213,6 +257,8 @@ def main() -> int:
                               "bytes_algorithmic_one_pass": sum(q_bytes),
                               "achieved_two_pass_accounting": (sum(q_bytes) + 2.0 * (n_x + n_w + n_dy)) / (sum(q_avg) * 1e-3) / 1e9},
     }
+    if not args.no_mxfp4:
+        out["mxfp4_comparison"] = mxfp4_comparison(torch, nv, x, w, dy)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(torch, nv, x, w)
     print(json.dumps(out))

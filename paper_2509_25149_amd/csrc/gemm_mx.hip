@@ -12,8 +12,8 @@
 // in register i of lane l, rows taken from the first operand.
 //
 // 256 x 256 outputs per workgroup, K step 128 (one instruction deep), 512 threads
-// = 8 wavefronts (2 x 4) of 128 x 64.  LDS holds two stages of (A codes, B codes,
-// A scales, B scales) = 34 KiB each, filled by direct global->LDS loads: a code
+// = 8 wavefronts (2 x 4) of 128 x 64.  LDS holds four stages of (A codes, B codes,
+// A scales, B scales) = 34 KiB each (two K steps per barrier), filled by direct global->LDS loads: a code
 // row of a stage is 64 bytes, so 16 consecutive tile rows are 1 KiB of LDS and a
 // fragment read (16 rows x 4 blocks x 16 bytes) is one contiguous KiB.
 #include "nvfp4_internal.h"
@@ -122,15 +122,9 @@ __global__ __launch_bounds__(kThreads) void gemm_mx_kernel(Operand A, Operand B,
 #pragma unroll
       for (int r = 0; r < 4; ++r) acc[i][j][r] = 0.0f;
 
-  const int KT = static_cast<int>(K / TK);
-  issue(0, 0);
-  __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): the direct loads have landed in LDS
-  __syncthreads();
-
-  for (int kt = 0; kt < KT; ++kt) {
-    const int stage = kt & 1;
-    const char* cur = lds + stage * kStageBytes;
-    if (kt + 1 < KT) issue(kt + 1, stage ^ 1);
+  // Two K steps per barrier: LDS holds two buffers of two stages each (4 x 34 KiB); the loads of
+  // the next pair of steps are in flight while this pair is multiplied.
+  auto multiply = [&](const char* cur) {
     const char* a_codes = cur;
     const char* b_codes = cur + kCodeBytes;
     const uint8_t* a_scales = reinterpret_cast<const uint8_t*>(cur + 2 * kCodeBytes);
@@ -160,6 +154,20 @@ __global__ __launch_bounds__(kThreads) void gemm_mx_kernel(Operand A, Operand B,
           acc[h * 4 + i][j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(fb[j], fa[i], acc[h * 4 + i][j], 4, 4, 0,
                                                                                sb[j], 0, sa[i]);
     }
+  };
+
+  const int KT = static_cast<int>(K / TK);
+  issue(0, 0);
+  if (KT > 1) issue(1, 1);
+  __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): the direct loads have landed in LDS
+  __syncthreads();
+
+  for (int kt = 0; kt < KT; kt += 2) {
+    const int buf = (kt >> 1) & 1;
+    if (kt + 2 < KT) issue(kt + 2, (buf ^ 1) * 2);
+    if (kt + 3 < KT) issue(kt + 3, (buf ^ 1) * 2 + 1);
+    multiply(lds + (buf * 2) * kStageBytes);
+    if (kt + 1 < KT) multiply(lds + (buf * 2 + 1) * kStageBytes);
     __builtin_amdgcn_s_waitcnt(0x0f70);
     __syncthreads();
   }
@@ -199,18 +207,18 @@ hipError_t launch_gemm_mx(const GemmArgs& g, hipStream_t s) {
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mx_kernel<true>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, 2 * kStageBytes);
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, 4 * kStageBytes);
     if (e == hipSuccess)
       e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mx_kernel<false>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, 2 * kStageBytes);
+                              hipFuncAttributeMaxDynamicSharedMemorySize, 4 * kStageBytes);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
   if (g.out_bf16)
-    hipLaunchKernelGGL(gemm_mx_kernel<true>, grid, dim3(kThreads), 2 * kStageBytes, s, g.a, g.b, g.K, g.d, g.ldd,
+    hipLaunchKernelGGL(gemm_mx_kernel<true>, grid, dim3(kThreads), 4 * kStageBytes, s, g.a, g.b, g.K, g.d, g.ldd,
                        g.accumulate, tiles_m, tiles_n);
   else
-    hipLaunchKernelGGL(gemm_mx_kernel<false>, grid, dim3(kThreads), 2 * kStageBytes, s, g.a, g.b, g.K, g.d, g.ldd,
+    hipLaunchKernelGGL(gemm_mx_kernel<false>, grid, dim3(kThreads), 4 * kStageBytes, s, g.a, g.b, g.K, g.d, g.ldd,
                        g.accumulate, tiles_m, tiles_n);
   return hipGetLastError();
 }

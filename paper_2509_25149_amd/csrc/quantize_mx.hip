@@ -127,16 +127,11 @@ __global__ __launch_bounds__(kThreads) void quantize_mx_kernel(const uint16_t* _
   }
 
   if (kCol) {
-#pragma unroll 1
+#pragma unroll
     for (int c = 0; c < 8; ++c) {
       float w[32];
 #pragma unroll
-      for (int r = 0; r < 32; ++r) {
-        const uint4 q = raw[r];
-        // dynamic column index: select by comparison chains on wave-uniform c (no register indexing)
-        const uint32_t word = (c < 2) ? q.x : (c < 4) ? q.y : (c < 6) ? q.z : q.w;
-        w[r] = (c & 1) ? bf16_hi(word) : bf16_lo(word);
-      }
+      for (int r = 0; r < 32; ++r) w[r] = elem(raw[r], c);
       if (kRht) rht32(w, sign_mask);
       float m = 0.0f;
 #pragma unroll

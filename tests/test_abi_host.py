@@ -159,3 +159,33 @@ def test_linear_layer_calls_reject_before_enqueueing(lib):
     qx.col_has_rht = 0
     assert bwd(fake, 32, 48, 48, ctypes.byref(qx), ctypes.byref(qw), 0, ctypes.byref(qdy), fake, 1, 64, fake, 48, 1, *ok_ws) == -3  # no rotated copy kept
     assert qdy.layout_mask == 0
+
+
+def test_mxfp4_mode_argument_checks(lib):
+    """block_dim 32 = MXFP4 (Sec. 2 / App. B.4): whole 32-blocks in both directions, no workspace needed, GEMM needs
+    two MXFP4 operands and K a multiple of 128.  All rejected on the host, before anything is enqueued."""
+    fake = 0x10000
+    q = nv.QTensorStruct()
+    q.row_codes = q.row_scales = q.row_tensor_scale = q.col_codes = q.col_scales = q.col_tensor_scale = fake
+    qz = lambda rows, cols, ld: lib.nvfp4_quantize(fake, rows, cols, ld, 3, 32, 0, 0, 0, 0, ctypes.byref(q), None, 0, None)
+    assert qz(48, 64, 64) == -2 and qz(64, 48, 48) == -2          # 16-multiples are not enough
+    assert lib.nvfp4_quantize(fake, 64, 64, 64, 3, 33, 0, 0, 0, 0, ctypes.byref(q), None, 0, None) == -1
+    a, b = nv.QTensorStruct(), nv.QTensorStruct()
+    for t in (a, b):
+        t.row_codes = t.row_scales = t.row_tensor_scale = fake
+        t.layout_mask, t.block_dim = 1, 32
+    a.rows, a.cols, b.rows, b.cols = 64, 256, 32, 256
+    D = fake
+    b.block_dim = 1
+    assert lib.nvfp4_gemm(ctypes.byref(a), ctypes.byref(b), 1, D, 0, 32, None, 0, None) == -4      # MXFP4 x NVFP4
+    b.block_dim = 32
+    a.cols = b.cols = 192
+    assert lib.nvfp4_gemm(ctypes.byref(a), ctypes.byref(b), 1, D, 0, 32, None, 0, None) == -2      # K % 128
+    a.cols = b.cols = 256
+    a.rows = 48
+    assert lib.nvfp4_gemm(ctypes.byref(a), ctypes.byref(b), 1, D, 0, 32, None, 0, None) == -2      # M % 32
+    a.rows = 64
+    a.row_scales = fake + 2
+    assert lib.nvfp4_gemm(ctypes.byref(a), ctypes.byref(b), 1, D, 0, 32, None, 0, None) == -1      # scale rows are read as dwords
+    out = fake
+    assert lib.nvfp4_dequantize(ctypes.byref(b), 0, 0, out, 0, 128, None) == -2                    # ld_out < K
