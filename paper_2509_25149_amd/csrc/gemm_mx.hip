@@ -34,22 +34,16 @@ typedef int int8v __attribute__((ext_vector_type(8)));
 typedef __attribute__((address_space(3))) void* lds_ptr;
 
 // 64 lanes x 16 (or 4) bytes from global memory straight into consecutive LDS at the wave-uniform
-// address lds_dst.  The builtin only exists in the device pass.
-__device__ __forceinline__ void load16_to_lds(const uint8_t* src, char* lds_dst) {
-#if defined(__HIP_DEVICE_COMPILE__)
-  __builtin_amdgcn_global_load_lds(src, (lds_ptr)lds_dst, 16, 0, 0);
-#else
-  (void)src;
-  (void)lds_dst;
-#endif
+// LDS byte offset lds_off (global_load_lds_*; M0 carries the LDS address).  Inline assembly on
+// purpose: for the builtin form the compiler makes every later LDS read wait for all direct loads
+// in flight (it cannot tell the stages apart), which serialises the prefetch of the next stages
+// with the reads of the current one.  The loop keeps them apart itself: s_waitcnt vmcnt(0) and a
+// barrier stand between a stage's loads and its first read.
+__device__ __forceinline__ void load16_to_lds(const uint8_t* src, uint32_t lds_off) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_off), "v"(src) : "memory", "m0");
 }
-__device__ __forceinline__ void load4_to_lds(const uint8_t* src, char* lds_dst) {
-#if defined(__HIP_DEVICE_COMPILE__)
-  __builtin_amdgcn_global_load_lds(src, (lds_ptr)lds_dst, 4, 0, 0);
-#else
-  (void)src;
-  (void)lds_dst;
-#endif
+__device__ __forceinline__ void load4_to_lds(const uint8_t* src, uint32_t lds_off) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, off" : : "s"(lds_off), "v"(src) : "memory", "m0");
 }
 
 // One operand fragment: the low four dwords are the 32 codes of the lane's block; the
@@ -104,8 +98,9 @@ __global__ __launch_bounds__(kThreads) void gemm_mx_kernel(Operand A, Operand B,
                                : B.scales + min<int64_t>(n0 + srow, B.outer - 1) * scale_ld;
   const int s_off = 2 * kCodeBytes + (wave < 4 ? 0 : kScaleBytes) + (wave & 3) * 256;
 
+  const uint32_t lds_base = static_cast<uint32_t>(reinterpret_cast<uintptr_t>((lds_ptr)lds));
   auto issue = [&](int kt, int stage) {
-    char* base = lds + stage * kStageBytes;
+    const uint32_t base = __builtin_amdgcn_readfirstlane(lds_base + stage * kStageBytes);
 #pragma unroll
     for (int q = 0; q < 2; ++q) {
       load16_to_lds(ga[q] + static_cast<int64_t>(kt) * kCodeRowBytes, base + (wave * 2 + q) * 1024);
@@ -122,54 +117,89 @@ __global__ __launch_bounds__(kThreads) void gemm_mx_kernel(Operand A, Operand B,
 #pragma unroll
       for (int r = 0; r < 4; ++r) acc[i][j][r] = 0.0f;
 
-  // Two K steps per barrier: LDS holds two buffers of two stages each (4 x 34 KiB); the loads of
-  // the next pair of steps are in flight while this pair is multiplied.
-  auto multiply = [&](const char* cur) {
-    const char* a_codes = cur;
-    const char* b_codes = cur + kCodeBytes;
-    const uint8_t* a_scales = reinterpret_cast<const uint8_t*>(cur + 2 * kCodeBytes);
-    const uint8_t* b_scales = a_scales + kScaleBytes;
-    int8v fb[4];
-    int sb[4];
+  // Fragment groups: a stage is two groups of (4 A fragments x 4 B fragments) = 16 MFMAs; the
+  // fragments of the next group are requested from LDS before the MFMAs of the current one start.
+  struct AFr {
+    int8v f[4];
+    int s[4];
+  };
+  struct BFr {
+    int8v f[4];
+    int s[4];
+  };
+  auto load_a = [&](AFr& a, const char* cur, int h) {
+    const uint8_t* sc = reinterpret_cast<const uint8_t*>(cur + 2 * kCodeBytes);
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      fb[j] = load_frag(b_codes, brow + j * 16, kb);
-      sb[j] = b_scales[(brow + j * 16) * 4 + kb];
-    }
-#pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      int8v fa[4];
-      int sa[4];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        fa[i] = load_frag(a_codes, arow + (h * 4 + i) * 16, kb);
-        sa[i] = a_scales[(arow + (h * 4 + i) * 16) * 4 + kb];
-      }
-      // The instruction's first operand supplies the rows of its result: passing B first leaves a
-      // lane with 4 consecutive n of one m, which makes the output stores 64/128-bit.
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-          acc[h * 4 + i][j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(fb[j], fa[i], acc[h * 4 + i][j], 4, 4, 0,
-                                                                               sb[j], 0, sa[i]);
+    for (int i = 0; i < 4; ++i) {
+      a.f[i] = load_frag(cur, arow + (h * 4 + i) * 16, kb);
+      a.s[i] = sc[(arow + (h * 4 + i) * 16) * 4 + kb];
     }
   };
+  auto load_b = [&](BFr& b, const char* cur) {
+    const uint8_t* sc = reinterpret_cast<const uint8_t*>(cur + 2 * kCodeBytes + kScaleBytes);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      b.f[j] = load_frag(cur + kCodeBytes, brow + j * 16, kb);
+      b.s[j] = sc[(brow + j * 16) * 4 + kb];
+    }
+  };
+  // The instruction's first operand supplies the rows of its result: passing B first leaves a lane
+  // with 4 consecutive n of one m, which makes the output stores 64/128-bit.
+  auto mma = [&](const AFr& a, const BFr& b, int h) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        acc[h * 4 + i][j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(b.f[j], a.f[i], acc[h * 4 + i][j], 4, 4, 0,
+                                                                             b.s[j], 0, a.s[i]);
+  };
 
+  // Two K steps per barrier: LDS holds two buffers of two stages each (4 x 34 KiB); the loads of
+  // the next pair of steps are in flight while this pair is multiplied.
   const int KT = static_cast<int>(K / TK);
   issue(0, 0);
   if (KT > 1) issue(1, 1);
   __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): the direct loads have landed in LDS
   __syncthreads();
 
-  for (int kt = 0; kt < KT; kt += 2) {
+  int kt = 0;
+  for (; kt + 1 < KT; kt += 2) {
     const int buf = (kt >> 1) & 1;
     if (kt + 2 < KT) issue(kt + 2, (buf ^ 1) * 2);
     if (kt + 3 < KT) issue(kt + 3, (buf ^ 1) * 2 + 1);
-    multiply(lds + (buf * 2) * kStageBytes);
-    if (kt + 1 < KT) multiply(lds + (buf * 2 + 1) * kStageBytes);
+    const char* s0 = lds + (buf * 2) * kStageBytes;
+    const char* s1 = s0 + kStageBytes;
+    AFr a0, a1;
+    BFr b0, b1;
+    load_b(b0, s0);
+    load_a(a0, s0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    load_a(a1, s0, 1);
+    __builtin_amdgcn_sched_barrier(0);
+    mma(a0, b0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    load_b(b1, s1);
+    load_a(a0, s1, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    mma(a1, b0, 1);
+    __builtin_amdgcn_sched_barrier(0);
+    load_a(a1, s1, 1);
+    __builtin_amdgcn_sched_barrier(0);
+    mma(a0, b1, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    mma(a1, b1, 1);
     __builtin_amdgcn_s_waitcnt(0x0f70);
     __syncthreads();
+  }
+  if (kt < KT) {   // odd number of K steps: the last one sits alone in its buffer's first stage
+    const char* s0 = lds + (((kt >> 1) & 1) * 2) * kStageBytes;
+    AFr a0, a1;
+    BFr b0;
+    load_b(b0, s0);
+    load_a(a0, s0, 0);
+    load_a(a1, s0, 1);
+    mma(a0, b0, 0);
+    mma(a1, b0, 1);
   }
 
   const float out_scale = A.ts[0] * B.ts[0];   // both are 1 for MXFP4 (no tensor-level scale)
