@@ -295,3 +295,44 @@ def test_linear_layer_calls_equal_the_call_sequence():
     with pytest.raises(nv.NVFP4Error) as e:
         nv.nvfp4_linear_backward(to_dev(dyb), qx3, qw, dw, ws)
     assert e.value.status == -3
+
+
+def test_layer_step_replays_from_a_hip_graph():
+    """A whole layer step (quantize + three GEMMs through the per-layer entry points, caller-owned buffers only) is
+    captured into a HIP graph and replayed with eager work in between; every replay must reproduce the eager
+    result bit for bit.  Shapes with a split-K last round (tickets are zeroed by a kernel, not by a memset)."""
+    tokens, d_in, d_out = 4352, 1024, 4096          # Fprop: 17 x 16 = 272 tiles -> the last 16 are split along K
+    wb = synth.normal(d_in, d_out, 0.02, 951)
+    xb = synth.normal_with_outliers(tokens, d_in, 1.0, 952)
+    dyb = synth.student_t3(tokens, d_out, 1e-3, 953)
+    x, dy = to_dev(xb), to_dev(dyb)
+    qw = nv.nvfp4_quantize(to_dev(wb), nv.LAYOUT_ROW | nv.LAYOUT_COL, nv.BLOCK_16x16)
+    ws = torch.empty(nv.linear_workspace_bytes(tokens, d_in, d_out), dtype=torch.uint8, device="cuda")
+    RC = nv.LAYOUT_ROW | nv.LAYOUT_COL
+    qx, qdy = nv.alloc_qtensor(tokens, d_in, RC), nv.alloc_qtensor(tokens, d_out, RC)
+    y = torch.empty((tokens, d_out), dtype=torch.bfloat16, device="cuda")
+    dx = torch.empty((tokens, d_in), dtype=torch.bfloat16, device="cuda")
+    dw = torch.zeros((d_in, d_out), dtype=torch.float32, device="cuda")
+
+    def step():
+        nv.nvfp4_linear_forward(x, qw, ws, True, 7, nv.OUT_BF16, qx=qx, y=y)
+        nv.nvfp4_linear_backward(dy, qx, qw, dw, ws, False, 99, nv.OUT_BF16, qdy=qdy, dx=dx)
+
+    step()                                           # eager: also sets the kernels' launch attributes
+    torch.cuda.synchronize()
+    want = [t.clone() for t in (y, dx, dw, qx.col_codes, qdy.row_codes, qdy.col_scales)]
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    for rep in range(3):
+        for t in (y, dx, dw):
+            t.fill_(float(rep + 1))                  # eager work between the replays; stale outputs must be overwritten
+        ws.random_(0, 255)                           # and the scratch contents must not matter
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = (y, dx, dw, qx.col_codes, qdy.row_codes, qdy.col_scales)
+        for g, w_ in zip(got, want):
+            assert torch.equal(g, w_), f"replay {rep} differs from the eager result"
