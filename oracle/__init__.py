@@ -63,6 +63,12 @@ def lib() -> ctypes.CDLL:
         L.orc_rht16_forward.argtypes = [vp, u32]
         L.orc_rht16_inverse.restype = None
         L.orc_rht16_inverse.argtypes = [vp, u32]
+        L.orc_rht_signs.restype = ctypes.c_int
+        L.orc_rht_signs.argtypes = [u64, ctypes.c_int, vp]
+        L.orc_rht_forward_d.restype = ctypes.c_int
+        L.orc_rht_forward_d.argtypes = [vp, ctypes.c_int, vp]
+        L.orc_rht_inverse_d.restype = ctypes.c_int
+        L.orc_rht_inverse_d.argtypes = [vp, ctypes.c_int, vp]
         L.orc_num_threads.restype = ctypes.c_int
         L.orc_quantize.restype = ctypes.c_int
         L.orc_quantize.argtypes = [vp, i64, i64, i64, ctypes.c_int, ctypes.c_int, ctypes.c_int,
@@ -159,6 +165,32 @@ def rht16_inverse(v, mask: int) -> np.ndarray:
     return a
 
 
+def rht_signs(seed: int, d: int) -> np.ndarray:
+    """1 where the sign diagonal of the d-point rotation negates (d in 2, 4, 16, 32, 128)."""
+    neg = np.zeros(d, dtype=np.uint8)
+    if lib().orc_rht_signs(seed, d, _p(neg)) != 0:
+        raise ValueError(f"no rotation of size {d}")
+    return neg
+
+
+def rht_forward(v, negate: np.ndarray) -> np.ndarray:
+    a = np.ascontiguousarray(v, dtype=np.float32).copy()
+    neg = np.ascontiguousarray(negate, dtype=np.uint8)
+    assert a.size == neg.size
+    if lib().orc_rht_forward_d(_p(a), a.size, _p(neg)) != 0:
+        raise ValueError(f"no rotation of size {a.size}")
+    return a
+
+
+def rht_inverse(v, negate: np.ndarray) -> np.ndarray:
+    a = np.ascontiguousarray(v, dtype=np.float32).copy()
+    neg = np.ascontiguousarray(negate, dtype=np.uint8)
+    assert a.size == neg.size
+    if lib().orc_rht_inverse_d(_p(a), a.size, _p(neg)) != 0:
+        raise ValueError(f"no rotation of size {a.size}")
+    return a
+
+
 def num_threads() -> int:
     return int(lib().orc_num_threads())
 
@@ -175,25 +207,25 @@ class QCopy:
 
 
 def quantize(x_bf16_bits: np.ndarray, copy: int, block_dim: int = BLOCK_1x16, rounding: int = RNE,
-             use_rht: bool = False, rht_seed: int = 0, sr_seed: int = 0) -> QCopy:
-    """x_bf16_bits: uint16 [rows, cols] holding bf16 bit patterns."""
+             use_rht: bool = False, rht_seed: int = 0, sr_seed: int = 0, rht_dim: int = 16) -> QCopy:
+    """x_bf16_bits: uint16 [rows, cols] holding bf16 bit patterns; rht_dim is the rotation size if use_rht."""
     x = np.ascontiguousarray(x_bf16_bits, dtype=np.uint16)
     rows, cols = x.shape
     outer, inner = (cols, rows) if copy == COL else (rows, cols)
     codes = np.zeros((outer, inner // 2), dtype=np.uint8)
     scales = np.zeros((outer, inner // 16), dtype=np.uint8)
     ts = np.zeros(2, dtype=np.float32)
-    rc = lib().orc_quantize(_p(x), rows, cols, cols, copy, block_dim, rounding, int(use_rht),
+    rc = lib().orc_quantize(_p(x), rows, cols, cols, copy, block_dim, rounding, rht_dim if use_rht else 0,
                             rht_seed, sr_seed, _p(codes), _p(scales), _p(ts))
     if rc != 0:
         raise ValueError(f"orc_quantize rejected its arguments (rc={rc})")
     return QCopy(codes, scales, np.float32(ts[0]), np.float32(ts[1]), outer, inner)
 
 
-def dequantize(q: QCopy, undo_rht: bool = False, rht_seed: int = 0) -> np.ndarray:
+def dequantize(q: QCopy, undo_rht: bool = False, rht_seed: int = 0, rht_dim: int = 16) -> np.ndarray:
     out = np.zeros((q.outer, q.inner), dtype=np.float32)
     rc = lib().orc_dequantize(_p(q.codes), _p(q.scales), float(q.s_dec), q.outer, q.inner,
-                              int(undo_rht), rht_seed, _p(out))
+                              rht_dim if undo_rht else 0, rht_seed, _p(out))
     if rc != 0:
         raise ValueError("orc_dequantize rejected its arguments")
     return out

@@ -238,6 +238,43 @@ void rht16_inverse(float y[16], uint32_t mask) {
   for (int i = 0; i < 16; ++i) if ((mask >> i) & 1u) y[i] = -y[i];
 }
 
+// Other rotation sizes (Sec. 4.2 "Hadamard matrix size", App. E.4: d = 2, 4, 128 are ablated against
+// d = 16; d = 32 belongs to the MXFP4 comparison).  Same construction for every d: sign i of the
+// diagonal is bit i of the 128 bits the Philox call above returns (word i / 32, bit i % 32), so
+// d = 16 gives rht_sign_mask(); butterfly stages h = 1, 2, ..., d / 2 in this order; then one
+// multiply by the binary32 nearest to 1 / sqrt(d) (exact for d = 4, 16).
+bool rht_dim_ok(int d) { return d == 2 || d == 4 || d == 16 || d == 32 || d == 128; }
+
+void rht_signs(uint64_t seed, int d, uint8_t* negate) {
+  const uint32_t ctr[4] = {0u, 0u, 0u, 0xFFFFFFFFu};
+  const uint32_t key[2] = {static_cast<uint32_t>(seed), static_cast<uint32_t>(seed >> 32)};
+  uint32_t w[4];
+  philox4x32_10(ctr, key, w);
+  for (int i = 0; i < d; ++i) negate[i] = static_cast<uint8_t>((w[i >> 5] >> (i & 31)) & 1u);
+}
+
+void hadamard_d(float* v, int d) {
+  for (int h = 1; h < d; h <<= 1)
+    for (int i = 0; i < d; ++i)
+      if ((i & h) == 0) {
+        const float a = v[i], b = v[i + h];
+        v[i] = a + b;
+        v[i + h] = a - b;
+      }
+  const float norm = static_cast<float>(1.0 / std::sqrt(static_cast<double>(d)));
+  for (int i = 0; i < d; ++i) v[i] = norm * v[i];
+}
+
+void rht_forward_d(float* v, int d, const uint8_t* negate) {
+  for (int i = 0; i < d; ++i) if (negate[i]) v[i] = -v[i];
+  hadamard_d(v, d);
+}
+
+void rht_inverse_d(float* y, int d, const uint8_t* negate) {
+  hadamard_d(y, d);
+  for (int i = 0; i < d; ++i) if (negate[i]) y[i] = -y[i];
+}
+
 // ---------------------------------------------------------------- quantize
 
 struct View {            // element (o, k) of the copy's [outer, inner] view
@@ -264,6 +301,21 @@ uint32_t orc_sr_random16(uint64_t seed, uint64_t i, uint64_t j) { return sr_rand
 uint32_t orc_rht_sign_mask(uint64_t seed) { return rht_sign_mask(seed); }
 void     orc_rht16_forward(float* v, uint32_t mask) { rht16_forward(v, mask); }
 void     orc_rht16_inverse(float* v, uint32_t mask) { rht16_inverse(v, mask); }
+int orc_rht_signs(uint64_t seed, int d, uint8_t* negate) {
+  if (!rht_dim_ok(d)) return -1;
+  rht_signs(seed, d, negate);
+  return 0;
+}
+int orc_rht_forward_d(float* v, int d, const uint8_t* negate) {
+  if (!rht_dim_ok(d)) return -1;
+  rht_forward_d(v, d, negate);
+  return 0;
+}
+int orc_rht_inverse_d(float* v, int d, const uint8_t* negate) {
+  if (!rht_dim_ok(d)) return -1;
+  rht_inverse_d(v, d, negate);
+  return 0;
+}
 int      orc_num_threads(void) {
 #ifdef _OPENMP
   return omp_get_max_threads();
@@ -277,13 +329,14 @@ int      orc_num_threads(void) {
 //              rows, stored transposed)
 //   block_dim  1 = 1x16 blocks, 16 = 16x16 blocks (weights, Sec. 4.3)
 //   rounding   0 = round-to-nearest-even, 1 = stochastic
-//   use_rht    rotate each aligned group of 16 along the block direction
-//              before anything else (Wgrad operands, Sec. 4.2)
+//   rht_dim    0, or the size d of the rotation: each aligned group of d along
+//              the block direction is rotated before anything else (Wgrad
+//              operands, Sec. 4.2; d = 16 is the paper's choice)
 // Outputs: codes [outer, inner/2] bytes, scales [outer, inner/16] bytes,
 // tensor_scale[0] = s_dec, tensor_scale[1] = amax (in the rotated space for a
 // rotated copy).  Returns 0, or -1 for bad arguments.
 int orc_quantize(const uint16_t* x, int64_t rows, int64_t cols, int64_t ld,
-                 int copy, int block_dim, int rounding, int use_rht,
+                 int copy, int block_dim, int rounding, int rht_dim,
                  uint64_t rht_seed, uint64_t sr_seed,
                  uint8_t* codes, uint8_t* scales, float* tensor_scale) {
   if (!x || !codes || !scales || !tensor_scale) return -1;
@@ -292,13 +345,15 @@ int orc_quantize(const uint16_t* x, int64_t rows, int64_t cols, int64_t ld,
   if (block_dim != 1 && block_dim != 16) return -1;
   if ((copy == 0 ? cols : rows) % 16) return -1;             // whole blocks along the block direction
   if (block_dim == 16 && (rows % 16 || cols % 16)) return -1;
-  if (block_dim == 16 && use_rht) return -1;   // the paper never rotates weights (Sec. 4.3)
+  if (block_dim == 16 && rht_dim) return -1;   // the paper never rotates weights (Sec. 4.3)
+  if (rht_dim && (!rht_dim_ok(rht_dim) || (copy == 0 ? cols : rows) % rht_dim)) return -1;
 
   const View view{x, ld, copy == 1};
   const int64_t outer = copy == 1 ? cols : rows;
   const int64_t inner = copy == 1 ? rows : cols;
   const int64_t nblk = inner / 16;
-  const uint32_t mask = use_rht ? rht_sign_mask(rht_seed) : 0u;
+  uint8_t negate[128] = {0};
+  if (rht_dim) rht_signs(rht_seed, rht_dim, negate);
 
   // Step 0: the values to be quantized, in binary32, rotated if asked.
   std::vector<float> w(static_cast<size_t>(outer) * static_cast<size_t>(inner));
@@ -306,8 +361,8 @@ int orc_quantize(const uint16_t* x, int64_t rows, int64_t cols, int64_t ld,
   for (int64_t o = 0; o < outer; ++o) {
     float* wo = w.data() + o * inner;
     for (int64_t k = 0; k < inner; ++k) wo[k] = view.at(o, k);
-    if (use_rht)
-      for (int64_t b = 0; b < nblk; ++b) rht16_forward(wo + 16 * b, mask);
+    if (rht_dim)
+      for (int64_t g = 0; g < inner / rht_dim; ++g) rht_forward_d(wo + rht_dim * g, rht_dim, negate);
   }
 
   // App. B.1, Eq. 1: tensor-level scale from the global amax.
@@ -386,27 +441,27 @@ int orc_quantize(const uint16_t* x, int64_t rows, int64_t cols, int64_t ld,
 
 // Decode a quantized copy [outer, inner] back to binary32:
 // value(code) * fp32(stored block scale), then * s_dec (Sec. 2: decode with
-// the reciprocal of the encode scale; App. B.2).  With undo_rht each aligned
-// group of 16 is rotated back.
+// the reciprocal of the encode scale; App. B.2).  With undo_rht_dim = d each
+// aligned group of d is rotated back.
 int orc_dequantize(const uint8_t* codes, const uint8_t* scales, float s_dec,
-                   int64_t outer, int64_t inner, int undo_rht, uint64_t rht_seed,
+                   int64_t outer, int64_t inner, int undo_rht_dim, uint64_t rht_seed,
                    float* out) {
   if (!codes || !scales || !out || inner % 16) return -1;
-  const uint32_t mask = undo_rht ? rht_sign_mask(rht_seed) : 0u;
+  if (undo_rht_dim && (!rht_dim_ok(undo_rht_dim) || inner % undo_rht_dim)) return -1;
+  uint8_t negate[128] = {0};
+  if (undo_rht_dim) rht_signs(rht_seed, undo_rht_dim, negate);
 #pragma omp parallel for schedule(static)
   for (int64_t o = 0; o < outer; ++o) {
-    for (int64_t b = 0; b < inner / 16; ++b) {
-      const float sd = e4m3_decode(scales[o * (inner / 16) + b]);
-      float g[16];
-      for (int k = 0; k < 16; ++k) {
-        const uint8_t byte = codes[o * (inner / 2) + (16 * b + k) / 2];
-        const uint32_t c = (k & 1) ? (byte >> 4) : (byte & 15u);
-        const float t = e2m1_decode(c) * sd;
-        g[k] = t * s_dec;
-      }
-      if (undo_rht) rht16_inverse(g, mask);
-      for (int k = 0; k < 16; ++k) out[o * inner + 16 * b + k] = g[k];
+    float* row = out + o * inner;
+    for (int64_t k = 0; k < inner; ++k) {
+      const float sd = e4m3_decode(scales[o * (inner / 16) + k / 16]);
+      const uint8_t byte = codes[o * (inner / 2) + k / 2];
+      const uint32_t c = (k & 1) ? (byte >> 4) : (byte & 15u);
+      const float t = e2m1_decode(c) * sd;
+      row[k] = t * s_dec;
     }
+    if (undo_rht_dim)
+      for (int64_t g = 0; g < inner / undo_rht_dim; ++g) rht_inverse_d(row + undo_rht_dim * g, undo_rht_dim, negate);
   }
   return 0;
 }
