@@ -57,7 +57,7 @@ typedef enum nvfp4_status {
   NVFP4_ERR_INVALID_ARG = -1,  /* null pointer, unknown enum value */
   NVFP4_ERR_BAD_SHAPE = -2,    /* rows or cols not a positive multiple of 16, ld too small */
   NVFP4_ERR_MISSING_COPY = -3, /* the copy an operation needs is absent from the descriptor */
-  NVFP4_ERR_MISMATCH = -4,     /* operands disagree on K, rotation flag or rotation seed */
+  NVFP4_ERR_MISMATCH = -4,     /* operands disagree on K, rotation size or rotation seed */
   NVFP4_ERR_HIP = -5,          /* a HIP runtime call failed (launch error) */
   NVFP4_ERR_WORKSPACE = -6     /* workspace missing or too small */
 } nvfp4_status;
@@ -93,7 +93,7 @@ typedef struct nvfp4_qtensor {
   int32_t layout_mask;      /* which copies hold data (set by nvfp4_quantize) */
   int32_t block_dim;        /* NVFP4_BLOCK_* used */
   int32_t rounding;         /* NVFP4_ROUND_* used */
-  int32_t col_has_rht;      /* 1 if the col copy was rotated */
+  int32_t col_has_rht;      /* 0, or the size d of the rotation applied to the col copy */
   uint64_t rht_seed;        /* seed of the sign diagonal, if rotated */
 } nvfp4_qtensor;
 
@@ -111,11 +111,18 @@ int nvfp4_quantized_sizes(int64_t rows, int64_t cols, size_t* codes_bytes, size_
  *   layout_mask  NVFP4_LAYOUT_ROW | NVFP4_LAYOUT_COL: which copies to emit
  *   block_dim    1x16 (activations, gradients) or 16x16 (weights, Sec. 4.3)
  *   rounding     RNE (weights, activations) or SR (gradients), Sec. 4.4
- *   rht_on_col   rotate the col copy: every aligned group of 16 consecutive
+ *   rht_on_col   rotate the col copy: every aligned group of d consecutive
  *                rows of a column is multiplied by the sign diagonal and the
- *                16-point Hadamard matrix before scaling (Sec. 4.2, App. C).
- *                Not allowed with 16x16 blocks.
- *   rht_seed     selects the sign diagonal (nvfp4_rht_sign_mask)
+ *                d-point Hadamard matrix before scaling (Sec. 4.2, App. C).
+ *                0 = no rotation; 1 = the format's own size (d = 16, the
+ *                paper's choice; 32 for MXFP4); 2, 4, 16, 32 or 128 = that
+ *                size (the other sizes of the ablation in Sec. 4.2 "Hadamard
+ *                matrix size" and App. E.4; NVFP4 only).  rows must be a
+ *                multiple of d.  Not allowed with 16x16 blocks.  Butterfly
+ *                stages h = 1, 2, .., d/2 in this order, then one multiply
+ *                by the binary32 nearest to 1/sqrt(d).
+ *   rht_seed     selects the sign diagonal: sign i is bit i of the 128 bits of
+ *                one Philox call (nvfp4_rht_sign_mask gives the first 16)
  *   sr_seed      key of the Philox4x32-10 stream used for SR; element (i, j)
  *                uses counter (j/8, i, 0, 0), 16 bits per element, so both
  *                copies round with the same draw
@@ -138,7 +145,7 @@ int nvfp4_quantize(const void* x, int64_t rows, int64_t cols, int64_t ld, int la
  *   DGRAD  dX = dY W^T   A = row copy of dY [M,K],  B = row copy of W [N,K]
  *   WGRAD  dW = A^T B    A = col copy of the first tensor [K,M] (-> [M,K]),
  *                        B = col copy of the second [K,N] (-> [N,K]); both must
- *                        agree on rotation flag and seed (App. C)
+ *                        agree on rotation size and seed (App. C)
  * D is device memory, [M, N] row-major with leading dimension ldd (a multiple
  * of 4), FP32 or bf16 (bf16 = round-to-nearest-even of the FP32 result).  With
  * NVFP4_OUT_F32_ACCUMULATE, D is FP32 and is read: every element becomes
@@ -198,7 +205,7 @@ int nvfp4_linear_backward(const void* dy, int64_t tokens, int64_t d_out, int64_t
  * Decode one copy back to FP32 or bf16: value(code) * block scale * s_dec
  * (Sec. 2; App. B.2).  The output has the copy's own orientation: [rows, cols]
  * for the row copy, [cols, rows] for the col copy, leading dimension ld_out.
- * undo_rht rotates each group of 16 back (only meaningful for a rotated copy).
+ * undo_rht rotates each group of d back, d = q->col_has_rht (only meaningful for a rotated copy).
  */
 int nvfp4_dequantize(const nvfp4_qtensor* q, int which_copy, int undo_rht, void* out, int out_dtype,
                      int64_t ld_out, nvfp4_stream_t stream);

@@ -154,9 +154,10 @@ def _workspace(device, nbytes: int) -> torch.Tensor:
 
 
 def nvfp4_quantize(x: torch.Tensor, layout_mask: int, block_dim: int = BLOCK_1x16, rounding: int = ROUND_RNE,
-                   rht_on_col: bool = False, rht_seed: int = 0, sr_seed: int = 0,
+                   rht_on_col=False, rht_seed: int = 0, sr_seed: int = 0,
                    out: Optional[QTensor] = None, workspace: Optional[torch.Tensor] = None) -> QTensor:
-    """x: bf16 CUDA tensor [rows, cols] (last dim contiguous)."""
+    """x: bf16 CUDA tensor [rows, cols] (last dim contiguous).  rht_on_col: False, True (the format's own rotation
+    size) or the size itself (2, 4, 16, 32, 128 for NVFP4)."""
     if not x.is_cuda or x.dtype != torch.bfloat16 or x.dim() != 2 or x.stride(1) != 1:
         raise ValueError("x must be a 2-D bf16 CUDA tensor with unit inner stride")
     rows, cols = x.shape

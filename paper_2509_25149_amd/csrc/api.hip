@@ -26,6 +26,31 @@ void host_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t o
 
 bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
+// Rotation size asked for by nvfp4_quantize's rht_on_col: 0 none, 1 the format's own (16; 32 for MXFP4), or the
+// size itself.  Returns -1 for a size the format does not have.
+int rotation_size(int rht_on_col, bool mx) {
+  if (rht_on_col == 0) return 0;
+  if (rht_on_col == 1) return mx ? 32 : 16;
+  if (mx) return rht_on_col == 32 ? 32 : -1;
+  return (rht_on_col == 2 || rht_on_col == 4 || rht_on_col == 16 || rht_on_col == 32 || rht_on_col == 128) ? rht_on_col : -1;
+}
+
+// The sign diagonal in the forms the kernels take (QuantizeArgs): all its bits, and for sizes up to 32 one word
+// (sizes below 16 repeated over the low 16 bits, since those kernels walk 16 rows at a time).
+void fill_signs(uint64_t seed, int d, uint32_t* mask, uint32_t words[4]) {
+  words[0] = words[1] = words[2] = words[3] = 0u;
+  *mask = 0u;
+  if (d == 0) return;
+  host_rht_sign_words(seed, words);
+  if (d >= 32) {
+    *mask = words[0];
+  } else {
+    const uint32_t bits = words[0] & ((1u << d) - 1u);
+    for (int i = 0; i < 16; i += d) *mask |= bits << i;
+    if (d == 16) *mask = bits;
+  }
+}
+
 
 }  // namespace
 
@@ -38,6 +63,12 @@ uint32_t host_rht_sign_mask32(uint64_t seed) {
 }
 
 uint32_t host_rht_sign_mask(uint64_t seed) { return host_rht_sign_mask32(seed) & 0xFFFFu; }
+
+void host_rht_sign_words(uint64_t seed, uint32_t words[4]) {
+  const uint32_t ctr[4] = {0u, 0u, 0u, 0xFFFFFFFFu};
+  const uint32_t key[2] = {static_cast<uint32_t>(seed), static_cast<uint32_t>(seed >> 32)};
+  host_philox4x32_10(ctr, key, words);
+}
 
 }  // namespace nvfp4
 
@@ -53,7 +84,7 @@ const char* nvfp4_status_string(int status) {
     case NVFP4_ERR_INVALID_ARG: return "invalid argument (null pointer, unknown enum, misaligned pointer)";
     case NVFP4_ERR_BAD_SHAPE: return "bad shape (rows/cols must be positive multiples of 16; leading dimension too small or misaligned)";
     case NVFP4_ERR_MISSING_COPY: return "the quantized tensor lacks the copy this operation needs";
-    case NVFP4_ERR_MISMATCH: return "operands disagree (contraction length, rotation flag or rotation seed)";
+    case NVFP4_ERR_MISMATCH: return "operands disagree (contraction length, rotation size or rotation seed)";
     case NVFP4_ERR_HIP: return "HIP runtime error";
     case NVFP4_ERR_WORKSPACE: return "workspace missing or too small";
     default: return "unknown status";
@@ -89,8 +120,10 @@ int plan_quantize(const void* x, int64_t rows, int64_t cols, int64_t ld, int lay
   if (rounding != NVFP4_ROUND_RNE && rounding != NVFP4_ROUND_SR) return NVFP4_ERR_INVALID_ARG;
   const bool want_row = layout_mask & NVFP4_LAYOUT_ROW, want_col = layout_mask & NVFP4_LAYOUT_COL;
   const bool mx = block_dim == NVFP4_BLOCK_MX32;
-  if (rht_on_col && (block_dim == NVFP4_BLOCK_16x16 || !want_col)) return NVFP4_ERR_INVALID_ARG;
+  const int rht_dim = rotation_size(rht_on_col, mx);
+  if (rht_dim < 0 || (rht_dim && (block_dim == NVFP4_BLOCK_16x16 || !want_col))) return NVFP4_ERR_INVALID_ARG;
   if (rows <= 0 || cols <= 0 || rows % 16 || cols % 16 || ld < cols || ld % 8) return NVFP4_ERR_BAD_SHAPE;
+  if (rht_dim && rows % rht_dim) return NVFP4_ERR_BAD_SHAPE;   // whole rotation groups along the rows
   if (mx && (rows % 32 || cols % 32)) return NVFP4_ERR_BAD_SHAPE;
   if (!aligned(x, 16)) return NVFP4_ERR_INVALID_ARG;
   if (want_row && (!out->row_codes || !out->row_scales || !out->row_tensor_scale)) return NVFP4_ERR_INVALID_ARG;
@@ -108,10 +141,11 @@ int plan_quantize(const void* x, int64_t rows, int64_t cols, int64_t ld, int lay
   a.ld = ld;
   a.want_row = want_row;
   a.want_col = want_col;
-  a.rht = rht_on_col != 0;
+  a.rht = rht_dim != 0;
+  a.rht_dim = rht_dim;
   a.sr = rounding == NVFP4_ROUND_SR;
   a.block2d = block_dim == NVFP4_BLOCK_16x16;
-  a.sign_mask = !a.rht ? 0u : mx ? host_rht_sign_mask32(rht_seed) : host_rht_sign_mask(rht_seed);
+  fill_signs(rht_seed, rht_dim, &a.sign_mask, a.sign_words);
   a.key0 = static_cast<uint32_t>(sr_seed);
   a.key1 = static_cast<uint32_t>(sr_seed >> 32);
   a.ws = static_cast<uint32_t*>(workspace);
@@ -128,7 +162,7 @@ int plan_quantize(const void* x, int64_t rows, int64_t cols, int64_t ld, int lay
   p->desc.layout_mask = layout_mask;
   p->desc.block_dim = block_dim;
   p->desc.rounding = rounding;
-  p->desc.col_has_rht = a.rht ? 1 : 0;
+  p->desc.col_has_rht = rht_dim;
   p->desc.rht_seed = a.rht ? rht_seed : 0;
   return NVFP4_OK;
 }
@@ -204,7 +238,7 @@ static int plan_gemm(const nvfp4_qtensor* a, const nvfp4_qtensor* b, int op, voi
     return NVFP4_ERR_INVALID_ARG;
   g.mx = a_mx;
   // Rotated operands only make sense in pairs that rotate the same way (App. C).
-  const bool a_rot = a_col && a->col_has_rht, b_rot = b_col && b->col_has_rht;
+  const int a_rot = a_col ? a->col_has_rht : 0, b_rot = b_col ? b->col_has_rht : 0;   // rotation sizes
   if (a_rot != b_rot || (a_rot && a->rht_seed != b->rht_seed)) return NVFP4_ERR_MISMATCH;
   if (ka <= 0 || ka % 16 || g.a.outer <= 0 || g.b.outer <= 0) return NVFP4_ERR_BAD_SHAPE;
   if (ldd < g.b.outer || ldd % 4) return NVFP4_ERR_BAD_SHAPE;
@@ -268,7 +302,7 @@ int nvfp4_linear_backward(const void* dy, int64_t tokens, int64_t d_out, int64_t
   if (!(qx->layout_mask & NVFP4_LAYOUT_COL) || !qx->col_has_rht) return NVFP4_ERR_MISSING_COPY;
   QuantPlan pdy;
   int rc = plan_quantize(dy, tokens, d_out, lddy, NVFP4_LAYOUT_ROW | NVFP4_LAYOUT_COL, NVFP4_BLOCK_1x16,
-                         NVFP4_ROUND_SR, 1, qx->rht_seed, sr_seed, qdy, workspace, workspace_bytes, &pdy);
+                         NVFP4_ROUND_SR, qx->col_has_rht, qx->rht_seed, sr_seed, qdy, workspace, workspace_bytes, &pdy);
   if (rc != NVFP4_OK) return rc;
   GemmArgs dgrad, wgrad;
   rc = plan_gemm(&pdy.desc, qw, NVFP4_OP_DGRAD, dx, dx_dtype, lddx, workspace, workspace_bytes, &dgrad);
@@ -296,7 +330,9 @@ int nvfp4_dequantize(const nvfp4_qtensor* q, int which_copy, int undo_rht, void*
   if (d.K <= 0 || d.K % (mx ? 32 : 16) || ld_out < d.K || ld_out % 8) return NVFP4_ERR_BAD_SHAPE;
   if (!aligned(out, 16) || !aligned(d.q.codes, mx ? 16 : 8)) return NVFP4_ERR_INVALID_ARG;
   d.undo_rht = undo_rht != 0;
-  d.sign_mask = !d.undo_rht ? 0u : mx ? host_rht_sign_mask32(q->rht_seed) : host_rht_sign_mask(q->rht_seed);
+  d.rht_dim = d.undo_rht ? q->col_has_rht : 0;
+  if (d.undo_rht && (rotation_size(d.rht_dim, mx) != d.rht_dim || d.rht_dim == 1 || d.K % d.rht_dim)) return NVFP4_ERR_MISMATCH;
+  fill_signs(q->rht_seed, d.rht_dim, &d.sign_mask, d.sign_words);
   d.out = out;
   d.ld_out = ld_out;
   d.out_bf16 = out_dtype == NVFP4_OUT_BF16;

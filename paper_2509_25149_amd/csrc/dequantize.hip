@@ -107,6 +107,90 @@ __global__ __launch_bounds__(256) void dequantize_mx_kernel(Operand q, int64_t K
   }
 }
 
+// NVFP4 with the inverse of a rotation of another size (2, 4, 32, 128 points; Sec. 4.2 "Hadamard matrix size"):
+// one thread per max(16, d) elements.  x = s .* (H_d y) with the same stage order and single 1/sqrt(d) multiply as
+// the forward transform (H_d is symmetric and orthogonal, App. C).
+template <bool kBf16Out, int kD>
+__global__ __launch_bounds__(256) void dequantize_rot_kernel(Operand q, int64_t K, uint4 sign_words, void* __restrict__ outv,
+                                                             int64_t ld_out) {
+  constexpr int kE = kD < 16 ? 16 : kD;   // elements per thread
+  const int64_t nper = K / kE;
+  const int64_t idx = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+  if (idx >= q.outer * nper) return;
+  const int64_t o = idx / nper, b = idx % nper;
+  const float s_dec = q.ts[0];
+  float v[kE];
+#pragma unroll
+  for (int blk = 0; blk < kE / 16; ++blk) {
+    const uint2 c = *reinterpret_cast<const uint2*>(q.codes + o * (K / 2) + b * (kE / 2) + blk * 8);
+    const float sd = e4m3_decode(q.scales[o * (K / 16) + b * (kE / 16) + blk]);
+    float* w = v + 16 * blk;
+    decode_pair_f32<0>(c.x, w + 0);
+    decode_pair_f32<1>(c.x, w + 2);
+    decode_pair_f32<2>(c.x, w + 4);
+    decode_pair_f32<3>(c.x, w + 6);
+    decode_pair_f32<0>(c.y, w + 8);
+    decode_pair_f32<1>(c.y, w + 10);
+    decode_pair_f32<2>(c.y, w + 12);
+    decode_pair_f32<3>(c.y, w + 14);
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+      const float t = w[k] * sd;
+      w[k] = t * s_dec;
+    }
+  }
+#pragma unroll
+  for (int h = 1; h < kD; h <<= 1) {
+#pragma unroll
+    for (int i = 0; i < kE; ++i) {
+      if ((i & h) == 0) {
+        const float a = v[i], c = v[i + h];
+        v[i] = a + c;
+        v[i + h] = a - c;
+      }
+    }
+  }
+  constexpr float kNorm = kD == 2 ? 0.707106781186547524f : kD == 4 ? 0.5f : kD == 32 ? 0.176776695296636893f : 0.0883883476483184405f;
+  const uint32_t sw[4] = {sign_words.x, sign_words.y, sign_words.z, sign_words.w};
+#pragma unroll
+  for (int i = 0; i < kE; ++i) {
+    const int bit = i % kD;
+    v[i] = __uint_as_float(__float_as_uint(kNorm * v[i]) ^ (((sw[bit >> 5] >> (bit & 31)) & 1u) << 31));
+  }
+  if (kBf16Out) {
+    uint4* dst = reinterpret_cast<uint4*>(static_cast<uint16_t*>(outv) + o * ld_out + b * kE);
+#pragma unroll
+    for (int t = 0; t < kE / 8; ++t) {
+      uint32_t w[4];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) w[k] = f32_to_bf16(v[8 * t + 2 * k]) | (f32_to_bf16(v[8 * t + 2 * k + 1]) << 16);
+      dst[t] = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+  } else {
+    float4v* dst = reinterpret_cast<float4v*>(static_cast<float*>(outv) + o * ld_out + b * kE);
+#pragma unroll
+    for (int t = 0; t < kE / 4; ++t) {
+      float4v f;
+      f[0] = v[4 * t];
+      f[1] = v[4 * t + 1];
+      f[2] = v[4 * t + 2];
+      f[3] = v[4 * t + 3];
+      dst[t] = f;
+    }
+  }
+}
+
+template <int kD>
+void launch_rot(const DequantArgs& d, hipStream_t s) {
+  const int64_t total = d.q.outer * (d.K / (kD < 16 ? 16 : kD));
+  const dim3 grid(static_cast<unsigned>((total + 255) / 256));
+  const uint4 signs = make_uint4(d.sign_words[0], d.sign_words[1], d.sign_words[2], d.sign_words[3]);
+  if (d.out_bf16)
+    hipLaunchKernelGGL((dequantize_rot_kernel<true, kD>), grid, dim3(256), 0, s, d.q, d.K, signs, d.out, d.ld_out);
+  else
+    hipLaunchKernelGGL((dequantize_rot_kernel<false, kD>), grid, dim3(256), 0, s, d.q, d.K, signs, d.out, d.ld_out);
+}
+
 }  // namespace
 
 hipError_t launch_dequantize_mx(const DequantArgs& d, hipStream_t s) {
@@ -123,6 +207,16 @@ hipError_t launch_dequantize_mx(const DequantArgs& d, hipStream_t s) {
 hipError_t launch_dequantize(const DequantArgs& d, hipStream_t s) {
   const int64_t total = d.q.outer * (d.K / 16);
   if (total == 0) return hipSuccess;
+  if (d.undo_rht && d.rht_dim != 16) {
+    switch (d.rht_dim) {
+      case 2: launch_rot<2>(d, s); break;
+      case 4: launch_rot<4>(d, s); break;
+      case 32: launch_rot<32>(d, s); break;
+      case 128: launch_rot<128>(d, s); break;
+      default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+  }
   const dim3 grid(static_cast<unsigned>((total + 255) / 256));
   if (d.out_bf16)
     hipLaunchKernelGGL(dequantize_kernel<true>, grid, dim3(256), 0, s, d.q, d.K, d.undo_rht, d.sign_mask, d.out, d.ld_out);

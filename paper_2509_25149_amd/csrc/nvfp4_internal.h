@@ -10,7 +10,10 @@ struct QuantizeArgs {
   const void* x;
   int64_t rows, cols, ld;
   bool want_row, want_col, rht, sr, block2d;
-  uint32_t sign_mask, key0, key1;
+  int rht_dim;             // 0, or the rotation size: 2, 4, 16, 32, 128 (NVFP4); 32 (MXFP4)
+  uint32_t sign_mask;      // the sign diagonal: d <= 16: its d bits repeated over the low 16 bits; 32: its 32 bits
+  uint32_t sign_words[4];  // the sign diagonal's bits, first rht_dim of the 128 meaningful
+  uint32_t key0, key1;
   uint32_t* ws;  // device workspace: [0] raw amax bits, [1] rotated amax bits, then per-workgroup partials
   uint8_t *row_codes, *row_scales;
   float* row_ts;
@@ -18,6 +21,8 @@ struct QuantizeArgs {
   float* col_ts;
 };
 hipError_t launch_quantize(const QuantizeArgs& a, hipStream_t s);
+// NVFP4 with a 32- or 128-point rotation of the col copy (rotation groups span several 16-row groups)
+hipError_t launch_quantize_wide(const QuantizeArgs& a, hipStream_t s);
 // MXFP4 mode (1x32 blocks, UE8M0 scales, one pass, no workspace); sign_mask holds 32 bits
 hipError_t launch_quantize_mx(const QuantizeArgs& a, hipStream_t s);
 size_t quantize_workspace_bytes(int64_t rows, int64_t cols);
@@ -49,7 +54,9 @@ struct DequantArgs {
   Operand q;
   int64_t K;
   bool undo_rht;
-  uint32_t sign_mask;
+  int rht_dim;             // size of the rotation to undo
+  uint32_t sign_mask;      // as in QuantizeArgs
+  uint32_t sign_words[4];
   void* out;
   int64_t ld_out;
   bool out_bf16;
@@ -62,6 +69,7 @@ hipError_t run_selftest(uint64_t* mismatches_dev, hipStream_t s);
 // Host Philox4x32-10, used only to derive the sign diagonal from a seed (16 bits, or 32 for the MXFP4 mode).
 uint32_t host_rht_sign_mask(uint64_t seed);
 uint32_t host_rht_sign_mask32(uint64_t seed);
+void host_rht_sign_words(uint64_t seed, uint32_t words[4]);   // all 128 bits of the same Philox call
 
 // MXFP4 GEMM on the scaled FP4 MFMA (scales per 32 are UE8M0); K must be a multiple of 128.
 hipError_t launch_gemm_mx(const GemmArgs& g, hipStream_t s);

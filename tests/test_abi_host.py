@@ -74,6 +74,10 @@ def test_quantize_rejects_bad_arguments(lib):
     assert lib.nvfp4_quantize(X, 16, 16, 16, 1, 1, 7, 0, 0, 0, *ok_tail) == -1      # unknown rounding
     assert lib.nvfp4_quantize(X, 16, 16, 16, 3, 16, 0, 1, 0, 0, *ok_tail) == -1     # rotation with 16x16 blocks
     assert lib.nvfp4_quantize(X, 16, 16, 16, 1, 1, 0, 1, 0, 0, *ok_tail) == -1      # rotation without a col copy
+    for size in (3, 8, 64, 256, -16):                                                # no rotation of these sizes
+        assert lib.nvfp4_quantize(X, 256, 16, 16, 2, 1, 0, size, 0, 0, *ok_tail) == -1
+    assert lib.nvfp4_quantize(X, 160, 16, 16, 2, 1, 0, 128, 0, 0, *ok_tail) == -2   # rows are not whole rotation groups
+    assert lib.nvfp4_quantize(X, 48, 16, 16, 2, 1, 0, 32, 0, 0, *ok_tail) == -2
     assert lib.nvfp4_quantize(X, 24, 16, 16, 1, 1, 0, 0, 0, 0, *ok_tail) == -2
     assert lib.nvfp4_quantize(X, 0, 16, 16, 1, 1, 0, 0, 0, 0, *ok_tail) == -2       # empty tensors are rejected
     assert lib.nvfp4_quantize(X, 16, 0, 16, 1, 1, 0, 0, 0, 0, *ok_tail) == -2
@@ -100,10 +104,16 @@ def test_gemm_and_dequantize_reject_bad_arguments(lib):
     only_row = _desc(64, 48, mask=1)
     assert lib.nvfp4_gemm(ctypes.byref(a), ctypes.byref(only_row), 0, D, 0, 48, None, 0, None) == -3
     # WGRAD operands must rotate alike
-    p, q = _desc(64, 32, rht=1, seed=5), _desc(64, 48, rht=0)
+    p, q = _desc(64, 32, rht=16, seed=5), _desc(64, 48, rht=0)
     assert lib.nvfp4_gemm(ctypes.byref(p), ctypes.byref(q), 2, D, 0, 48, None, 0, None) == -4
-    q2 = _desc(64, 48, rht=1, seed=6)
+    q2 = _desc(64, 48, rht=16, seed=6)
     assert lib.nvfp4_gemm(ctypes.byref(p), ctypes.byref(q2), 2, D, 0, 48, None, 0, None) == -4
+    p3, q3 = _desc(128, 32, rht=128, seed=5), _desc(128, 48, rht=32, seed=5)            # same seed, different rotation size
+    assert lib.nvfp4_gemm(ctypes.byref(p3), ctypes.byref(q3), 2, D, 0, 48, None, 0, None) == -4
+    bad = _desc(128, 32, rht=64, seed=5)                                                # a size that does not exist
+    assert lib.nvfp4_dequantize(ctypes.byref(bad), 1, 1, D, 0, 128, None) == -4
+    short = _desc(64, 32, rht=128, seed=5)                                              # 64 rows cannot hold a 128-point group
+    assert lib.nvfp4_dequantize(ctypes.byref(short), 1, 1, D, 0, 64, None) == -4
     assert lib.nvfp4_dequantize(ctypes.byref(a), 3, 0, D, 0, 64, None) == -1
     assert lib.nvfp4_dequantize(ctypes.byref(a), 0, 1, D, 0, 64, None) == -4            # undo_rht on a plain copy
     assert lib.nvfp4_dequantize(ctypes.byref(a), 0, 0, D, 0, 32, None) == -2
@@ -151,7 +161,7 @@ def test_linear_layer_calls_reject_before_enqueueing(lib):
     assert fwd(fake, 32, 64, 64, ctypes.byref(qw), 1, 0, ctypes.byref(qx), fake, 1, 48, fake, 8, None) == -6
     assert qx.layout_mask == 0                                   # a rejected call leaves the descriptor alone
     bwd = lambda *a: lib.nvfp4_linear_backward(*a)
-    qx.rows, qx.cols, qx.layout_mask, qx.block_dim, qx.col_has_rht, qx.rht_seed = 32, 64, 3, 1, 1, 5
+    qx.rows, qx.cols, qx.layout_mask, qx.block_dim, qx.col_has_rht, qx.rht_seed = 32, 64, 3, 1, 16, 5
     assert bwd(fake, 32, 48, 48, ctypes.byref(qx), ctypes.byref(qw), 0, ctypes.byref(qdy), fake, 7, 64, fake, 48, 1, *ok_ws) == -1
     assert bwd(fake, 32, 48, 48, ctypes.byref(qx), ctypes.byref(qw), 0, ctypes.byref(qdy), fake, 1, 48, fake, 48, 1, *ok_ws) == -2  # lddx < d_in
     assert bwd(fake, 32, 48, 48, ctypes.byref(qx), ctypes.byref(qw), 0, ctypes.byref(qdy), fake, 1, 64, fake, 32, 1, *ok_ws) == -2  # lddw < d_out
