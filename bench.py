@@ -134,6 +134,35 @@ def mxfp4_comparison(torch, nv, x, w, dy, iters: int = 5):
             "quantize_ms_per_step": q_ms / iters}
 
 
+def rht_size_sweep(torch, nv, x, dy, iters: int = 5):
+    """The Wgrad operands' quantize calls with the rotation sizes the paper ablates (Sec. 4.2 "Hadamard matrix size",
+    App. E.4) beside its choice d = 16.  Outside the timed region of `value`."""
+    RC = nv.LAYOUT_ROW | nv.LAYOUT_COL
+    qx = nv.alloc_qtensor(TOKENS, D_MODEL, RC)
+    qdy = nv.alloc_qtensor(TOKENS, D_FFN, RC)
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    res = {}
+    for d in (2, 4, 16, 32, 128):
+        tx = tg = 0.0
+        for it in range(iters + 1):
+            m = [ev() for _ in range(3)]
+            m[0].record()
+            nv.nvfp4_quantize(x, RC, nv.BLOCK_1x16, nv.ROUND_RNE, d, 2025, 0, out=qx)
+            m[1].record()
+            nv.nvfp4_quantize(dy, RC, nv.BLOCK_1x16, nv.ROUND_SR, d, 2025, 77 + it, out=qdy)
+            m[2].record()
+            torch.cuda.synchronize()
+            if it:
+                tx += m[0].elapsed_time(m[1])
+                tg += m[1].elapsed_time(m[2])
+        res[f"d{d}"] = {"X_ms": tx / iters, "dY_ms": tg / iters,
+                        "GBps_one_pass_accounting": (quant_bytes(TOKENS * D_MODEL, 2) + quant_bytes(TOKENS * D_FFN, 2))
+                                                    / ((tx + tg) / iters * 1e-3) / 1e9}
+    res["note"] = ("not part of `value`: nvfp4_quantize of X (RNE) and dY (SR), row + rotated col copy, per rotation size; "
+                   "d <= 16 rotate inside a lane's 16 rows, d = 32 / 128 exchange through LDS")
+    return res
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -141,6 +170,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-mxfp4", action="store_true", help="skip the MXFP4 comparison block")
+    ap.add_argument("--no-rht-sweep", action="store_true", help="skip the rotation-size block")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1",
@@ -259,6 +289,8 @@ def main() -> int:
     }
     if not args.no_mxfp4:
         out["mxfp4_comparison"] = mxfp4_comparison(torch, nv, x, w, dy)
+    if not args.no_rht_sweep:
+        out["rht_size_sweep"] = rht_size_sweep(torch, nv, x, dy)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(torch, nv, x, w)
     print(json.dumps(out))

@@ -148,7 +148,9 @@ __global__ __launch_bounds__(kThreads, 2) void cast_kernel(
 #pragma unroll
       for (int t = 0; t < 4; ++t) {
         float lo[16], hi[16];
-        signed_column_pair(p, t, kRht ? sign_mask : 0u, lo, hi);
+        // Without a rotation sign_mask is 0 at run time; it is still applied, so that these values are not
+        // recognised as the row pass's: keeping all 128 of those alive costs more registers than there are.
+        signed_column_pair(p, t, sign_mask, lo, hi);
         if (kRht) {
           butterfly_rows<kRht>(lo);
           butterfly_rows<kRht>(hi);

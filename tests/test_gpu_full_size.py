@@ -149,6 +149,22 @@ def test_config5_quantize_sweep(name, mode):
     assert_copy(q.col_codes, q.col_scales, q.col_ts, col, f"{name} col copy")
 
 
+@pytest.mark.parametrize("name,d,rounding", [("activation", 4, nv.ROUND_RNE), ("activation", 32, nv.ROUND_RNE),
+                                             ("gradient", 128, nv.ROUND_SR)])
+def test_other_rotation_sizes_at_full_size(name, d, rounding):
+    """The Wgrad copies of the 12B shapes with the rotation sizes ablated in Sec. 4.2 / App. E.4."""
+    rows, cols, seed = {"activation": (8192, 5120, 511), "gradient": (8192, 20480, 512)}[name]
+    xb = synth.student_t3(rows, cols, 0.02, seed)
+    q = nv.nvfp4_quantize(to_dev(xb), nv.LAYOUT_ROW | nv.LAYOUT_COL, rounding=rounding, rht_on_col=d, rht_seed=RHT_SEED,
+                          sr_seed=SR_SEED)
+    orr = oracle.SR if rounding == nv.ROUND_SR else oracle.RNE
+    row = oracle.quantize(xb, oracle.ROW, oracle.BLOCK_1x16, orr, False, 0, SR_SEED)
+    assert_copy(q.row_codes, q.row_scales, q.row_ts, row, f"{name} d={d} row copy")
+    del row
+    col = oracle.quantize(xb, oracle.COL, oracle.BLOCK_1x16, orr, True, RHT_SEED, SR_SEED, rht_dim=d)
+    assert_copy(q.col_codes, q.col_scales, q.col_ts, col, f"{name} d={d} col copy")
+
+
 def test_indexing_beyond_2_31_elements():
     """A tensor of 2^31 + 2^27 elements (4.5 GB of bf16): the small tensor it is tiled from fixes the expected
     bytes, since tiling by whole 16-row groups changes neither the amax nor any block (RNE)."""
