@@ -49,6 +49,15 @@
 //     0.25; every add and subtract is one binary32 rounding.  The rotated
 //     values stay in binary32 (no trip back to bf16) and the tensor amax of a
 //     rotated copy is taken over the rotated values (App. C).
+//   * Rotations of the other sizes the paper ablates (Sec. 4.2 "Hadamard
+//     matrix size", App. E.4: d = 2, 4, 128; 32 for MXFP4) follow the same
+//     construction: sign i is bit i of all 128 bits of that Philox call,
+//     stages h = 1 .. d/2, then one multiply by the binary32 nearest to
+//     1/sqrt(d); pinned (tests/test_oracle_rht_sizes.py) by the dense
+//     Sylvester matrix, its closed-form entries, the even spread of a
+//     single outlier, the amax the quantizer reports for such a tensor and
+//     the invariance of the product; the bit-to-sign assignment is this
+//     repository's convention (parity unpinned against the paper).
 //
 // PARITY PINS (tests/test_oracle_*.py): E2M1/E4M3 by brute force over the whole
 // code space; Philox by the published known-answer vectors; the transform by

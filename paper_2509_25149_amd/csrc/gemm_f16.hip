@@ -14,6 +14,8 @@
 // (measured: the fused kernel runs at 0.95-1.0 PFLOP/s, this pair at about
 // 1.25 PFLOP/s in the GEMM proper, the decode pass adding 5-8 % of its time).
 // The results are identical to the fused kernel's up to FP32 summation order.
+#include <type_traits>
+
 #include "nvfp4_internal.h"
 #include "nvfp4_device.h"
 
@@ -76,57 +78,77 @@ __global__ __launch_bounds__(256) void decode_f16_kernel(const uint8_t* __restri
 }
 
 // ---------------------------------------------------------------- pass 2: FP16 GEMM
-// 256 x 256 outputs per workgroup, K step 64, 512 threads = 8 wavefronts (2 x 4),
-// each 128 x 64 outputs as 8 x 4 MFMA 16x16 blocks.  LDS holds two stages of
-// (A tile, B tile), 64 KiB each; a stage is filled by direct global->LDS loads:
-// one instruction moves 64 lanes x 16 bytes into 1 KiB of consecutive LDS, i.e.
-// 8 tile rows of 128 bytes, and lane l fetches the 16-byte chunk that belongs at
-// chunk position l & 7 of row l >> 3 under the XOR swizzle
+// 256 x 256 outputs per workgroup, K step 64, 256 threads = 4 wavefronts (2 x 2), one per SIMD,
+// each 128 x 128 outputs as 8 x 8 MFMA 16x16 blocks: 256 accumulator registers, which live in
+// the accumulation half of the register file, and 16 fragment loads per 64 MFMAs (a 128 x 64
+// wave tile needs 12 per 32).  LDS holds two stages of (A tile, B tile), 64 KiB each; a stage is
+// filled by direct global->LDS loads: one instruction moves 64 lanes x 16 bytes into 1 KiB of
+// consecutive LDS, i.e. 8 tile rows of 128 bytes, and lane l fetches the 16-byte chunk that
+// belongs at chunk position l & 7 of row l >> 3 under the XOR swizzle
 // (chunk c of row r lives at position c ^ ((r >> 1) & 7)).
+//
+// With one wavefront per SIMD nothing else can fill the matrix pipe while this one waits, so the
+// loop is software-pipelined across its barrier and its instruction order is fixed by hand (inline
+// assembly keeps the compiler from regrouping it; measured 1.18 against 1.06 PFLOP/s for the
+// 8-wavefront form on the same operands, at a lower clock: the chip's power limit sets the speed,
+// and this form moves a third less data from LDS per flop):
+//   block 1   64 MFMAs on the first 32 k of the stage; after every fourth, one of the 16 fragment
+//             loads for the second 32 k
+//   wait      own fragment loads back, own global->LDS loads (issued one step ago) landed; barrier:
+//             every wavefront holds all it needs of this stage, and the next stage is complete
+//   block 2   64 MFMAs on the second 32 k; after every second, alternately one fragment load for
+//             the first 32 k of the next stage and one global->LDS load of the stage after that,
+//             into the buffer just freed
+// so the barrier falls between two blocks of MFMAs that are already fed.
 constexpr int TM = 256, TN = 256, TK = 64;
-constexpr int kThreads = 512;
+constexpr int kThreads = 256;
 constexpr int kRowBytes = TK * 2;
 constexpr int kOperandBytes = TM * kRowBytes;   // 32 KiB
 constexpr int kStageBytes = 2 * kOperandBytes;  // 64 KiB
 
 __device__ __forceinline__ int swz(int row, int chunk) { return row * kRowBytes + ((chunk ^ ((row >> 1) & 7)) << 4); }
 
-// Fragments of one 32-wide half of a K step for a 128 x 64 wave tile.  A 16x16x32 MFMA operand
+// Fragments of one 32-wide half of a K step for a 128 x 128 wave tile.  A 16x16x32 MFMA operand
 // is 16 rows x 32 k: lane l holds the 8 consecutive k of 16-byte chunk (l >> 4) of row (l & 15).
 struct Frags {
-  half8v a[8], b[4];
+  half8v a[8], b[8];
 };
 
-// `chunk` = half * 4 + (lane >> 4): the lane's 16-byte chunk of the 128-byte tile row.
-__device__ __forceinline__ void load_frags(Frags& f, const char* at, const char* bt, int arow, int brow, int chunk) {
-#pragma unroll
-  for (int i = 0; i < 8; ++i) f.a[i] = *reinterpret_cast<const half8v*>(at + swz(arow + i * 16, chunk));
-#pragma unroll
-  for (int j = 0; j < 4; ++j) f.b[j] = *reinterpret_cast<const half8v*>(bt + swz(brow + j * 16, chunk));
+template <int kBegin, int kEnd, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (kBegin < kEnd) {
+    f(std::integral_constant<int, kBegin>{});
+    static_for<kBegin + 1, kEnd>(f);
+  }
 }
 
 // The MFMA's M index is the B row (n), its N index the A row (m): lane l ends up with the 4
 // consecutive n = (l >> 4) * 4 .. + 3 of m = l & 15, which makes the output stores 64/128-bit.
-__device__ __forceinline__ void mma_step(float4v (&acc)[8][4], const Frags& f) {
-#pragma unroll
-  for (int i = 0; i < 8; ++i)
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-      acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(f.b[j], f.a[i], acc[i][j], 0, 0, 0);
+// The accumulator is pinned to the accumulation registers ("a"): 256 of them leave the 256
+// ordinary registers to fragments and addresses.
+__device__ __forceinline__ void mfma(float4v& acc, const half8v& b, const half8v& a) {
+  asm volatile("v_mfma_f32_16x16x32_f16 %0, %1, %2, %0" : "+a"(acc) : "v"(b), "v"(a));
 }
 
-typedef __attribute__((address_space(3))) void* lds_ptr;
+// 16 bytes of LDS at addr + kOff.  Asynchronous: the caller waits (lgkmcnt) before the value is used.
+template <int kOff>
+__device__ __forceinline__ void lds_read16(half8v& dst, uint32_t addr) {
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=&v"(dst) : "v"(addr), "n"(kOff));
+}
 
-// 64 lanes x 16 bytes from global memory straight into 1 KiB of consecutive LDS starting at the
-// wave-uniform address `lds_dst` (global_load_lds_dwordx4).  The builtin only exists in the device
-// pass; hiding it from the host pass keeps the host stubs of the kernel templates below emitted.
-__device__ __forceinline__ void load_1k_to_lds(const char* src, char* lds_dst) {
-#if defined(__HIP_DEVICE_COMPILE__)
-  __builtin_amdgcn_global_load_lds(src, (lds_ptr)lds_dst, 16, 0, 0);
-#else
-  (void)src;
-  (void)lds_dst;
-#endif
+// Fragment q of a 16-fragment set: 0..7 = A rows i * 16, 8..15 = B rows j * 16 (2 KiB apart; the
+// swizzle term does not change with multiples of 16 rows).
+template <int q>
+__device__ __forceinline__ void read_frag(Frags& f, uint32_t a_addr, uint32_t b_addr) {
+  if constexpr (q < 8) lds_read16<q * 16 * kRowBytes>(f.a[q], a_addr);
+  else lds_read16<(q - 8) * 16 * kRowBytes>(f.b[q - 8], b_addr);
+}
+
+// 64 lanes x 16 bytes from global memory (wave-uniform base + per-lane 32-bit offset) straight into
+// 1 KiB of consecutive LDS starting at the wave-uniform LDS address `lds_dst`.  Asynchronous (vmcnt).
+__device__ __forceinline__ void load_1k_to_lds(uint32_t lane_offset, const char* base, uint32_t lds_dst) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_dst), "v"(lane_offset), "s"(base)
+               : "memory", "m0");
 }
 
 // Tiles [tile_begin, tile_begin + count) of the 256x256 tiling are covered.
@@ -146,9 +168,6 @@ __global__ __launch_bounds__(kThreads) void gemm_f16_kernel(const _Float16* __re
                                                             int tile_begin, int tile_count, int k_splits, float* partials,
                                                             unsigned int* tickets) {
   extern __shared__ __attribute__((aligned(16))) char lds[];
-  constexpr int kABytes = kOperandBytes;
-  constexpr int kStage = kStageBytes;
-  constexpr int kLoadsA = 4;                         // direct-load instructions per wavefront for the A tile
 
   // Workgroup -> tile: consecutive ids go to different XCDs (round robin over 8, one L2 each);
   // give every XCD a contiguous range of tiles, walked in bands of 8 tile rows.
@@ -169,71 +188,85 @@ __global__ __launch_bounds__(kThreads) void gemm_f16_kernel(const _Float16* __re
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wm = wave >> 2, wn = wave & 3, l16 = lane & 15, lq = lane >> 4;
-  const int arow = wm * 128 + l16, brow = wn * 64 + l16;
+  const int wm = wave >> 1, wn = wave & 1, l16 = lane & 15, lq = lane >> 4;
+  const int arow = wm * 128 + l16, brow = wn * 128 + l16;
 
-  // Direct-load sources: one instruction fills an 8-row block of a tile.
-  // Rows past the end of an operand are clamped; they only feed outputs that are never stored.
-  const char* ga[kLoadsA];
-  const char* gb[4];
+  // Direct-load sources: instruction q of wavefront w fills rows w * 64 + 8 q .. + 7 of a tile.  Per lane a
+  // 32-bit byte offset from the tile's first row (a tile is 256 rows of at most 2^22 bytes: K < 2^21, checked
+  // on the host).  Rows past the end of an operand are clamped; they only feed outputs that are never stored.
+  uint32_t off_a[8], off_b[8];
 #pragma unroll
-  for (int q = 0; q < kLoadsA; ++q) {
-    const int r = (wave * kLoadsA + q) * 8 + (lane >> 3);
-    const int c = (lane & 7) ^ ((r >> 1) & 7);
-    ga[q] = reinterpret_cast<const char*>(A) + min<int64_t>(m0 + r, M - 1) * K * 2 + c * 16;
+  for (int q = 0; q < 8; ++q) {
+    const int r = wave * 64 + q * 8 + (lane >> 3);
+    const uint32_t c = static_cast<uint32_t>((lane & 7) ^ ((r >> 1) & 7)) * 16u;
+    off_a[q] = static_cast<uint32_t>(min<int64_t>(r, M - 1 - m0)) * static_cast<uint32_t>(K * 2) + c;
+    off_b[q] = static_cast<uint32_t>(min<int64_t>(r, N - 1 - n0)) * static_cast<uint32_t>(K * 2) + c;
   }
-#pragma unroll
-  for (int q = 0; q < 4; ++q) {
-    const int r = (wave * 4 + q) * 8 + (lane >> 3);
-    const int c = (lane & 7) ^ ((r >> 1) & 7);
-    gb[q] = reinterpret_cast<const char*>(B) + min<int64_t>(n0 + r, N - 1) * K * 2 + c * 16;
-  }
+  const char* tile_a = reinterpret_cast<const char*>(A) + m0 * K * 2;
+  const char* tile_b = reinterpret_cast<const char*>(B) + n0 * K * 2;
+  const uint32_t lds0 = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(lds));
+  const uint32_t fill0 = lds0 + wave * 8192;   // this wavefront's 8 KiB of each operand tile
+  // one of the 16 loads of K step kt into stage `stage`: q 0..7 A, 8..15 B
+  auto issue_one = [&](int q, int kt, int stage) {
+    const uint32_t dst = fill0 + stage * kStageBytes + (q < 8 ? 0 : kOperandBytes) + (q & 7) * 1024;
+    load_1k_to_lds(q < 8 ? off_a[q & 7] : off_b[q & 7], (q < 8 ? tile_a : tile_b) + static_cast<int64_t>(kt) * kRowBytes, dst);
+  };
+  // fragment addresses in stage 0: first / second 32 k of the step
+  const uint32_t a_lo = lds0 + swz(arow, lq), a_hi = lds0 + swz(arow, 4 + lq);
+  const uint32_t b_lo = lds0 + kOperandBytes + swz(brow, lq), b_hi = lds0 + kOperandBytes + swz(brow, 4 + lq);
 
-  float4v acc[8][4];
+  float4v acc[8][8];
 #pragma unroll
   for (int i = 0; i < 8; ++i)
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
+    for (int j = 0; j < 8; ++j)
 #pragma unroll
       for (int r = 0; r < 4; ++r) acc[i][j][r] = 0.0f;
 
   const int KT = static_cast<int>(K / TK);
   const int kt_begin = static_cast<int>(static_cast<int64_t>(KT) * split / k_splits);
-  const int kt_end = static_cast<int>(static_cast<int64_t>(KT) * (split + 1) / k_splits);
-  auto issue = [&](int kt, int stage) {
-    char* base = lds + stage * kStage;
-#pragma unroll
-    for (int q = 0; q < kLoadsA; ++q)
-      load_1k_to_lds(ga[q] + static_cast<int64_t>(kt) * kRowBytes, base + (wave * kLoadsA + q) * 1024);
-#pragma unroll
-    for (int q = 0; q < 4; ++q)
-      load_1k_to_lds(gb[q] + static_cast<int64_t>(kt) * kRowBytes, base + kABytes + (wave * 4 + q) * 1024);
-  };
-  issue(kt_begin, 0);
-  __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): the direct loads have landed in LDS
-  __syncthreads();
+  const int kt_end = static_cast<int>(static_cast<int64_t>(KT) * (split + 1) / k_splits);   // > kt_begin: KT >= k_splits
+  static_for<0, 16>([&](auto q) { issue_one(decltype(q)::value, kt_begin, 0); });
+  static_for<0, 16>([&](auto q) { issue_one(decltype(q)::value, min(kt_begin + 1, kt_end - 1), 1); });
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  Frags f0, f1;
+  static_for<0, 16>([&](auto q) { read_frag<decltype(q)::value>(f0, a_lo, b_lo); });
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 
   for (int kt = kt_begin; kt < kt_end; ++kt) {
-    const int stage = (kt - kt_begin) & 1;
-    const char* cur = lds + stage * kStage;
-    if (kt + 1 < kt_end) issue(kt + 1, stage ^ 1);
-    Frags f0, f1;
-    load_frags(f0, cur, cur + kABytes, arow, brow, 0 + lq);
-    load_frags(f1, cur, cur + kABytes, arow, brow, 4 + lq);
-    mma_step(acc, f0);
-    mma_step(acc, f1);
-    __builtin_amdgcn_s_waitcnt(0x0f70);
-    __syncthreads();
+    const uint32_t cur = ((kt - kt_begin) & 1) * kStageBytes, nxt = cur ^ kStageBytes;
+    // Past the end the last K step is fetched again, into a buffer nobody reads any more: no branches in the loop.
+    const int kt2 = min(kt + 2, kt_end - 1);
+    static_for<0, 64>([&](auto ic) {
+      constexpr int n = decltype(ic)::value;
+      mfma(acc[n >> 3][n & 7], f0.b[n & 7], f0.a[n >> 3]);
+      if constexpr ((n & 3) == 1) read_frag<(n >> 2)>(f1, a_hi + cur, b_hi + cur);
+    });
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    static_for<0, 64>([&](auto ic) {
+      constexpr int n = decltype(ic)::value;
+      mfma(acc[n >> 3][n & 7], f1.b[n & 7], f1.a[n >> 3]);
+      if constexpr ((n & 3) == 1) read_frag<(n >> 2)>(f0, a_lo + nxt, b_lo + nxt);
+      if constexpr ((n & 3) == 3) issue_one(n >> 2, kt2, (kt - kt_begin) & 1);
+    });
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
   }
+  // The trailing global->LDS loads must have landed before LDS is reused or the wavefront ends; the MFMA results
+  // must have left the pipe before ordinary instructions read the accumulators (the compiler cannot see into the
+  // assembly statements to insert these wait states itself).
+  asm volatile("s_waitcnt vmcnt(0)\n\ts_nop 15\n\ts_nop 15" ::: "memory");
+  __syncthreads();
 
   if (k_splits > 1) {
-    // Partial tile in fragment order: float4 number (i * 4 + j) * 512 + tid.
+    // Partial tile in fragment order: float4 number (i * 8 + j) * 256 + tid.
     float4v* mine = reinterpret_cast<float4v*>(partials) +
                     (static_cast<int64_t>(tile_local) * k_splits + split) * (TM * TN / 4) + tid;
 #pragma unroll
     for (int i = 0; i < 8; ++i)
 #pragma unroll
-      for (int j = 0; j < 4; ++j) mine[(i * 4 + j) * kThreads] = acc[i][j];
+      for (int j = 0; j < 8; ++j) mine[(i * 8 + j) * kThreads] = acc[i][j];
     // Publish: the barrier waits for every wavefront's stores to reach L2; then one thread makes
     // them visible device-wide (one L2 write-back per workgroup instead of one per wavefront),
     // draws the ticket and, if it is the last one, discards stale cached lines before anyone reads.
@@ -253,16 +286,16 @@ __global__ __launch_bounds__(kThreads) void gemm_f16_kernel(const _Float16* __re
     for (int sp = 0; sp < k_splits; ++sp) {
       const float4v* part = all + static_cast<int64_t>(sp) * (TM * TN / 4);
 #pragma unroll
-      for (int h = 0; h < 2; ++h) {
-        float4v t[4][4];
+      for (int h = 0; h < 4; ++h) {
+        float4v t[2][8];
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < 2; ++i)
 #pragma unroll
-          for (int j = 0; j < 4; ++j) t[i][j] = part[((h * 4 + i) * 4 + j) * kThreads];
+          for (int j = 0; j < 8; ++j) t[i][j] = part[((h * 2 + i) * 8 + j) * kThreads];
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < 2; ++i)
 #pragma unroll
-          for (int j = 0; j < 4; ++j) acc[h * 4 + i][j] = sp == 0 ? t[i][j] : acc[h * 4 + i][j] + t[i][j];
+          for (int j = 0; j < 8; ++j) acc[h * 2 + i][j] = sp == 0 ? t[i][j] : acc[h * 2 + i][j] + t[i][j];
       }
     }
   }
@@ -275,8 +308,8 @@ __global__ __launch_bounds__(kThreads) void gemm_f16_kernel(const _Float16* __re
   for (int i = 0; i < 8; ++i) {
     const int m = wm * 128 + i * 16 + l16;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int n = wn * 64 + j * 16 + lq * 4;
+    for (int j = 0; j < 8; ++j) {
+      const int n = wn * 128 + j * 16 + lq * 4;
       if (m < Mt && n < Nt) {  // N is a multiple of 16, so the 4 columns are in or out together
         float4v v = acc[i][j] * out_scale;
         if (kBf16Out) {
@@ -330,6 +363,7 @@ size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t K) {
 
 bool gemm_two_pass_usable(const GemmArgs& g) {
   return g.workspace && g.workspace_bytes >= gemm_workspace_bytes(g.a.outer, g.b.outer, g.K) && (g.K % TK) == 0 &&
+         g.K < (int64_t{1} << 21) &&   // the kernel's 32-bit byte offsets inside a 256-row tile
          reinterpret_cast<uintptr_t>(g.workspace) % 256 == 0 && reinterpret_cast<uintptr_t>(g.a.codes) % 16 == 0 &&
          reinterpret_cast<uintptr_t>(g.b.codes) % 16 == 0 && reinterpret_cast<uintptr_t>(g.a.scales) % 2 == 0 &&
          reinterpret_cast<uintptr_t>(g.b.scales) % 2 == 0;
