@@ -18,6 +18,7 @@
 
 #include "nvfp4_internal.h"
 #include "nvfp4_device.h"
+#include "gemm_epilogue.h"
 
 namespace nvfp4 {
 
@@ -105,6 +106,7 @@ constexpr int kThreads = 256;
 constexpr int kRowBytes = TK * 2;
 constexpr int kOperandBytes = TM * kRowBytes;   // 32 KiB
 constexpr int kStageBytes = 2 * kOperandBytes;  // 64 KiB
+constexpr int kLdsBytes = 2 * kStageBytes;
 
 __device__ __forceinline__ int swz(int row, int chunk) { return row * kRowBytes + ((chunk ^ ((row >> 1) & 7)) << 4); }
 
@@ -191,25 +193,30 @@ __global__ __launch_bounds__(kThreads) void gemm_f16_kernel(const _Float16* __re
   const int wm = wave >> 1, wn = wave & 1, l16 = lane & 15, lq = lane >> 4;
   const int arow = wm * 128 + l16, brow = wn * 128 + l16;
 
-  // Direct-load sources: instruction q of wavefront w fills rows w * 64 + 8 q .. + 7 of a tile.  Per lane a
-  // 32-bit byte offset from the tile's first row (a tile is 256 rows of at most 2^22 bytes: K < 2^21, checked
-  // on the host).  Rows past the end of an operand are clamped; they only feed outputs that are never stored.
-  uint32_t off_a[8], off_b[8];
+  // Direct-load sources: instruction q of wavefront w fills rows w * 64 + 8 q .. + 7 of a tile (lane -> row lane / 8,
+  // position lane % 8, i.e. chunk (lane % 8) ^ ((row >> 1) & 7); adding 8 q to the row leaves that term alone for even
+  // q and flips its bit 2 for odd q).  Wave-uniform 64-bit base per 8-row block + one per-lane 32-bit offset for
+  // even and one for odd q, shared by both operands (8 rows of K * 2 bytes: K < 2^21, checked on the host).  A block
+  // past the end of an operand is replaced by the operand's last block (rows come in multiples of 16); it only
+  // feeds outputs that are never stored.
+  const int r0 = wave * 64 + (lane >> 3);
+  const uint32_t c0 = static_cast<uint32_t>((lane & 7) ^ ((r0 >> 1) & 7)) * 16u;
+  const uint32_t off_even = static_cast<uint32_t>(lane >> 3) * static_cast<uint32_t>(K * 2) + c0;
+  const uint32_t off_odd = static_cast<uint32_t>(lane >> 3) * static_cast<uint32_t>(K * 2) + (c0 ^ 64u);
+  const char* blk_a[8];
+  const char* blk_b[8];
 #pragma unroll
   for (int q = 0; q < 8; ++q) {
-    const int r = wave * 64 + q * 8 + (lane >> 3);
-    const uint32_t c = static_cast<uint32_t>((lane & 7) ^ ((r >> 1) & 7)) * 16u;
-    off_a[q] = static_cast<uint32_t>(min<int64_t>(r, M - 1 - m0)) * static_cast<uint32_t>(K * 2) + c;
-    off_b[q] = static_cast<uint32_t>(min<int64_t>(r, N - 1 - n0)) * static_cast<uint32_t>(K * 2) + c;
+    const int64_t r = wave * 64 + q * 8;
+    blk_a[q] = reinterpret_cast<const char*>(A) + (m0 + min<int64_t>(r, M - 8 - m0)) * K * 2;
+    blk_b[q] = reinterpret_cast<const char*>(B) + (n0 + min<int64_t>(r, N - 8 - n0)) * K * 2;
   }
-  const char* tile_a = reinterpret_cast<const char*>(A) + m0 * K * 2;
-  const char* tile_b = reinterpret_cast<const char*>(B) + n0 * K * 2;
   const uint32_t lds0 = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(lds));
   const uint32_t fill0 = lds0 + wave * 8192;   // this wavefront's 8 KiB of each operand tile
   // one of the 16 loads of K step kt into stage `stage`: q 0..7 A, 8..15 B
   auto issue_one = [&](int q, int kt, int stage) {
     const uint32_t dst = fill0 + stage * kStageBytes + (q < 8 ? 0 : kOperandBytes) + (q & 7) * 1024;
-    load_1k_to_lds(q < 8 ? off_a[q & 7] : off_b[q & 7], (q < 8 ? tile_a : tile_b) + static_cast<int64_t>(kt) * kRowBytes, dst);
+    load_1k_to_lds((q & 1) ? off_odd : off_even, (q < 8 ? blk_a[q & 7] : blk_b[q & 7]) + static_cast<int64_t>(kt) * kRowBytes, dst);
   };
   // fragment addresses in stage 0: first / second 32 k of the step
   const uint32_t a_lo = lds0 + swz(arow, lq), a_hi = lds0 + swz(arow, 4 + lq);
@@ -304,28 +311,8 @@ __global__ __launch_bounds__(kThreads) void gemm_f16_kernel(const _Float16* __re
   const float out_scale = a_ts[0] * b_ts[0];
   const int Mt = static_cast<int>(M - m0 < TM ? M - m0 : TM);
   const int Nt = static_cast<int>(N - n0 < TN ? N - n0 : TN);
-#pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    const int m = wm * 128 + i * 16 + l16;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      const int n = wn * 128 + j * 16 + lq * 4;
-      if (m < Mt && n < Nt) {  // N is a multiple of 16, so the 4 columns are in or out together
-        float4v v = acc[i][j] * out_scale;
-        if (kBf16Out) {
-          uint16_t* d = static_cast<uint16_t*>(Dv) + (m0 + m) * ldd + n0 + n;
-          uint2 o;
-          o.x = f32_to_bf16(v[0]) | (f32_to_bf16(v[1]) << 16);
-          o.y = f32_to_bf16(v[2]) | (f32_to_bf16(v[3]) << 16);
-          *reinterpret_cast<uint2*>(d) = o;
-        } else {
-          float* d = static_cast<float*>(Dv) + (m0 + m) * ldd + n0 + n;
-          if (accumulate) v += *reinterpret_cast<const float4v*>(d);
-          *reinterpret_cast<float4v*>(d) = v;
-        }
-      }
-    }
-  }
+  store_wave_block<kBf16Out>(acc, out_scale, Dv, ldd, accumulate, m0 + wm * 128, n0 + wn * 128, Mt - wm * 128, Nt - wn * 128,
+                             lane);
 }
 
 }  // namespace
@@ -374,11 +361,11 @@ bool gemm_two_pass_usable(const GemmArgs& g) {
     static bool attr_set = false;                                                                                 \
     if (!attr_set) {                                                                                              \
       hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_f16_kernel<BF16>),                   \
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, 2 * kStageBytes);            \
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);            \
       if (e != hipSuccess) return e;                                                                              \
       attr_set = true;                                                                                            \
     }                                                                                                             \
-    hipLaunchKernelGGL((gemm_f16_kernel<BF16>), dim3(wgs), dim3(kThreads), 2 * kStageBytes, s, a16, b16,          \
+    hipLaunchKernelGGL((gemm_f16_kernel<BF16>), dim3(wgs), dim3(kThreads), kLdsBytes, s, a16, b16,                   \
                        g.a.outer, g.b.outer, g.K, g.a.ts, g.b.ts, g.d, g.ldd, g.accumulate, tiles_m, tiles_n,     \
                        tile_begin, tile_count, k_splits, partials, tickets);                                      \
   } while (0)

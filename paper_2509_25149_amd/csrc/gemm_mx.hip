@@ -11,56 +11,131 @@
 // plus that block's scale byte; the 16x16 result puts D[(l >> 4) * 4 + i][l & 15]
 // in register i of lane l, rows taken from the first operand.
 //
-// 256 x 256 outputs per workgroup, K step 128 (one instruction deep), 512 threads
-// = 8 wavefronts (2 x 4) of 128 x 64.  LDS holds four stages of (A codes, B codes,
-// A scales, B scales) = 34 KiB each (two K steps per barrier), filled by direct global->LDS loads: a code
-// row of a stage is 64 bytes, so 16 consecutive tile rows are 1 KiB of LDS and a
+// 256 x 256 outputs per workgroup, K step 128 (one instruction deep), 256 threads = 4 wavefronts
+// (2 x 2), one per SIMD, of 128 x 128 outputs each: 8 x 8 instructions per K step, 256 accumulator
+// registers in the accumulation half of the register file.  LDS holds two buffers of two K steps,
+// a step being (A codes, B codes, A scales, B scales) = 34 KiB, filled by direct global->LDS
+// loads: a code row of a step is 64 bytes, so 16 consecutive tile rows are 1 KiB of LDS and a
 // fragment read (16 rows x 4 blocks x 16 bytes) is one contiguous KiB.
+//
+// With one wavefront per SIMD nothing else can fill the matrix pipe while this one waits, so the
+// loop is software-pipelined across its barrier and its instruction order is fixed by hand (inline
+// assembly; the compiler would regroup it).  One iteration = the two K steps of a buffer:
+//   block 1   64 MFMAs on the first step; behind them the 24 fragment reads of the second
+//   wait      own reads back, own global->LDS loads (issued one iteration ago) landed; barrier:
+//             every wavefront holds all it needs of this buffer, and the other buffer is complete
+//   block 2   64 MFMAs on the second step; behind them the reads for the first step of the
+//             other buffer and the 20 loads that refill this one with the steps after that
+#include <type_traits>
+
 #include "nvfp4_internal.h"
 #include "nvfp4_device.h"
+#include "gemm_epilogue.h"
 
 namespace nvfp4 {
 
 namespace {
 
 constexpr int TM = 256, TN = 256, TK = 128;
-constexpr int kThreads = 512;
+constexpr int kThreads = 256;
 constexpr int kCodeRowBytes = TK / 2;                 // 64
 constexpr int kCodeBytes = TM * kCodeRowBytes;        // 16 KiB per operand
 constexpr int kScaleBytes = TM * (TK / 32);           // 1 KiB per operand
-constexpr int kStageBytes = 2 * kCodeBytes + 2 * kScaleBytes;
+constexpr int kStepBytes = 2 * kCodeBytes + 2 * kScaleBytes;   // 34 KiB
+constexpr int kLdsBytes = 4 * kStepBytes;
 
-typedef int int8v __attribute__((ext_vector_type(8)));
-typedef __attribute__((address_space(3))) void* lds_ptr;
+typedef int int4v __attribute__((ext_vector_type(4)));
 
-// 64 lanes x 16 (or 4) bytes from global memory straight into consecutive LDS at the wave-uniform
-// LDS byte offset lds_off (global_load_lds_*; M0 carries the LDS address).  Inline assembly on
-// purpose: for the builtin form the compiler makes every later LDS read wait for all direct loads
-// in flight (it cannot tell the stages apart), which serialises the prefetch of the next stages
-// with the reads of the current one.  The loop keeps them apart itself: s_waitcnt vmcnt(0) and a
-// barrier stand between a stage's loads and its first read.
-__device__ __forceinline__ void load16_to_lds(const uint8_t* src, uint32_t lds_off) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_off), "v"(src) : "memory", "m0");
-}
-__device__ __forceinline__ void load4_to_lds(const uint8_t* src, uint32_t lds_off) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, off" : : "s"(lds_off), "v"(src) : "memory", "m0");
+template <int kBegin, int kEnd, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (kBegin < kEnd) {
+    f(std::integral_constant<int, kBegin>{});
+    static_for<kBegin + 1, kEnd>(f);
+  }
 }
 
-// One operand fragment: the low four dwords are the 32 codes of the lane's block; the
-// instruction ignores the rest of the 256-bit operand for FP4, so it is left undefined.
-__device__ __forceinline__ int8v load_frag(const char* codes, int row, int kb) {
-  const uint4 q = *reinterpret_cast<const uint4*>(codes + row * kCodeRowBytes + kb * 16);
-  int8v f;
-  f[0] = static_cast<int>(q.x);
-  f[1] = static_cast<int>(q.y);
-  f[2] = static_cast<int>(q.z);
-  f[3] = static_cast<int>(q.w);
-  return f;
+// 64 lanes x 16 (or 4) bytes from global memory (wave-uniform base + per-lane 32-bit offset) straight
+// into consecutive LDS at the wave-uniform LDS address lds_dst (M0 carries it).  Asynchronous (vmcnt).
+__device__ __forceinline__ void load16_to_lds(uint32_t lane_offset, const uint8_t* base, uint32_t lds_dst) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_dst), "v"(lane_offset), "s"(base)
+               : "memory", "m0");
+}
+__device__ __forceinline__ void load4_to_lds(uint32_t lane_offset, const uint8_t* base, uint32_t lds_dst) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2" ::"s"(lds_dst), "v"(lane_offset), "s"(base)
+               : "memory", "m0");
+}
+
+// LDS reads; asynchronous, the caller waits (lgkmcnt) before the values are used.
+template <int kOff>
+__device__ __forceinline__ void lds_read16(int4v& dst, uint32_t addr) {
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=&v"(dst) : "v"(addr), "n"(kOff));
+}
+typedef int int2v __attribute__((ext_vector_type(2)));
+// two dwords, kOff0 and kOff1 dwords past addr
+template <int kOff0, int kOff1>
+__device__ __forceinline__ void lds_read_2x4(int2v& dst, uint32_t addr) {
+  asm volatile("ds_read2_b32 %0, %1 offset0:%2 offset1:%3" : "=&v"(dst) : "v"(addr), "n"(kOff0), "n"(kOff1));
+}
+// byte k of the result = byte sel[k] of the eight bytes {hi, lo}; in assembly so that it stays behind the
+// wait for the LDS reads that produce its inputs (the compiler does not know those are asynchronous)
+__device__ __forceinline__ int perm_bytes(int hi, int lo, int sel) {
+  int d;
+  asm volatile("v_perm_b32 %0, %1, %2, %3" : "=v"(d) : "v"(hi), "v"(lo), "v"(sel));
+  return d;
+}
+
+// Fragments of one K step for a 128 x 128 wave tile: per 16-row block the lane's 32 codes (the
+// instruction's FP4 operand is four dwords) and its block's scale byte.  Single-byte LDS reads are slow
+// (measured: 16 of them per K step cost more than the 64 MFMAs), so the scales are read as the row's whole
+// dword (the step's four blocks) and the lane's own byte of four rows is gathered into one register (pa, pb);
+// the instruction then picks the row's byte with its op_sel field.
+constexpr int kFragReads = 24;
+struct Frags {
+  int4v a[8], b[8];
+  int pa[2], pb[2];     // byte t of pa[h] = this lane's scale of block 4h + t
+};
+// Raw scale dwords of 16-row blocks (2t, 2t + 1) between their read and the gather; one set serves both
+// fragment sets, whose reads never overlap (each set is gathered before the other's reads start).
+struct RawScales {
+  int2v a[4], b[4];
+};
+
+// Read number q of the 24 of a fragment set: 0..7 A codes, 8..15 B codes, 16..19 A scales, 20..23 B scales
+// (16-row blocks are 1 KiB of codes and 64 bytes = 16 dwords of scales apart).
+template <int q>
+__device__ __forceinline__ void read_frag(Frags& f, RawScales& r, uint32_t a_codes, uint32_t b_codes, uint32_t a_scales,
+                                          uint32_t b_scales) {
+  if constexpr (q < 8) lds_read16<q * 16 * kCodeRowBytes>(f.a[q], a_codes);
+  else if constexpr (q < 16) lds_read16<(q - 8) * 16 * kCodeRowBytes>(f.b[q - 8], b_codes);
+  else if constexpr (q < 20) lds_read_2x4<(q - 16) * 32, (q - 16) * 32 + 16>(r.a[q - 16], a_scales);
+  else lds_read_2x4<(q - 20) * 32, (q - 20) * 32 + 16>(r.b[q - 20], b_scales);
+}
+
+// After the reads are back: gather the lane's byte (sel01 = kb | (4 + kb) << 8 picks byte kb of two dwords).
+__device__ __forceinline__ void pack_scales(Frags& f, const RawScales& r, int sel01) {
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const int a01 = perm_bytes(r.a[2 * h][1], r.a[2 * h][0], sel01), a23 = perm_bytes(r.a[2 * h + 1][1], r.a[2 * h + 1][0], sel01);
+    f.pa[h] = perm_bytes(a23, a01, 0x05040100);
+    const int b01 = perm_bytes(r.b[2 * h][1], r.b[2 * h][0], sel01), b23 = perm_bytes(r.b[2 * h + 1][1], r.b[2 * h + 1][0], sel01);
+    f.pb[h] = perm_bytes(b23, b01, 0x05040100);
+  }
+}
+
+// The instruction's first operand supplies the rows of its result: passing B first leaves a lane with 4
+// consecutive n of one m, which makes the output stores 64/128-bit.  cbsz / blgp = 4: both operands FP4;
+// scale byte kSelB of sb and kSelA of sa (op_sel = the low bit, op_sel_hi = the high bit of the byte number).
+// The accumulator is pinned to the accumulation registers.
+template <int kSelB, int kSelA>
+__device__ __forceinline__ void mfma(float4v& acc, const int4v& b, const int4v& a, int sb, int sa) {
+  asm volatile("v_mfma_scale_f32_16x16x128_f8f6f4 %0, %1, %2, %0, %3, %4 op_sel:[%5,%6,0] op_sel_hi:[%7,%8,0] cbsz:4 blgp:4"
+               : "+a"(acc)
+               : "v"(b), "v"(a), "v"(sb), "v"(sa), "n"(kSelB & 1), "n"(kSelA & 1), "n"(kSelB >> 1), "n"(kSelA >> 1));
 }
 
 template <bool kBf16Out>
-__global__ __launch_bounds__(kThreads) void gemm_mx_kernel(Operand A, Operand B, int64_t K, void* __restrict__ Dv,
-                                                           int64_t ldd, bool accumulate, int tiles_m, int tiles_n) {
+__global__ __launch_bounds__(kThreads) void gemm_mx_kernel_any_k(Operand A, Operand B, int64_t K, void* __restrict__ Dv,
+                                                                 int64_t ldd, bool accumulate, int tiles_m, int tiles_n) {
   extern __shared__ __attribute__((aligned(16))) char lds[];
 
   // Workgroup -> tile: consecutive ids go to different XCDs (round robin over 8, one L2 each);
@@ -77,180 +152,286 @@ __global__ __launch_bounds__(kThreads) void gemm_mx_kernel(Operand A, Operand B,
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wm = wave >> 2, wn = wave & 3, l16 = lane & 15, kb = lane >> 4;
-  const int arow = wm * 128 + l16, brow = wn * 64 + l16;
+  const int wm = wave >> 1, wn = wave & 1, l16 = lane & 15, kb = lane >> 4;
+  const int arow = wm * 128 + l16, brow = wn * 128 + l16;
   const int64_t code_ld = K / 2, scale_ld = K / 32;
 
-  // Direct-load sources.  Codes: an instruction fills 16 tile rows (lane -> row lane / 4, 16-byte
-  // piece lane % 4); every wavefront loads 32 rows of A and 32 rows of B.  Scales: an instruction
-  // fills 64 tile rows x 4 bytes; wavefronts 0-3 take A, 4-7 take B.  Rows past the end of an
-  // operand are clamped; they only feed outputs that are never stored.
-  const uint8_t* ga[2];
-  const uint8_t* gb[2];
+  // Direct-load sources = wave-uniform 64-bit base + per-lane 32-bit offset.  Codes: an instruction fills 16 tile
+  // rows (lane -> row lane / 4, 16-byte piece lane % 4), so one per-lane offset serves every instruction and both
+  // operands (a 16-row block is at most 16 * K / 2 bytes: K < 2^24, checked on the host); every wavefront loads 64
+  // rows of A and of B.  A 16-row block past the end of an operand is replaced by the operand's last block (rows
+  // come in multiples of 32, so a block is in or out as a whole); it only feeds outputs that are never stored.
+  // Scales: an instruction fills 64 tile rows x 4 bytes, rows clamped per lane; every wavefront loads its 64 rows.
+  const uint32_t off_codes = static_cast<uint32_t>(lane >> 2) * static_cast<uint32_t>(code_ld) + (lane & 3) * 16;
+  const uint32_t off_sa = static_cast<uint32_t>(min<int64_t>(wave * 64 + lane, A.outer - 1 - m0)) * static_cast<uint32_t>(scale_ld);
+  const uint32_t off_sb = static_cast<uint32_t>(min<int64_t>(wave * 64 + lane, B.outer - 1 - n0)) * static_cast<uint32_t>(scale_ld);
+  const uint8_t* tile_sa = A.scales + m0 * scale_ld;
+  const uint8_t* tile_sb = B.scales + n0 * scale_ld;
+  const uint8_t* blk_a[4];
+  const uint8_t* blk_b[4];
 #pragma unroll
-  for (int q = 0; q < 2; ++q) {
-    const int r = (wave * 2 + q) * 16 + (lane >> 2);
-    ga[q] = A.codes + min<int64_t>(m0 + r, A.outer - 1) * code_ld + (lane & 3) * 16;
-    gb[q] = B.codes + min<int64_t>(n0 + r, B.outer - 1) * code_ld + (lane & 3) * 16;
+  for (int q = 0; q < 4; ++q) {
+    const int64_t r = (wave * 4 + q) * 16;
+    blk_a[q] = A.codes + (m0 + min<int64_t>(r, A.outer - 16 - m0)) * code_ld;
+    blk_b[q] = B.codes + (n0 + min<int64_t>(r, B.outer - 16 - n0)) * code_ld;
   }
-  const int srow = (wave & 3) * 64 + lane;
-  const uint8_t* gs = wave < 4 ? A.scales + min<int64_t>(m0 + srow, A.outer - 1) * scale_ld
-                               : B.scales + min<int64_t>(n0 + srow, B.outer - 1) * scale_ld;
-  const int s_off = 2 * kCodeBytes + (wave < 4 ? 0 : kScaleBytes) + (wave & 3) * 256;
-
-  const uint32_t lds_base = static_cast<uint32_t>(reinterpret_cast<uintptr_t>((lds_ptr)lds));
-  auto issue = [&](int kt, int stage) {
-    const uint32_t base = __builtin_amdgcn_readfirstlane(lds_base + stage * kStageBytes);
-#pragma unroll
-    for (int q = 0; q < 2; ++q) {
-      load16_to_lds(ga[q] + static_cast<int64_t>(kt) * kCodeRowBytes, base + (wave * 2 + q) * 1024);
-      load16_to_lds(gb[q] + static_cast<int64_t>(kt) * kCodeRowBytes, base + kCodeBytes + (wave * 2 + q) * 1024);
-    }
-    load4_to_lds(gs + static_cast<int64_t>(kt) * 4, base + s_off);
+  const uint32_t lds0 = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(lds));
+  // load number q (0..9) of K step kt into step slot `slot` (0..3): 0..3 A codes, 4..7 B codes, 8 A scales, 9 B scales
+  auto issue_one = [&](int q, int kt, int slot) {
+    const uint32_t base = lds0 + slot * kStepBytes;
+    if (q < 4)
+      load16_to_lds(off_codes, blk_a[q & 3] + static_cast<int64_t>(kt) * kCodeRowBytes, base + (wave * 4 + q) * 1024);
+    else if (q < 8)
+      load16_to_lds(off_codes, blk_b[q & 3] + static_cast<int64_t>(kt) * kCodeRowBytes, base + kCodeBytes + (wave * 4 + (q & 3)) * 1024);
+    else if (q == 8)
+      load4_to_lds(off_sa, tile_sa + static_cast<int64_t>(kt) * 4, base + 2 * kCodeBytes + wave * 256);
+    else
+      load4_to_lds(off_sb, tile_sb + static_cast<int64_t>(kt) * 4, base + 2 * kCodeBytes + kScaleBytes + wave * 256);
   };
+  // fragment addresses in step slot 0
+  const uint32_t a_codes = lds0 + arow * kCodeRowBytes + kb * 16, b_codes = lds0 + kCodeBytes + brow * kCodeRowBytes + kb * 16;
+  const uint32_t a_scales = lds0 + 2 * kCodeBytes + arow * 4, b_scales = lds0 + 2 * kCodeBytes + kScaleBytes + brow * 4;
+  const int sel01 = kb | ((4 + kb) << 8);
 
-  float4v acc[8][4];
+  float4v acc[8][8];
 #pragma unroll
   for (int i = 0; i < 8; ++i)
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
+    for (int j = 0; j < 8; ++j)
 #pragma unroll
       for (int r = 0; r < 4; ++r) acc[i][j][r] = 0.0f;
 
-  // Fragment groups: a stage is two groups of (4 A fragments x 4 B fragments) = 16 MFMAs; the
-  // fragments of the next group are requested from LDS before the MFMAs of the current one start.
-  struct AFr {
-    int8v f[4];
-    int s[4];
-  };
-  struct BFr {
-    int8v f[4];
-    int s[4];
-  };
-  auto load_a = [&](AFr& a, const char* cur, int h) {
-    const uint8_t* sc = reinterpret_cast<const uint8_t*>(cur + 2 * kCodeBytes);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      a.f[i] = load_frag(cur, arow + (h * 4 + i) * 16, kb);
-      a.s[i] = sc[(arow + (h * 4 + i) * 16) * 4 + kb];
-    }
-  };
-  auto load_b = [&](BFr& b, const char* cur) {
-    const uint8_t* sc = reinterpret_cast<const uint8_t*>(cur + 2 * kCodeBytes + kScaleBytes);
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      b.f[j] = load_frag(cur + kCodeBytes, brow + j * 16, kb);
-      b.s[j] = sc[(brow + j * 16) * 4 + kb];
-    }
-  };
-  // The instruction's first operand supplies the rows of its result: passing B first leaves a lane
-  // with 4 consecutive n of one m, which makes the output stores 64/128-bit.
-  auto mma = [&](const AFr& a, const BFr& b, int h) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-      for (int j = 0; j < 4; ++j)
-        acc[h * 4 + i][j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(b.f[j], a.f[i], acc[h * 4 + i][j], 4, 4, 0,
-                                                                             b.s[j], 0, a.s[i]);
-  };
-
-  // Two K steps per barrier: LDS holds two buffers of two stages each (4 x 34 KiB); the loads of
-  // the next pair of steps are in flight while this pair is multiplied.
   const int KT = static_cast<int>(K / TK);
-  issue(0, 0);
-  if (KT > 1) issue(1, 1);
-  __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): the direct loads have landed in LDS
-  __syncthreads();
+  // K steps 0..3 into step slots 0..3.  Steps past the end are clamped to the last one: they land in slots nobody
+  // multiplies any more, and no branch is needed.
+  static_for<0, 40>([&](auto ic) {
+    constexpr int n = decltype(ic)::value;
+    issue_one(n % 10, min(n / 10, KT - 1), n / 10);
+  });
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  Frags f0, f1;
+  RawScales raw;
+  static_for<0, kFragReads>([&](auto q) { read_frag<decltype(q)::value>(f0, raw, a_codes, b_codes, a_scales, b_scales); });
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+  pack_scales(f0, raw, sel01);
 
-  int kt = 0;
-  for (; kt + 1 < KT; kt += 2) {
-    const int buf = (kt >> 1) & 1;
-    if (kt + 2 < KT) issue(kt + 2, (buf ^ 1) * 2);
-    if (kt + 3 < KT) issue(kt + 3, (buf ^ 1) * 2 + 1);
-    const char* s0 = lds + (buf * 2) * kStageBytes;
-    const char* s1 = s0 + kStageBytes;
-    AFr a0, a1;
-    BFr b0, b1;
-    load_b(b0, s0);
-    load_a(a0, s0, 0);
-    __builtin_amdgcn_sched_barrier(0);
-    load_a(a1, s0, 1);
-    __builtin_amdgcn_sched_barrier(0);
-    mma(a0, b0, 0);
-    __builtin_amdgcn_sched_barrier(0);
-    load_b(b1, s1);
-    load_a(a0, s1, 0);
-    __builtin_amdgcn_sched_barrier(0);
-    mma(a1, b0, 1);
-    __builtin_amdgcn_sched_barrier(0);
-    load_a(a1, s1, 1);
-    __builtin_amdgcn_sched_barrier(0);
-    mma(a0, b1, 0);
-    __builtin_amdgcn_sched_barrier(0);
-    mma(a1, b1, 1);
-    __builtin_amdgcn_s_waitcnt(0x0f70);
-    __syncthreads();
+  for (int kt = 0; kt < KT; kt += 2) {
+    const uint32_t cur = ((kt >> 1) & 1) * (2 * kStepBytes), nxt = cur ^ (2 * kStepBytes);
+    const uint32_t second = cur + kStepBytes;
+    static_for<0, 64>([&](auto ic) {
+      constexpr int n = decltype(ic)::value;
+      mfma<(n & 3), ((n >> 3) & 3)>(acc[n >> 3][n & 7], f0.b[n & 7], f0.a[n >> 3], f0.pb[(n & 7) >> 2], f0.pa[n >> 5]);
+      if constexpr ((n & 1) == 1 && (n >> 1) < kFragReads)
+        read_frag<(n >> 1)>(f1, raw, a_codes + second, b_codes + second, a_scales + second, b_scales + second);
+    });
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    pack_scales(f1, raw, sel01);
+    if (kt + 1 < KT) {   // an odd number of K steps leaves the last buffer's second step empty
+      const int slot = ((kt >> 1) & 1) * 2;
+      const int kt4 = min(kt + 4, KT - 1), kt5 = min(kt + 5, KT - 1);
+      static_for<0, 64>([&](auto ic) {
+        constexpr int n = decltype(ic)::value;
+        mfma<(n & 3), ((n >> 3) & 3)>(acc[n >> 3][n & 7], f1.b[n & 7], f1.a[n >> 3], f1.pb[(n & 7) >> 2], f1.pa[n >> 5]);
+        if constexpr ((n & 1) == 0 && (n >> 1) < kFragReads)
+          read_frag<(n >> 1)>(f0, raw, a_codes + nxt, b_codes + nxt, a_scales + nxt, b_scales + nxt);
+        if constexpr ((n & 1) == 1 && n < 40)
+          issue_one((n >> 1) % 10, (n >> 1) < 10 ? kt4 : kt5, slot + ((n >> 1) < 10 ? 0 : 1));
+      });
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+      pack_scales(f0, raw, sel01);
+    }
   }
-  if (kt < KT) {   // odd number of K steps: the last one sits alone in its buffer's first stage
-    const char* s0 = lds + (((kt >> 1) & 1) * 2) * kStageBytes;
-    AFr a0, a1;
-    BFr b0;
-    load_b(b0, s0);
-    load_a(a0, s0, 0);
-    load_a(a1, s0, 1);
-    mma(a0, b0, 0);
-    mma(a1, b0, 1);
-  }
+  // The trailing global->LDS loads must have landed before the wavefront ends; the MFMA results must have left
+  // the pipe before ordinary instructions read the accumulators (the compiler cannot see into the assembly
+  // statements to insert these wait states itself).
+  asm volatile("s_waitcnt vmcnt(0)\n\ts_nop 15\n\ts_nop 15" ::: "memory");
 
-  const float out_scale = A.ts[0] * B.ts[0];   // both are 1 for MXFP4 (no tensor-level scale)
+  const float out_scale = A.ts[0] * B.ts[0];    // both are 1 for MXFP4 (no tensor-level scale)
   const int Mt = static_cast<int>(A.outer - m0 < TM ? A.outer - m0 : TM);
   const int Nt = static_cast<int>(B.outer - n0 < TN ? B.outer - n0 : TN);
+  store_wave_block<kBf16Out>(acc, out_scale, Dv, ldd, accumulate, m0 + wm * 128, n0 + wn * 128, Mt - wm * 128, Nt - wn * 128,
+                             lane);
+}
+
+// ---------------------------------------------------------------- K a multiple of 512
+// The kernel above asks the memory system for many small pieces: per K step a 64-byte piece of every code row
+// and a 4-byte piece of every scale row, each its own cache-line request (measured: about one request per
+// clock and CU, which is what bounds it).  When K is a multiple of 512 the same loop runs on fuller lines:
+//   codes   a stage is two K steps = 128 bytes of each row, 8 rows per load instruction, stored with the XOR
+//           swizzle chunk c of row r -> position c ^ ((r >> 1) & 7) so that fragment reads stay conflict-free;
+//           the two steps of an iteration are the two 64-byte halves of a stage
+//   scales  16 bytes of each scale row = four K steps = two iterations per load instruction, in a ring of
+//           two 8 KiB slots; a lane reads its row's dword of the step and gathers bytes as before
+// a third of the line requests for the same bytes.  The pipeline is the one described at the top.
+constexpr int kWideRowBytes = 128;
+constexpr int kWideOperandBytes = TM * kWideRowBytes;       // 32 KiB
+constexpr int kWideStageBytes = 2 * kWideOperandBytes;      // 64 KiB
+constexpr int kWideScaleOperandBytes = TM * 16;             // 4 KiB: 256 rows x 4 steps x 4 blocks
+constexpr int kWideScaleSlotBytes = 2 * kWideScaleOperandBytes;
+constexpr int kWideLdsBytes = 2 * kWideStageBytes + 2 * kWideScaleSlotBytes;   // 144 KiB
+
+__device__ __forceinline__ int swz128(int row, int chunk) { return row * kWideRowBytes + ((chunk ^ ((row >> 1) & 7)) << 4); }
+
+// two dwords, kOff0 and kOff1 times 256 bytes past addr
+template <int kOff0, int kOff1>
+__device__ __forceinline__ void lds_read_2x4_st64(int2v& dst, uint32_t addr) {
+  asm volatile("ds_read2st64_b32 %0, %1 offset0:%2 offset1:%3" : "=&v"(dst) : "v"(addr), "n"(kOff0), "n"(kOff1));
+}
+
+// Read number q of the 24 of a fragment set: 0..7 A codes, 8..15 B codes (16-row blocks are 2 KiB apart), 16..19 A
+// scales, 20..23 B scales (16-row blocks are 256 bytes apart).
+template <int q>
+__device__ __forceinline__ void read_frag_wide(Frags& f, RawScales& r, uint32_t a_codes, uint32_t b_codes, uint32_t a_scales,
+                                               uint32_t b_scales) {
+  if constexpr (q < 8) lds_read16<q * 16 * kWideRowBytes>(f.a[q], a_codes);
+  else if constexpr (q < 16) lds_read16<(q - 8) * 16 * kWideRowBytes>(f.b[q - 8], b_codes);
+  else if constexpr (q < 20) lds_read_2x4_st64<(q - 16) * 2, (q - 16) * 2 + 1>(r.a[q - 16], a_scales);
+  else lds_read_2x4_st64<(q - 20) * 2, (q - 20) * 2 + 1>(r.b[q - 20], b_scales);
+}
+
+template <bool kBf16Out>
+__global__ __launch_bounds__(kThreads) void gemm_mx_kernel_k512(Operand A, Operand B, int64_t K, void* __restrict__ Dv,
+                                                                int64_t ldd, bool accumulate, int tiles_m, int tiles_n) {
+  extern __shared__ __attribute__((aligned(16))) char lds[];
+
+  const int num_tiles = tiles_m * tiles_n;
+  int pid = blockIdx.x;
+  if ((num_tiles & 7) == 0) pid = (pid & 7) * (num_tiles >> 3) + (pid >> 3);
+  constexpr int kBand = 8;
+  const int band = pid / (kBand * tiles_n);
+  const int band_rows = min(kBand, tiles_m - band * kBand);
+  const int in_band = pid - band * kBand * tiles_n;
+  const int tm = band * kBand + in_band % band_rows, tn = in_band / band_rows;
+  const int64_t m0 = static_cast<int64_t>(tm) * TM, n0 = static_cast<int64_t>(tn) * TN;
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave >> 1, wn = wave & 1, l16 = lane & 15, kb = lane >> 4;
+  const int arow = wm * 128 + l16, brow = wn * 128 + l16;
+  const int64_t code_ld = K / 2, scale_ld = K / 32;
+
+  // Code loads: instruction q (0..7) of wavefront w fills tile rows w * 64 + 8 q .. + 7 (lane -> row lane / 8,
+  // position lane % 8, i.e. chunk (lane % 8) ^ ((row >> 1) & 7); 8 q leaves that term alone for even q and flips
+  // its bit 2 for odd q).  Wave-uniform 64-bit base per 8-row block + one per-lane 32-bit offset for even and one
+  // for odd q (K < 2^24, checked on the host).  A block past the end of an operand is replaced by the operand's
+  // last block (rows come in multiples of 32); it only feeds outputs that are never stored.
+  const int r0 = wave * 64 + (lane >> 3);
+  const uint32_t c0 = static_cast<uint32_t>((lane & 7) ^ ((r0 >> 1) & 7)) * 16u;
+  const uint32_t off_even = static_cast<uint32_t>(lane >> 3) * static_cast<uint32_t>(code_ld) + c0;
+  const uint32_t off_odd = static_cast<uint32_t>(lane >> 3) * static_cast<uint32_t>(code_ld) + (c0 ^ 64u);
+  const uint8_t* blk_a[8];
+  const uint8_t* blk_b[8];
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    const int m = wm * 128 + i * 16 + l16;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int n = wn * 64 + j * 16 + kb * 4;
-      if (m < Mt && n < Nt) {  // N is a multiple of 32, so the 4 columns are in or out together
-        float4v v = acc[i][j] * out_scale;
-        if (kBf16Out) {
-          uint16_t* d = static_cast<uint16_t*>(Dv) + (m0 + m) * ldd + n0 + n;
-          uint2 o;
-          o.x = f32_to_bf16(v[0]) | (f32_to_bf16(v[1]) << 16);
-          o.y = f32_to_bf16(v[2]) | (f32_to_bf16(v[3]) << 16);
-          *reinterpret_cast<uint2*>(d) = o;
-        } else {
-          float* d = static_cast<float*>(Dv) + (m0 + m) * ldd + n0 + n;
-          if (accumulate) v += *reinterpret_cast<const float4v*>(d);
-          *reinterpret_cast<float4v*>(d) = v;
-        }
-      }
-    }
+  for (int q = 0; q < 8; ++q) {
+    const int64_t r = wave * 64 + q * 8;
+    blk_a[q] = A.codes + (m0 + min<int64_t>(r, A.outer - 8 - m0)) * code_ld;
+    blk_b[q] = B.codes + (n0 + min<int64_t>(r, B.outer - 8 - n0)) * code_ld;
   }
+  // Scale loads: one instruction = 64 tile rows x 16 bytes (four K steps), rows clamped per lane.
+  const uint32_t off_sa = static_cast<uint32_t>(min<int64_t>(wave * 64 + lane, A.outer - 1 - m0)) * static_cast<uint32_t>(scale_ld);
+  const uint32_t off_sb = static_cast<uint32_t>(min<int64_t>(wave * 64 + lane, B.outer - 1 - n0)) * static_cast<uint32_t>(scale_ld);
+  const uint8_t* tile_sa = A.scales + m0 * scale_ld;
+  const uint8_t* tile_sb = B.scales + n0 * scale_ld;
+  const uint32_t lds0 = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(lds));
+  const uint32_t scales0 = lds0 + 2 * kWideStageBytes;
+  // load number q (0..15) of stage `st` (K steps 2 st, 2 st + 1) into stage buffer `buf`: 0..7 A, 8..15 B
+  auto issue_codes = [&](int q, int st, int buf) {
+    const uint32_t dst = lds0 + buf * kWideStageBytes + (q < 8 ? 0 : kWideOperandBytes) + wave * 8192 + (q & 7) * 1024;
+    load16_to_lds((q & 1) ? off_odd : off_even, (q < 8 ? blk_a[q & 7] : blk_b[q & 7]) + static_cast<int64_t>(st) * kWideRowBytes, dst);
+  };
+  // the two loads of scale chunk `ch` (K steps 4 ch .. 4 ch + 3) into ring slot `slot`
+  auto issue_scales = [&](int ch, int slot) {
+    const uint32_t dst = scales0 + slot * kWideScaleSlotBytes + wave * 1024;
+    load16_to_lds(off_sa, tile_sa + static_cast<int64_t>(ch) * 16, dst);
+    load16_to_lds(off_sb, tile_sb + static_cast<int64_t>(ch) * 16, dst + kWideScaleOperandBytes);
+  };
+  // fragment addresses in stage buffer 0 / scale slot 0, step 0
+  const uint32_t a_lo = lds0 + swz128(arow, kb), a_hi = lds0 + swz128(arow, 4 + kb);
+  const uint32_t b_lo = lds0 + kWideOperandBytes + swz128(brow, kb), b_hi = lds0 + kWideOperandBytes + swz128(brow, 4 + kb);
+  const uint32_t a_scales = scales0 + arow * 16, b_scales = scales0 + kWideScaleOperandBytes + brow * 16;
+  const int sel01 = kb | ((4 + kb) << 8);
+
+  float4v acc[8][8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) acc[i][j][r] = 0.0f;
+
+  const int stages = static_cast<int>(K / 256), chunks = static_cast<int>(K / 512);   // stages = 2 chunks >= 2
+  static_for<0, 16>([&](auto q) { issue_codes(decltype(q)::value, 0, 0); });
+  static_for<0, 16>([&](auto q) { issue_codes(decltype(q)::value, 1, 1); });
+  issue_scales(0, 0);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  Frags f0, f1;
+  RawScales raw;
+  static_for<0, kFragReads>([&](auto q) { read_frag_wide<decltype(q)::value>(f0, raw, a_lo, b_lo, a_scales, b_scales); });
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+  pack_scales(f0, raw, sel01);
+
+  for (int st = 0; st < stages; ++st) {
+    const uint32_t cur = (st & 1) * kWideStageBytes, nxt = cur ^ kWideStageBytes;
+    // scale addresses: this stage's second step; the next stage's first step (ring slot of its chunk)
+    const uint32_t sc1 = ((st >> 1) & 1) * kWideScaleSlotBytes + (st & 1) * 8 + 4;
+    const uint32_t sc2 = (((st + 1) >> 1) & 1) * kWideScaleSlotBytes + ((st + 1) & 1) * 8;
+    const int st2 = min(st + 2, stages - 1);   // past the end: the last stage again, into a buffer nobody reads any more
+    static_for<0, 64>([&](auto ic) {
+      constexpr int n = decltype(ic)::value;
+      mfma<(n & 3), ((n >> 3) & 3)>(acc[n >> 3][n & 7], f0.b[n & 7], f0.a[n >> 3], f0.pb[(n & 7) >> 2], f0.pa[n >> 5]);
+      if constexpr ((n & 1) == 1 && (n >> 1) < kFragReads)
+        read_frag_wide<(n >> 1)>(f1, raw, a_hi + cur, b_hi + cur, a_scales + sc1, b_scales + sc1);
+    });
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    pack_scales(f1, raw, sel01);
+    static_for<0, 64>([&](auto ic) {
+      constexpr int n = decltype(ic)::value;
+      mfma<(n & 3), ((n >> 3) & 3)>(acc[n >> 3][n & 7], f1.b[n & 7], f1.a[n >> 3], f1.pb[(n & 7) >> 2], f1.pa[n >> 5]);
+      if constexpr ((n & 1) == 0 && (n >> 1) < kFragReads)
+        read_frag_wide<(n >> 1)>(f0, raw, a_lo + nxt, b_lo + nxt, a_scales + sc2, b_scales + sc2);
+      if constexpr ((n & 3) == 3) issue_codes(n >> 2, st2, st & 1);
+    });
+    // even stages also fetch the scales of the chunk after the next stage's, into the slot its predecessor left
+    // at this stage's barrier
+    if ((st & 1) == 0) issue_scales(min((st >> 1) + 1, chunks - 1), ((st >> 1) + 1) & 1);
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    pack_scales(f0, raw, sel01);
+  }
+  asm volatile("s_waitcnt vmcnt(0)\n\ts_nop 15\n\ts_nop 15" ::: "memory");
+
+  const float out_scale = A.ts[0] * B.ts[0];    // both are 1 for MXFP4 (no tensor-level scale)
+  const int Mt = static_cast<int>(A.outer - m0 < TM ? A.outer - m0 : TM);
+  const int Nt = static_cast<int>(B.outer - n0 < TN ? B.outer - n0 : TN);
+  store_wave_block<kBf16Out>(acc, out_scale, Dv, ldd, accumulate, m0 + wm * 128, n0 + wn * 128, Mt - wm * 128, Nt - wn * 128,
+                             lane);
 }
 
 }  // namespace
 
+template <class Kernel>
+static hipError_t launch_mx(Kernel kernel, int lds_bytes, const GemmArgs& g, dim3 grid, int tiles_m, int tiles_n, hipStream_t s) {
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(kernel, grid, dim3(kThreads), lds_bytes, s, g.a, g.b, g.K, g.d, g.ldd, g.accumulate, tiles_m, tiles_n);
+  return hipGetLastError();
+}
+
 hipError_t launch_gemm_mx(const GemmArgs& g, hipStream_t s) {
+  if (g.K >= (int64_t{1} << 24)) return hipErrorInvalidValue;   // the kernels' 32-bit byte offsets inside a block of rows
   const int tiles_m = static_cast<int>((g.a.outer + TM - 1) / TM), tiles_n = static_cast<int>((g.b.outer + TN - 1) / TN);
   const dim3 grid(static_cast<unsigned>(tiles_m) * static_cast<unsigned>(tiles_n));
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mx_kernel<true>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, 4 * kStageBytes);
-    if (e == hipSuccess)
-      e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mx_kernel<false>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, 4 * kStageBytes);
-    if (e != hipSuccess) return e;
-    attr_set = true;
+  // 16-byte pieces of scale rows need K / 32 to be a multiple of 16 and the scale arrays 16-byte aligned
+  const bool wide = g.K % 512 == 0 && reinterpret_cast<uintptr_t>(g.a.scales) % 16 == 0 && reinterpret_cast<uintptr_t>(g.b.scales) % 16 == 0;
+  if (wide) {
+    if (g.out_bf16) return launch_mx(gemm_mx_kernel_k512<true>, kWideLdsBytes, g, grid, tiles_m, tiles_n, s);
+    return launch_mx(gemm_mx_kernel_k512<false>, kWideLdsBytes, g, grid, tiles_m, tiles_n, s);
   }
-  if (g.out_bf16)
-    hipLaunchKernelGGL(gemm_mx_kernel<true>, grid, dim3(kThreads), 4 * kStageBytes, s, g.a, g.b, g.K, g.d, g.ldd,
-                       g.accumulate, tiles_m, tiles_n);
-  else
-    hipLaunchKernelGGL(gemm_mx_kernel<false>, grid, dim3(kThreads), 4 * kStageBytes, s, g.a, g.b, g.K, g.d, g.ldd,
-                       g.accumulate, tiles_m, tiles_n);
-  return hipGetLastError();
+  if (g.out_bf16) return launch_mx(gemm_mx_kernel_any_k<true>, kLdsBytes, g, grid, tiles_m, tiles_n, s);
+  return launch_mx(gemm_mx_kernel_any_k<false>, kLdsBytes, g, grid, tiles_m, tiles_n, s);
 }
 
 }  // namespace nvfp4

@@ -80,7 +80,10 @@ def rel_fro(got, ref):
     return float(np.linalg.norm(got.astype(np.float64) - ref) / np.linalg.norm(ref))
 
 
-@pytest.mark.parametrize("mnk", [(256, 256, 128), (288, 160, 384), (512, 768, 1024), (32, 32, 128)])
+# K a multiple of 512 takes the kernel with full-line loads (two K steps per stage, scales four steps at a time),
+# any other multiple of 128 the general one (with an odd number of K steps for 384 and 640)
+@pytest.mark.parametrize("mnk", [(256, 256, 128), (288, 160, 384), (512, 768, 1024), (32, 32, 128), (288, 160, 512),
+                                 (544, 96, 1536), (32, 32, 2048), (160, 288, 640)])
 def test_mx_gemm_all_ops(mnk):
     M, N, K = mnk
     ab = synth.normal_with_outliers(M, K, 1.0, 910, frac=0.01)
