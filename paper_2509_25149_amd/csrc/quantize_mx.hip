@@ -102,7 +102,7 @@ __global__ __launch_bounds__(kThreads) void quantize_mx_kernel(const uint16_t* _
   }
 
   if (kRow) {
-#pragma unroll 4
+#pragma unroll   // fully: a partly unrolled loop indexes raw[] at run time, which puts the whole patch in scratch memory
     for (int r = 0; r < 32; ++r) {
       float v[8];
 #pragma unroll
@@ -123,9 +123,17 @@ __global__ __launch_bounds__(kThreads) void quantize_mx_kernel(const uint16_t* _
         *reinterpret_cast<uint32_t*>(row_codes + (row0 + r) * (cols / 2) + col0 / 2) = codes;
         if ((lane & 3) == 0) st_row_scales[(wave * kRowsPerWave + r) * 16 + (lane >> 2)] = static_cast<uint8_t>(sc);
       }
+      // keep the scheduler from interleaving all 32 rows' temporaries on top of the 128 registers of the patch
+      if ((r & 3) == 3) __builtin_amdgcn_sched_barrier(0);
     }
   }
 
+  if (kRow && kCol) {
+    // Opaque to the optimiser (no instruction emitted): otherwise it recognises the row pass's unpacked values
+    // in the column pass and keeps all 256 of them alive on top of the 128 registers of the patch.
+#pragma unroll
+    for (int r = 0; r < 32; ++r) asm volatile("" : "+v"(raw[r].x), "+v"(raw[r].y), "+v"(raw[r].z), "+v"(raw[r].w));
+  }
   if (kCol) {
 #pragma unroll
     for (int c = 0; c < 8; ++c) {
@@ -150,6 +158,7 @@ __global__ __launch_bounds__(kThreads) void quantize_mx_kernel(const uint16_t* _
       }
       *reinterpret_cast<uint4*>(st_col_codes + ((c * 4 + wave) * kSlot + lane) * 16) = make_uint4(out[0], out[1], out[2], out[3]);
       st_col_scales[(c * 4 + wave) * 64 + lane] = static_cast<uint8_t>(sc);
+      __builtin_amdgcn_sched_barrier(0);
     }
   }
   __syncthreads();
