@@ -11,8 +11,8 @@
 //           v_mfma_f32_32x32x16_f16 on the same operand values).
 // Why: decoding inside the GEMM loop costs about one VALU instruction per
 // element, and VALU instructions co-issued with MFMAs take matrix-pipe time
-// (measured: the fused kernel runs at 0.95-1.0 PFLOP/s, this pair at about
-// 1.25 PFLOP/s in the GEMM proper, the decode pass adding 5-8 % of its time).
+// (measured: the fused kernel runs at 1.0-1.07 PFLOP/s, this pair at about
+// 1.39 PFLOP/s in the GEMM proper, the decode pass adding 5-8 % of its time).
 // The results are identical to the fused kernel's up to FP32 summation order.
 #include <type_traits>
 

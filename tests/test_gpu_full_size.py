@@ -165,6 +165,24 @@ def test_other_rotation_sizes_at_full_size(name, d, rounding):
     assert_copy(q.col_codes, q.col_scales, q.col_ts, col, f"{name} d={d} col copy")
 
 
+def test_contraction_too_long_for_the_two_pass_kernel():
+    """K = 2^21: the FP16 GEMM kernel's 32-bit byte offsets inside a block of rows stop there, so the call must take
+    the fused route even when a workspace is lent; results as usual."""
+    M, N, K = 32, 48, 1 << 21
+    ab = synth.normal_with_outliers(M, K, 1.0, 901, frac=0.001)
+    bb = synth.normal(N, K, 0.02, 902)
+    qa = nv.nvfp4_quantize(to_dev(ab), nv.LAYOUT_ROW)
+    qb = nv.nvfp4_quantize(to_dev(bb), nv.LAYOUT_ROW)
+    ra, rb = oracle.quantize(ab, oracle.ROW), oracle.quantize(bb, oracle.ROW)
+    assert_copy(qa.row_codes, qa.row_scales, qa.row_ts, ra, "A")
+    want = oracle.gemm_f64(ra, rb)
+    for ws in (None, ws_for(M, N, K)):
+        got = nv.nvfp4_gemm(qa, qb, nv.OP_DGRAD, nv.OUT_F32, workspace=ws)
+        torch.cuda.synchronize()
+        err = np.linalg.norm(got.cpu().numpy().astype(np.float64) - want) / np.linalg.norm(want)
+        assert err <= GEMM_TOL, err
+
+
 def test_indexing_beyond_2_31_elements():
     """A tensor of 2^31 + 2^27 elements (4.5 GB of bf16): the small tensor it is tiled from fixes the expected
     bytes, since tiling by whole 16-row groups changes neither the amax nor any block (RNE)."""
