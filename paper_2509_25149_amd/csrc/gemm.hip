@@ -155,13 +155,13 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_kernel(Operand A, Operand B
 
 // ---------------------------------------------------------------- large-tile kernel
 // 256 x 256 outputs per workgroup, K step 64, 512 threads = 8 wavefronts in a
-// 2 (m) x 4 (n) grid, each owning 128 x 64 outputs as 4 x 2 MFMA 32x32 blocks
+// 2 (m) x 4 (n) grid, each owning 128 x 64 outputs as 8 x 4 MFMA 16x16 blocks
 // (128 accumulator registers per lane).  The decoded FP16 tiles are
 // double-buffered in LDS (2 x 64 KiB), one barrier per K step.
 //
 // The two halves of the workgroup run the step's two phases in opposite
 // order ("ping-pong"): wavefronts 0-3 (one per SIMD) issue their global loads,
-// run the step's 32 MFMAs and then decode the NEXT A tile into the other LDS
+// run the step's 64 MFMAs and then decode the NEXT A tile into the other LDS
 // buffer; wavefronts 4-7 first decode the next B tile, then issue their loads
 // for the step after and run their MFMAs.  On every SIMD one wavefront is
 // therefore in its VALU/LDS-write phase while the other keeps the matrix pipe
