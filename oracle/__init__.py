@@ -72,7 +72,7 @@ def lib() -> ctypes.CDLL:
         L.orc_num_threads.restype = ctypes.c_int
         L.orc_quantize.restype = ctypes.c_int
         L.orc_quantize.argtypes = [vp, i64, i64, i64, ctypes.c_int, ctypes.c_int, ctypes.c_int,
-                                   ctypes.c_int, u64, u64, vp, vp, vp]
+                                   ctypes.c_int, u64, u64, vp, vp, vp, vp]
         L.orc_dequantize.restype = ctypes.c_int
         L.orc_dequantize.argtypes = [vp, vp, f32, i64, i64, ctypes.c_int, u64, vp]
         gemm_head = [vp, vp, f32, vp, vp, f32]
@@ -207,16 +207,18 @@ class QCopy:
 
 
 def quantize(x_bf16_bits: np.ndarray, copy: int, block_dim: int = BLOCK_1x16, rounding: int = RNE,
-             use_rht: bool = False, rht_seed: int = 0, sr_seed: int = 0, rht_dim: int = 16) -> QCopy:
-    """x_bf16_bits: uint16 [rows, cols] holding bf16 bit patterns; rht_dim is the rotation size if use_rht."""
+             use_rht: bool = False, rht_seed: int = 0, sr_seed: int = 0, rht_dim: int = 16, amax=None) -> QCopy:
+    """x_bf16_bits: uint16 [rows, cols] holding bf16 bit patterns; rht_dim is the rotation size if use_rht;
+    amax: None, or the amax to use for the tensor-level scale instead of the tensor's own."""
     x = np.ascontiguousarray(x_bf16_bits, dtype=np.uint16)
     rows, cols = x.shape
     outer, inner = (cols, rows) if copy == COL else (rows, cols)
     codes = np.zeros((outer, inner // 2), dtype=np.uint8)
     scales = np.zeros((outer, inner // 16), dtype=np.uint8)
     ts = np.zeros(2, dtype=np.float32)
+    given = None if amax is None else np.array([amax], dtype=np.float32)
     rc = lib().orc_quantize(_p(x), rows, cols, cols, copy, block_dim, rounding, rht_dim if use_rht else 0,
-                            rht_seed, sr_seed, _p(codes), _p(scales), _p(ts))
+                            rht_seed, sr_seed, None if given is None else _p(given), _p(codes), _p(scales), _p(ts))
     if rc != 0:
         raise ValueError(f"orc_quantize rejected its arguments (rc={rc})")
     return QCopy(codes, scales, np.float32(ts[0]), np.float32(ts[1]), outer, inner)

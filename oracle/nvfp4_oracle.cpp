@@ -341,12 +341,14 @@ int      orc_num_threads(void) {
 //   rht_dim    0, or the size d of the rotation: each aligned group of d along
 //              the block direction is rotated before anything else (Wgrad
 //              operands, Sec. 4.2; d = 16 is the paper's choice)
+//   amax_given null, or the amax to use in Eq. 1 instead of this tensor's own
+//              (in the rotated space for a rotated copy)
 // Outputs: codes [outer, inner/2] bytes, scales [outer, inner/16] bytes,
 // tensor_scale[0] = s_dec, tensor_scale[1] = amax (in the rotated space for a
 // rotated copy).  Returns 0, or -1 for bad arguments.
 int orc_quantize(const uint16_t* x, int64_t rows, int64_t cols, int64_t ld,
                  int copy, int block_dim, int rounding, int rht_dim,
-                 uint64_t rht_seed, uint64_t sr_seed,
+                 uint64_t rht_seed, uint64_t sr_seed, const float* amax_given,
                  uint8_t* codes, uint8_t* scales, float* tensor_scale) {
   if (!x || !codes || !scales || !tensor_scale) return -1;
   if (rows < 0 || cols < 0 || ld < cols) return -1;
@@ -374,11 +376,18 @@ int orc_quantize(const uint16_t* x, int64_t rows, int64_t cols, int64_t ld,
       for (int64_t g = 0; g < inner / rht_dim; ++g) rht_forward_d(wo + rht_dim * g, rht_dim, negate);
   }
 
-  // App. B.1, Eq. 1: tensor-level scale from the global amax.
+  // App. B.1, Eq. 1: tensor-level scale from the global amax -- of this tensor, or one the caller supplies
+  // (an amax known beforehand or reduced over the shards of a larger tensor saves the first of the two passes
+  // over memory that App. B.1 counts; nothing else changes, values beyond it saturate as in Eq. 3-4).
   float amax = 0.0f;
-  for (size_t t = 0; t < w.size(); ++t) {
-    const float a = std::fabs(w[t]);
-    if (a > amax) amax = a;
+  if (amax_given) {
+    amax = *amax_given;
+    if (!(amax >= 0.0f)) return -1;
+  } else {
+    for (size_t t = 0; t < w.size(); ++t) {
+      const float a = std::fabs(w[t]);
+      if (a > amax) amax = a;
+    }
   }
   float s_enc, s_dec;
   if (amax == 0.0f) {

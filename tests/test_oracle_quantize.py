@@ -269,3 +269,52 @@ def test_sr_in_the_tensor_path_uses_the_element_draw_for_both_copies():
     c = oracle.quantize(xb, oracle.ROW, sr_seed=1)
     d = oracle.quantize(xb, oracle.ROW, sr_seed=2)
     assert np.array_equal(c.codes, d.codes)
+
+
+# ---------------------------------------------------------------- supplied amax (App. B.1: the first pass is only the amax)
+
+def test_supplied_amax_equal_to_the_tensors_own_changes_nothing():
+    xb = synth.normal_with_outliers(48, 96, 1.0, 71, frac=0.01)
+    for copy in (oracle.ROW, oracle.COL):
+        for rht in (False, True):
+            if rht and copy == oracle.ROW:
+                continue
+            a = oracle.quantize(xb, copy, use_rht=rht, rht_seed=5)
+            b = oracle.quantize(xb, copy, use_rht=rht, rht_seed=5, amax=float(a.amax))
+            assert np.array_equal(a.codes, b.codes) and np.array_equal(a.scales, b.scales)
+            assert a.s_dec == b.s_dec and a.amax == b.amax
+
+
+def test_supplied_amax_sets_the_tensor_scale_of_eq1():
+    xb = bits(np.linspace(-3.0, 3.0, 16 * 32).reshape(16, 32))
+    own = oracle.quantize(xb, oracle.ROW)
+    for factor in (2.0, 16.0, 0.5):
+        q = oracle.quantize(xb, oracle.ROW, amax=float(own.amax) * factor)
+        assert q.amax == np.float32(float(own.amax) * factor)
+        s_enc = np.float32(2688.0) / q.amax                      # Eq. 1: 6 * 448 / amax
+        assert q.s_dec == np.float32(1.0) / s_enc
+        # Eq. 2-3 with that s_enc: every stored block scale is e4m3(amax_b / 6 * s_enc), saturated at 448
+        x = synth.bf16_bits_to_f32(xb)
+        for r in range(16):
+            for b in range(2):
+                amax_b = np.float32(np.abs(x[r, 16 * b:16 * b + 16]).max())
+                want = oracle.e4m3_encode_rne_sat(float(np.float32(amax_b / np.float32(6.0)) * s_enc))
+                assert q.scales[r, b] == want
+
+
+def test_a_larger_amax_loses_resolution_and_a_smaller_one_saturates():
+    xb = synth.normal(64, 64, 1.0, 72)
+    x = synth.bf16_bits_to_f32(xb)
+    own = oracle.quantize(xb, oracle.ROW)
+    err = lambda q: float(np.linalg.norm(oracle.dequantize(q) - x) / np.linalg.norm(x))
+    # 2x or 4x too large only moves the block scales along the E4M3 grid: about the same error
+    assert err(oracle.quantize(xb, oracle.ROW, amax=float(own.amax) * 4)) < 1.3 * err(own)
+    # far too small: the block scales saturate at 448 and the codes at +-6 (Eq. 3-4), so large values are clipped
+    small = oracle.quantize(xb, oracle.ROW, amax=float(own.amax) / 64)
+    assert small.scales.max() == 0x7E                               # 448
+    back = oracle.dequantize(small)
+    cap = np.float32(6.0) * np.float32(448.0) * small.s_dec
+    assert np.abs(back).max() <= cap * (1 + 1e-6) and np.abs(x).max() > cap
+    assert err(small) > 2 * err(own)
+    with pytest.raises(ValueError):
+        oracle.quantize(xb, oracle.ROW, amax=-1.0)
