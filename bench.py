@@ -163,6 +163,33 @@ def rht_size_sweep(torch, nv, x, dy, iters: int = 5):
     return res
 
 
+def known_amax_block(torch, nv, x, w, dy, iters: int = 5):
+    """The three quantize calls when the amax is already known (nvfp4_amax once, then nvfp4_quantize_with_amax):
+    App. B.1's extra pass through device memory is gone.  Outside the timed region of `value`."""
+    RC = nv.LAYOUT_ROW | nv.LAYOUT_COL
+    cases = {"X_8192x5120_rne_rht": (x, nv.BLOCK_1x16, nv.ROUND_RNE, 16),
+             "W_5120x20480_2d": (w, nv.BLOCK_16x16, nv.ROUND_RNE, 0),
+             "dY_8192x20480_sr_rht": (dy, nv.BLOCK_1x16, nv.ROUND_SR, 16)}
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    res = {}
+    for name, (t, bd, rnd, rht) in cases.items():
+        q = nv.alloc_qtensor(t.shape[0], t.shape[1], RC, block_dim=bd)
+        amax = nv.nvfp4_amax(t, rht, 2025)
+        tot = 0.0
+        for it in range(iters + 1):
+            a, b = ev(), ev()
+            a.record()
+            nv.nvfp4_quantize_with_amax(t, amax, RC, bd, rnd, rht, 2025, 77 + it, out=q)
+            b.record()
+            torch.cuda.synchronize()
+            if it:
+                tot += a.elapsed_time(b)
+        ms = tot / iters
+        res[name] = {"ms": ms, "GBps": quant_bytes(t.numel(), 2) / (ms * 1e-3) / 1e9}
+    res["note"] = "not part of `value`: pass 2 alone with a supplied amax; GB/s = bf16 read once + both copies written"
+    return res
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -291,6 +318,7 @@ def main() -> int:
         out["mxfp4_comparison"] = mxfp4_comparison(torch, nv, x, w, dy)
     if not args.no_rht_sweep:
         out["rht_size_sweep"] = rht_size_sweep(torch, nv, x, dy)
+        out["quantize_with_known_amax"] = known_amax_block(torch, nv, x, w, dy)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(torch, nv, x, w)
     print(json.dumps(out))

@@ -139,6 +139,28 @@ int nvfp4_quantize(const void* x, int64_t rows, int64_t cols, int64_t ld, int la
                    nvfp4_stream_t stream);
 
 /*
+ * The two passes of nvfp4_quantize as separate calls.  App. B.1 counts the global amax as an extra pass through
+ * device memory; a caller that knows the amax beforehand (a weight whose amax the optimizer step tracked, an amax
+ * kept from the previous iteration) or has to combine it over the shards of a larger tensor (a max all-reduce
+ * between the two calls) runs only what it needs.  NVFP4 only (MXFP4 has no tensor-level scale).
+ *
+ * nvfp4_amax: pass 1.  amax_out is device memory, float[2]: { max |x|, max |rotated x| } (the second is 0 without
+ * rht_on_col; it is what Eq. 1 uses for a rotated col copy, App. C).  rht_on_col, rht_seed, workspace as in
+ * nvfp4_quantize (same workspace size).
+ *
+ * nvfp4_quantize_with_amax: pass 2.  amax_in is device memory, float[2] laid out as nvfp4_amax writes it, read by the
+ * kernels when they run; values must be >= 0 and finite.  Every other argument as in nvfp4_quantize; no workspace.
+ * With amax_in = this tensor's own amax the result is bit-identical to nvfp4_quantize's.  A larger amax only moves
+ * the block scales along the E4M3 grid; with a smaller one block scales saturate at 448 and codes at +-6
+ * (Eq. 3-4).  tensor_scale[1] reports the amax that was used.
+ */
+int nvfp4_amax(const void* x, int64_t rows, int64_t cols, int64_t ld, int rht_on_col, uint64_t rht_seed,
+               float* amax_out, void* workspace, size_t workspace_bytes, nvfp4_stream_t stream);
+int nvfp4_quantize_with_amax(const void* x, int64_t rows, int64_t cols, int64_t ld, int layout_mask, int block_dim,
+                             int rounding, int rht_on_col, uint64_t rht_seed, uint64_t sr_seed,
+                             const float* amax_in, nvfp4_qtensor* out, nvfp4_stream_t stream);
+
+/*
  * Block-scaled GEMM (Eq. 5): D[m, n] = s_dec^A s_dec^B sum_b sA[m,b] sB[n,b]
  * sum_{k in b} A[m,k] B[n,k], FP32 accumulation.  `op` picks the copies:
  *   FPROP  Y  = X W      A = row copy of X [M,K],   B = col copy of W [K,N] (-> [N,K])

@@ -25,7 +25,8 @@ COPY_ROW, COPY_COL = 0, 1
 
 EXPORTS = ["nvfp4_quantized_sizes", "nvfp4_quantize", "nvfp4_gemm", "nvfp4_gemm_workspace_bytes", "nvfp4_dequantize",
            "nvfp4_rht_sign_mask", "nvfp4_selftest_conversions", "nvfp4_status_string", "nvfp4_version",
-           "nvfp4_linear_workspace_bytes", "nvfp4_linear_forward", "nvfp4_linear_backward"]
+           "nvfp4_linear_workspace_bytes", "nvfp4_linear_forward", "nvfp4_linear_backward",
+           "nvfp4_amax", "nvfp4_quantize_with_amax"]
 
 
 class QTensorStruct(ctypes.Structure):
@@ -56,6 +57,11 @@ def load_library() -> ctypes.CDLL:
         L.nvfp4_quantize.restype = ci
         L.nvfp4_quantize.argtypes = [vp, i64, i64, i64, ci, ci, ci, ci, u64, u64,
                                      ctypes.POINTER(QTensorStruct), vp, ctypes.c_size_t, vp]
+        L.nvfp4_amax.restype = ci
+        L.nvfp4_amax.argtypes = [vp, i64, i64, i64, ci, u64, vp, vp, ctypes.c_size_t, vp]
+        L.nvfp4_quantize_with_amax.restype = ci
+        L.nvfp4_quantize_with_amax.argtypes = [vp, i64, i64, i64, ci, ci, ci, ci, u64, u64, vp,
+                                               ctypes.POINTER(QTensorStruct), vp]
         L.nvfp4_gemm.restype = ci
         L.nvfp4_gemm.argtypes = [ctypes.POINTER(QTensorStruct), ctypes.POINTER(QTensorStruct), ci, vp, ci, i64,
                                  vp, ctypes.c_size_t, vp]
@@ -167,6 +173,37 @@ def nvfp4_quantize(x: torch.Tensor, layout_mask: int, block_dim: int = BLOCK_1x1
     _check(load_library().nvfp4_quantize(x.data_ptr(), rows, cols, x.stride(0), layout_mask, block_dim, rounding,
                                          int(rht_on_col), rht_seed, sr_seed, ctypes.byref(out.desc),
                                          ws.data_ptr(), ws.numel(), _stream()))
+    return out
+
+
+def nvfp4_amax(x: torch.Tensor, rht_on_col=False, rht_seed: int = 0, out: Optional[torch.Tensor] = None,
+               workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Pass 1 alone: float32 CUDA tensor [2] = (amax of x, amax of the rotated x or 0)."""
+    if not x.is_cuda or x.dtype != torch.bfloat16 or x.dim() != 2 or x.stride(1) != 1:
+        raise ValueError("x must be a 2-D bf16 CUDA tensor with unit inner stride")
+    rows, cols = x.shape
+    if out is None:
+        out = torch.empty(2, dtype=torch.float32, device=x.device)
+    ws = workspace if workspace is not None else _workspace(x.device, quantized_sizes(rows, cols)[2])
+    _check(load_library().nvfp4_amax(x.data_ptr(), rows, cols, x.stride(0), int(rht_on_col), rht_seed, out.data_ptr(),
+                                     ws.data_ptr(), ws.numel(), _stream()))
+    return out
+
+
+def nvfp4_quantize_with_amax(x: torch.Tensor, amax: torch.Tensor, layout_mask: int, block_dim: int = BLOCK_1x16,
+                             rounding: int = ROUND_RNE, rht_on_col=False, rht_seed: int = 0, sr_seed: int = 0,
+                             out: Optional[QTensor] = None) -> QTensor:
+    """Pass 2 alone: `amax` is a float32 CUDA tensor [2] as nvfp4_amax returns it."""
+    if not x.is_cuda or x.dtype != torch.bfloat16 or x.dim() != 2 or x.stride(1) != 1:
+        raise ValueError("x must be a 2-D bf16 CUDA tensor with unit inner stride")
+    if not amax.is_cuda or amax.dtype != torch.float32 or amax.numel() != 2 or not amax.is_contiguous():
+        raise ValueError("amax must be a contiguous float32 CUDA tensor of 2 elements")
+    rows, cols = x.shape
+    if out is None:
+        out = alloc_qtensor(rows, cols, layout_mask, x.device, block_dim)
+    _check(load_library().nvfp4_quantize_with_amax(x.data_ptr(), rows, cols, x.stride(0), layout_mask, block_dim, rounding,
+                                                   int(rht_on_col), rht_seed, sr_seed, amax.data_ptr(),
+                                                   ctypes.byref(out.desc), _stream()))
     return out
 
 

@@ -110,9 +110,10 @@ struct QuantPlan {
   nvfp4_qtensor desc;
 };
 
+// amax_given: pass 2 only; `workspace` then is the caller's two amax words and no workspace size applies.
 int plan_quantize(const void* x, int64_t rows, int64_t cols, int64_t ld, int layout_mask, int block_dim, int rounding,
                   int rht_on_col, uint64_t rht_seed, uint64_t sr_seed, const nvfp4_qtensor* out, void* workspace,
-                  size_t workspace_bytes, QuantPlan* p) {
+                  size_t workspace_bytes, QuantPlan* p, bool amax_given = false) {
   if (!x || !out) return NVFP4_ERR_INVALID_ARG;
   if (layout_mask <= 0 || (layout_mask & ~(NVFP4_LAYOUT_ROW | NVFP4_LAYOUT_COL))) return NVFP4_ERR_INVALID_ARG;
   if (block_dim != NVFP4_BLOCK_1x16 && block_dim != NVFP4_BLOCK_16x16 && block_dim != NVFP4_BLOCK_MX32)
@@ -131,8 +132,11 @@ int plan_quantize(const void* x, int64_t rows, int64_t cols, int64_t ld, int lay
   if (want_row && (!aligned(out->row_codes, 16) || !aligned(out->row_scales, 16))) return NVFP4_ERR_INVALID_ARG;
   if (want_col && (!aligned(out->col_codes, 16) || !aligned(out->col_scales, 16))) return NVFP4_ERR_INVALID_ARG;
   // the MXFP4 mode is a single pass and needs no workspace
-  if (!mx && (!workspace || workspace_bytes < quantize_workspace_bytes(rows, cols) || !aligned(workspace, 16)))
+  if (amax_given) {
+    if (mx || !workspace || !aligned(workspace, 4)) return NVFP4_ERR_INVALID_ARG;
+  } else if (!mx && (!workspace || workspace_bytes < quantize_workspace_bytes(rows, cols) || !aligned(workspace, 16))) {
     return NVFP4_ERR_WORKSPACE;
+  }
 
   QuantizeArgs& a = p->a;
   a.x = x;
@@ -149,6 +153,7 @@ int plan_quantize(const void* x, int64_t rows, int64_t cols, int64_t ld, int lay
   a.key0 = static_cast<uint32_t>(sr_seed);
   a.key1 = static_cast<uint32_t>(sr_seed >> 32);
   a.ws = static_cast<uint32_t*>(workspace);
+  a.do_amax = !amax_given;
   a.row_codes = static_cast<uint8_t*>(out->row_codes);
   a.row_scales = static_cast<uint8_t*>(out->row_scales);
   a.row_ts = out->row_tensor_scale;
@@ -168,6 +173,43 @@ int plan_quantize(const void* x, int64_t rows, int64_t cols, int64_t ld, int lay
 }
 
 }  // namespace
+
+int nvfp4_amax(const void* x, int64_t rows, int64_t cols, int64_t ld, int rht_on_col, uint64_t rht_seed, float* amax_out,
+               void* workspace, size_t workspace_bytes, nvfp4_stream_t stream) {
+  if (!x || !amax_out || !aligned(x, 16) || !aligned(amax_out, 4)) return NVFP4_ERR_INVALID_ARG;
+  const int rht_dim = rotation_size(rht_on_col, false);
+  if (rht_dim < 0) return NVFP4_ERR_INVALID_ARG;
+  if (rows <= 0 || cols <= 0 || rows % 16 || cols % 16 || ld < cols || ld % 8) return NVFP4_ERR_BAD_SHAPE;
+  if (rht_dim && rows % rht_dim) return NVFP4_ERR_BAD_SHAPE;
+  if (!workspace || workspace_bytes < quantize_workspace_bytes(rows, cols) || !aligned(workspace, 16)) return NVFP4_ERR_WORKSPACE;
+  QuantizeArgs a{};
+  a.x = x;
+  a.rows = rows;
+  a.cols = cols;
+  a.ld = ld;
+  a.want_row = true;            // the amax of the tensor itself is always computed
+  a.want_col = rht_dim != 0;    // that of the rotated tensor if a rotation is named
+  a.rht = rht_dim != 0;
+  a.rht_dim = rht_dim;
+  fill_signs(rht_seed, rht_dim, &a.sign_mask, a.sign_words);
+  a.ws = static_cast<uint32_t*>(workspace);
+  a.do_amax = true;
+  a.do_cast = false;
+  a.amax_copy = reinterpret_cast<uint32_t*>(amax_out);
+  return launch_quantize(a, static_cast<hipStream_t>(stream)) == hipSuccess ? NVFP4_OK : NVFP4_ERR_HIP;
+}
+
+int nvfp4_quantize_with_amax(const void* x, int64_t rows, int64_t cols, int64_t ld, int layout_mask, int block_dim,
+                             int rounding, int rht_on_col, uint64_t rht_seed, uint64_t sr_seed, const float* amax_in,
+                             nvfp4_qtensor* out, nvfp4_stream_t stream) {
+  QuantPlan p;
+  const int rc = plan_quantize(x, rows, cols, ld, layout_mask, block_dim, rounding, rht_on_col, rht_seed, sr_seed, out,
+                               const_cast<float*>(amax_in), 0, &p, true);
+  if (rc != NVFP4_OK) return rc;
+  if (launch_quantize(p.a, static_cast<hipStream_t>(stream)) != hipSuccess) return NVFP4_ERR_HIP;
+  *out = p.desc;
+  return NVFP4_OK;
+}
 
 int nvfp4_quantize(const void* x, int64_t rows, int64_t cols, int64_t ld, int layout_mask, int block_dim,
                    int rounding, int rht_on_col, uint64_t rht_seed, uint64_t sr_seed, nvfp4_qtensor* out,

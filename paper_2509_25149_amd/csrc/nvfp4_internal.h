@@ -15,6 +15,10 @@ struct QuantizeArgs {
   uint32_t sign_words[4];  // the sign diagonal's bits, first rht_dim of the 128 meaningful
   uint32_t key0, key1;
   uint32_t* ws;  // device workspace: [0] raw amax bits, [1] rotated amax bits, then per-workgroup partials
+  // The two passes can run apart: without do_amax, ws is any two device words holding the amax bits (raw, rotated);
+  // without do_cast only the amax is computed, and amax_copy (if set) receives the two words as well.
+  bool do_amax = true, do_cast = true;
+  uint32_t* amax_copy = nullptr;
   uint8_t *row_codes, *row_scales;
   float* row_ts;
   uint8_t *col_codes, *col_scales;

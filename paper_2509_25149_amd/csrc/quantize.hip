@@ -199,9 +199,11 @@ static void dispatch_cast2(const QuantizeArgs& a, dim3 grid, hipStream_t s) {
 template <bool kRow, int kRht>
 static void launch_rotated(const QuantizeArgs& a, dim3 grid, hipStream_t s) {
   const uint16_t* x = static_cast<const uint16_t*>(a.x);
-  hipLaunchKernelGGL((amax_kernel<kRow, kRht>), grid, dim3(kThreads), 0, s, x, a.rows, a.cols, a.ld, a.sign_mask, a.ws);
-  hipLaunchKernelGGL(amax_finalize_kernel, dim3(1), dim3(1024), 0, s, a.ws, grid.x * grid.y);
-  dispatch_cast2<kRow, true, kRht>(a, grid, s);
+  if (a.do_amax) {
+    hipLaunchKernelGGL((amax_kernel<kRow, kRht>), grid, dim3(kThreads), 0, s, x, a.rows, a.cols, a.ld, a.sign_mask, a.ws);
+    hipLaunchKernelGGL(amax_finalize_kernel, dim3(1), dim3(1024), 0, s, a.ws, grid.x * grid.y, a.amax_copy);
+  }
+  if (a.do_cast) dispatch_cast2<kRow, true, kRht>(a, grid, s);
 }
 
 hipError_t launch_quantize(const QuantizeArgs& a, hipStream_t s) {
@@ -222,12 +224,16 @@ hipError_t launch_quantize(const QuantizeArgs& a, hipStream_t s) {
     }
     return hipGetLastError();
   }
-  hipLaunchKernelGGL((amax_kernel<true, 0>), grid, dim3(kThreads), 0, s, static_cast<const uint16_t*>(a.x), a.rows, a.cols,
-                     a.ld, a.sign_mask, a.ws);
-  hipLaunchKernelGGL(amax_finalize_kernel, dim3(1), dim3(1024), 0, s, a.ws, grid.x * grid.y);
-  if (a.want_row && a.want_col) dispatch_cast2<true, true, 0>(a, grid, s);
-  else if (a.want_row) dispatch_cast2<true, false, 0>(a, grid, s);
-  else dispatch_cast2<false, true, 0>(a, grid, s);
+  if (a.do_amax) {
+    hipLaunchKernelGGL((amax_kernel<true, 0>), grid, dim3(kThreads), 0, s, static_cast<const uint16_t*>(a.x), a.rows, a.cols,
+                       a.ld, a.sign_mask, a.ws);
+    hipLaunchKernelGGL(amax_finalize_kernel, dim3(1), dim3(1024), 0, s, a.ws, grid.x * grid.y, a.amax_copy);
+  }
+  if (a.do_cast) {
+    if (a.want_row && a.want_col) dispatch_cast2<true, true, 0>(a, grid, s);
+    else if (a.want_row) dispatch_cast2<true, false, 0>(a, grid, s);
+    else dispatch_cast2<false, true, 0>(a, grid, s);
+  }
   return hipGetLastError();
 }
 

@@ -149,8 +149,10 @@ constexpr int kColScalesBytes = 8 * kGroupsPerBlock * 64;            // 4096
 constexpr int kRowScalesBytes = 16 * kGroupsPerBlock * 32;           // 4096
 
 // Folds the per-workgroup maxima of pass 1 (nwg raw maxima, then nwg rotated maxima, after the header):
-// ws[0] = amax of the tensor, ws[1] = amax of the rotated tensor, both as FP32 bits.  One workgroup of 1024.
-static __global__ __launch_bounds__(1024) void amax_finalize_kernel(uint32_t* __restrict__ ws, uint32_t nwg) {
+// ws[0] = amax of the tensor, ws[1] = amax of the rotated tensor, both as FP32 bits (also stored to `copy` if
+// given).  One workgroup of 1024.
+static __global__ __launch_bounds__(1024) void amax_finalize_kernel(uint32_t* __restrict__ ws, uint32_t nwg,
+                                                                   uint32_t* __restrict__ copy) {
   __shared__ uint32_t red[2][16];
   uint32_t m0 = 0, m1 = 0;
   for (uint32_t i = threadIdx.x; i < nwg; i += 1024) {
@@ -168,6 +170,7 @@ static __global__ __launch_bounds__(1024) void amax_finalize_kernel(uint32_t* __
     uint32_t m = 0;
     for (int i = 0; i < 16; ++i) m = max(m, red[threadIdx.x][i]);
     ws[threadIdx.x] = m;
+    if (copy) copy[threadIdx.x] = m;
   }
 }
 

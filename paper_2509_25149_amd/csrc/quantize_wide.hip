@@ -210,8 +210,11 @@ template <bool kRow, int kD>
 void launch_wide(const QuantizeArgs& a, dim3 grid, hipStream_t s) {
   const uint16_t* x = static_cast<const uint16_t*>(a.x);
   const uint4 signs = make_uint4(a.sign_words[0], a.sign_words[1], a.sign_words[2], a.sign_words[3]);
-  hipLaunchKernelGGL((amax_wide_kernel<kRow, kD>), grid, dim3(kWideThreads), 0, s, x, a.rows, a.cols, a.ld, signs, a.ws);
-  hipLaunchKernelGGL(amax_finalize_kernel, dim3(1), dim3(1024), 0, s, a.ws, grid.x * grid.y);
+  if (a.do_amax) {
+    hipLaunchKernelGGL((amax_wide_kernel<kRow, kD>), grid, dim3(kWideThreads), 0, s, x, a.rows, a.cols, a.ld, signs, a.ws);
+    hipLaunchKernelGGL(amax_finalize_kernel, dim3(1), dim3(1024), 0, s, a.ws, grid.x * grid.y, a.amax_copy);
+  }
+  if (!a.do_cast) return;
   if (a.sr)
     hipLaunchKernelGGL((cast_wide_kernel<kRow, kD, true>), grid, dim3(kWideThreads), 0, s, x, a.rows, a.cols, a.ld, a.ws, signs,
                        a.key0, a.key1, a.row_codes, a.row_scales, a.row_ts, a.col_codes, a.col_scales, a.col_ts);

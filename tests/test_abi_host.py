@@ -199,3 +199,22 @@ def test_mxfp4_mode_argument_checks(lib):
     assert lib.nvfp4_gemm(ctypes.byref(a), ctypes.byref(b), 1, D, 0, 32, None, 0, None) == -1      # scale rows are read as dwords
     out = fake
     assert lib.nvfp4_dequantize(ctypes.byref(b), 0, 0, out, 0, 128, None) == -2                    # ld_out < K
+
+
+def test_separate_passes_reject_bad_arguments(lib):
+    """nvfp4_amax / nvfp4_quantize_with_amax validate on the host like nvfp4_quantize (no GPU here)."""
+    X, WS, AM = 0x10000, 0x20000, 0x30000
+    assert lib.nvfp4_amax(None, 16, 16, 16, 0, 0, AM, WS, 256, None) == -1
+    assert lib.nvfp4_amax(X, 16, 16, 16, 0, 0, None, WS, 256, None) == -1
+    assert lib.nvfp4_amax(X, 16, 16, 16, 8, 0, AM, WS, 256, None) == -1             # no rotation of size 8
+    assert lib.nvfp4_amax(X, 24, 16, 16, 0, 0, AM, WS, 256, None) == -2
+    assert lib.nvfp4_amax(X, 48, 16, 16, 32, 0, AM, WS, 256, None) == -2            # 48 rows: no whole groups of 32
+    assert lib.nvfp4_amax(X, 16, 16, 16, 0, 0, AM, None, 256, None) == -6
+    assert lib.nvfp4_amax(X, 16, 16, 16, 0, 0, AM, WS, 8, None) == -6
+    d = _desc()
+    tail = (AM, ctypes.byref(d), None)
+    assert lib.nvfp4_quantize_with_amax(X, 16, 16, 16, 1, 1, 0, 0, 0, 0, None, ctypes.byref(d), None) == -1   # no amax
+    assert lib.nvfp4_quantize_with_amax(X, 32, 32, 32, 1, 32, 0, 0, 0, 0, *tail) == -1                        # MXFP4 has none
+    assert lib.nvfp4_quantize_with_amax(X, 16, 16, 16, 0, 1, 0, 0, 0, 0, *tail) == -1
+    assert lib.nvfp4_quantize_with_amax(X, 24, 16, 16, 1, 1, 0, 0, 0, 0, *tail) == -2
+    assert lib.nvfp4_quantize_with_amax(X, 16, 16, 16, 1, 1, 0, 1, 0, 0, *tail) == -1                         # rotation without a col copy

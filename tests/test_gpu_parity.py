@@ -336,3 +336,56 @@ def test_layer_step_replays_from_a_hip_graph():
         got = (y, dx, dw, qx.col_codes, qdy.row_codes, qdy.col_scales)
         for g, w_ in zip(got, want):
             assert torch.equal(g, w_), f"replay {rep} differs from the eager result"
+
+
+# ---------------------------------------------------------------- the two passes as separate calls (App. B.1)
+
+@pytest.mark.parametrize("mode", [
+    dict(layout=nv.LAYOUT_ROW | nv.LAYOUT_COL, rht=16),
+    dict(layout=nv.LAYOUT_ROW | nv.LAYOUT_COL, rht=128, rounding=nv.ROUND_SR, sr_seed=7),
+    dict(layout=nv.LAYOUT_COL, rht=4),
+    dict(layout=nv.LAYOUT_ROW | nv.LAYOUT_COL, rht=0, block_dim=nv.BLOCK_16x16),
+    dict(layout=nv.LAYOUT_ROW, rht=0, rounding=nv.ROUND_SR, sr_seed=9),
+], ids=lambda m: "-".join(f"{k}{v}" for k, v in m.items()))
+def test_amax_then_quantize_with_amax_equals_quantize(mode):
+    rows, cols = 384, 1040
+    xb = synth.normal_with_outliers(rows, cols, 1.0, 4242, frac=0.01)
+    x = to_dev(xb)
+    kw = dict(block_dim=mode.get("block_dim", nv.BLOCK_1x16), rounding=mode.get("rounding", nv.ROUND_RNE),
+              rht_on_col=mode["rht"], rht_seed=31, sr_seed=mode.get("sr_seed", 0))
+    whole = nv.nvfp4_quantize(x, mode["layout"], **kw)
+    amax = nv.nvfp4_amax(x, mode["rht"], 31)
+    split = nv.nvfp4_quantize_with_amax(x, amax, mode["layout"], **kw)
+    torch.cuda.synchronize()
+    ob = oracle.BLOCK_16x16 if kw["block_dim"] == nv.BLOCK_16x16 else oracle.BLOCK_1x16
+    orr = oracle.SR if kw["rounding"] == nv.ROUND_SR else oracle.RNE
+    am = amax.cpu().numpy()
+    raw = oracle.quantize(xb, oracle.ROW, ob, orr, False, 0, kw["sr_seed"])
+    assert am[0].view(np.uint32) == raw.amax.view(np.uint32)
+    if mode["rht"]:
+        rot = oracle.quantize(xb, oracle.COL, ob, orr, True, 31, kw["sr_seed"], rht_dim=mode["rht"])
+        assert am[1].view(np.uint32) == rot.amax.view(np.uint32)
+    else:
+        assert am[1] == 0.0
+    assert split.desc.col_has_rht == whole.desc.col_has_rht and split.desc.layout_mask == whole.desc.layout_mask
+    if mode["layout"] & nv.LAYOUT_ROW:
+        assert torch.equal(split.row_codes, whole.row_codes) and torch.equal(split.row_scales, whole.row_scales)
+        assert torch.equal(split.row_ts, whole.row_ts)
+    if mode["layout"] & nv.LAYOUT_COL:
+        assert torch.equal(split.col_codes, whole.col_codes) and torch.equal(split.col_scales, whole.col_scales)
+        assert torch.equal(split.col_ts, whole.col_ts)
+
+
+@pytest.mark.parametrize("factor", [4.0, 1.0 / 64.0])
+def test_quantize_with_a_supplied_amax_matches_the_oracle(factor):
+    """A larger amax (as after a max over shards) and a far too small one (block scales and codes saturate)."""
+    rows, cols = 144, 528
+    xb = synth.normal_with_outliers(rows, cols, 1.0, 4343, frac=0.01)
+    x = to_dev(xb)
+    own = nv.nvfp4_amax(x, 16, 5).cpu().numpy()
+    given = torch.tensor(own * np.float32(factor), dtype=torch.float32, device="cuda")
+    q = nv.nvfp4_quantize_with_amax(x, given, nv.LAYOUT_ROW | nv.LAYOUT_COL, rht_on_col=16, rht_seed=5)
+    g = given.cpu().numpy()
+    assert_copy_equal(q.row_codes, q.row_scales, q.row_ts, oracle.quantize(xb, oracle.ROW, amax=float(g[0])), "row copy")
+    assert_copy_equal(q.col_codes, q.col_scales, q.col_ts,
+                      oracle.quantize(xb, oracle.COL, use_rht=True, rht_seed=5, amax=float(g[1])), "col copy")
