@@ -142,24 +142,25 @@ def rht_size_sweep(torch, nv, x, dy, iters: int = 5):
     qdy = nv.alloc_qtensor(TOKENS, D_FFN, RC)
     ev = lambda: torch.cuda.Event(enable_timing=True)
     res = {}
-    for d in (2, 4, 16, 32, 128):
+    for d, layout in ((2, RC), (4, RC), (16, RC), (32, RC), (128, RC), (16, RC | nv.LAYOUT_ROW_RHT)):
         tx = tg = 0.0
         for it in range(iters + 1):
             m = [ev() for _ in range(3)]
             m[0].record()
-            nv.nvfp4_quantize(x, RC, nv.BLOCK_1x16, nv.ROUND_RNE, d, 2025, 0, out=qx)
+            nv.nvfp4_quantize(x, layout, nv.BLOCK_1x16, nv.ROUND_RNE, d, 2025, 0, out=qx)
             m[1].record()
-            nv.nvfp4_quantize(dy, RC, nv.BLOCK_1x16, nv.ROUND_SR, d, 2025, 77 + it, out=qdy)
+            nv.nvfp4_quantize(dy, layout, nv.BLOCK_1x16, nv.ROUND_SR, d, 2025, 77 + it, out=qdy)
             m[2].record()
             torch.cuda.synchronize()
             if it:
                 tx += m[0].elapsed_time(m[1])
                 tg += m[1].elapsed_time(m[2])
-        res[f"d{d}"] = {"X_ms": tx / iters, "dY_ms": tg / iters,
+        res[f"d{d}" + ("_row_copy_rotated_too" if layout != RC else "")] = {"X_ms": tx / iters, "dY_ms": tg / iters,
                         "GBps_one_pass_accounting": (quant_bytes(TOKENS * D_MODEL, 2) + quant_bytes(TOKENS * D_FFN, 2))
                                                     / ((tx + tg) / iters * 1e-3) / 1e9}
     res["note"] = ("not part of `value`: nvfp4_quantize of X (RNE) and dY (SR), row + rotated col copy, per rotation size; "
-                   "d <= 16 rotate inside a lane's 16 rows, d = 32 / 128 exchange through LDS")
+                   "d <= 16 rotate inside a lane's 16 rows, d = 32 / 128 exchange through LDS; the last entry also rotates the "
+                   "row copy along its columns (the Fprop / Dgrad operands of App. E.4.1)")
     return res
 
 

@@ -63,6 +63,14 @@ typedef enum nvfp4_status {
 } nvfp4_status;
 
 enum { NVFP4_LAYOUT_ROW = 1, NVFP4_LAYOUT_COL = 2 };       /* layout mask bits */
+/* Extra layout mask bit of nvfp4_quantize: rotate the row copy too.  Sec. 4.2 restricts the random Hadamard
+ * transform to the Wgrad operands (the col copies); App. E.4.1 ablates it on the operands of Fprop and Dgrad, whose
+ * contraction runs along the row copy's columns.  With this bit every aligned group of 16 consecutive columns of a
+ * row is multiplied by the sign diagonal of rht_seed and by H_16 before scaling (App. C; same stage order and
+ * normalisation as for the col copy), and the row copy's tensor scale comes from the amax of the values rotated
+ * that way.  NVFP4 with 1x16 blocks only, NVFP4_LAYOUT_ROW required, the col copy (if asked for) plain or rotated
+ * with d = 16; not accepted by nvfp4_quantize_with_amax.  The descriptor records it as row_has_rht = 16. */
+enum { NVFP4_LAYOUT_ROW_RHT = 4 };
 /* block_dim.  NVFP4_BLOCK_MX32 selects the paper's comparison format MXFP4 instead of NVFP4 (Sec. 2, App. B.4,
  * Sec. 5): blocks of 32 along the copy's contiguous dimension, one UE8M0 byte per block (2^(byte - 127), amax_b / 6
  * rounded up to a power of two), no tensor-level scale (tensor_scale = {1, 0}), scales [.., ../32] bytes, a 32-point
@@ -95,6 +103,7 @@ typedef struct nvfp4_qtensor {
   int32_t rounding;         /* NVFP4_ROUND_* used */
   int32_t col_has_rht;      /* 0, or the size d of the rotation applied to the col copy */
   uint64_t rht_seed;        /* seed of the sign diagonal, if rotated */
+  int32_t row_has_rht;      /* 0, or 16: the row copy is rotated along its columns (NVFP4_LAYOUT_ROW_RHT) */
 } nvfp4_qtensor;
 
 /*
@@ -109,6 +118,7 @@ int nvfp4_quantized_sizes(int64_t rows, int64_t cols, size_t* codes_bytes, size_
  * Quantize a bf16 tensor to NVFP4 (App. B Eq. 1-4).
  *   x            device, bf16 [rows, cols], row-major with leading dimension ld (elements)
  *   layout_mask  NVFP4_LAYOUT_ROW | NVFP4_LAYOUT_COL: which copies to emit
+ *                (| NVFP4_LAYOUT_ROW_RHT: the row copy rotated as well)
  *   block_dim    1x16 (activations, gradients) or 16x16 (weights, Sec. 4.3)
  *   rounding     RNE (weights, activations) or SR (gradients), Sec. 4.4
  *   rht_on_col   rotate the col copy: every aligned group of d consecutive
@@ -166,8 +176,10 @@ int nvfp4_quantize_with_amax(const void* x, int64_t rows, int64_t cols, int64_t 
  *   FPROP  Y  = X W      A = row copy of X [M,K],   B = col copy of W [K,N] (-> [N,K])
  *   DGRAD  dX = dY W^T   A = row copy of dY [M,K],  B = row copy of W [N,K]
  *   WGRAD  dW = A^T B    A = col copy of the first tensor [K,M] (-> [M,K]),
- *                        B = col copy of the second [K,N] (-> [N,K]); both must
- *                        agree on rotation size and seed (App. C)
+ *                        B = col copy of the second [K,N] (-> [N,K])
+ * For every op the two copies it reads must agree on rotation size and seed
+ * (col_has_rht / row_has_rht of the copy read; App. C: the two rotations cancel
+ * in the product only if they are the same), else NVFP4_ERR_MISMATCH.
  * D is device memory, [M, N] row-major with leading dimension ldd (a multiple
  * of 4), FP32 or bf16 (bf16 = round-to-nearest-even of the FP32 result).  With
  * NVFP4_OUT_F32_ACCUMULATE, D is FP32 and is read: every element becomes
@@ -227,7 +239,8 @@ int nvfp4_linear_backward(const void* dy, int64_t tokens, int64_t d_out, int64_t
  * Decode one copy back to FP32 or bf16: value(code) * block scale * s_dec
  * (Sec. 2; App. B.2).  The output has the copy's own orientation: [rows, cols]
  * for the row copy, [cols, rows] for the col copy, leading dimension ld_out.
- * undo_rht rotates each group of d back, d = q->col_has_rht (only meaningful for a rotated copy).
+ * undo_rht rotates each group of d back, d = q->col_has_rht or q->row_has_rht of the chosen copy (NVFP4_ERR_MISMATCH
+ * for a copy that is not rotated).
  */
 int nvfp4_dequantize(const nvfp4_qtensor* q, int which_copy, int undo_rht, void* out, int out_dtype,
                      int64_t ld_out, nvfp4_stream_t stream);

@@ -58,6 +58,14 @@
 //     single outlier, the amax the quantizer reports for such a tensor and
 //     the invariance of the product; the bit-to-sign assignment is this
 //     repository's convention (parity unpinned against the paper).
+//   * A rotation always runs along the block direction of the copy being
+//     quantized.  For a col copy that is the tensor's rows (the Wgrad
+//     operands of the recipe); asked for on a row copy it is the tensor's
+//     columns, the transform on the Fprop / Dgrad operands that App. E.4.1
+//     ablates.  Pinned (tests/test_oracle_row_rotation.py) by the spread of
+//     a single outlier along its row with the signs of the dense form, the
+//     dense form of the stored values, the transposition identity with the
+//     col copy, and the cancellation in Fprop and Dgrad.
 //
 // PARITY PINS (tests/test_oracle_*.py): E2M1/E4M3 by brute force over the whole
 // code space; Philox by the published known-answer vectors; the transform by

@@ -17,6 +17,7 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libnvfp4_hip.so")
 
 LAYOUT_ROW, LAYOUT_COL = 1, 2
+LAYOUT_ROW_RHT = 4   # with LAYOUT_ROW: the row copy is rotated too (16-point, along its columns)
 BLOCK_1x16, BLOCK_16x16, BLOCK_MX32 = 1, 16, 32
 ROUND_RNE, ROUND_SR = 0, 1
 OP_FPROP, OP_DGRAD, OP_WGRAD = 0, 1, 2
@@ -38,7 +39,7 @@ class QTensorStruct(ctypes.Structure):
                 ("col_tensor_scale", ctypes.c_void_p),
                 ("layout_mask", ctypes.c_int32), ("block_dim", ctypes.c_int32),
                 ("rounding", ctypes.c_int32), ("col_has_rht", ctypes.c_int32),
-                ("rht_seed", ctypes.c_uint64)]
+                ("rht_seed", ctypes.c_uint64), ("row_has_rht", ctypes.c_int32)]
 
 
 _lib = None

@@ -115,7 +115,11 @@ int plan_quantize(const void* x, int64_t rows, int64_t cols, int64_t ld, int lay
                   int rht_on_col, uint64_t rht_seed, uint64_t sr_seed, const nvfp4_qtensor* out, void* workspace,
                   size_t workspace_bytes, QuantPlan* p, bool amax_given = false) {
   if (!x || !out) return NVFP4_ERR_INVALID_ARG;
-  if (layout_mask <= 0 || (layout_mask & ~(NVFP4_LAYOUT_ROW | NVFP4_LAYOUT_COL))) return NVFP4_ERR_INVALID_ARG;
+  if (layout_mask <= 0 || (layout_mask & ~(NVFP4_LAYOUT_ROW | NVFP4_LAYOUT_COL | NVFP4_LAYOUT_ROW_RHT)))
+    return NVFP4_ERR_INVALID_ARG;
+  const bool row_rht = layout_mask & NVFP4_LAYOUT_ROW_RHT;
+  layout_mask &= NVFP4_LAYOUT_ROW | NVFP4_LAYOUT_COL;
+  if (layout_mask == 0) return NVFP4_ERR_INVALID_ARG;
   if (block_dim != NVFP4_BLOCK_1x16 && block_dim != NVFP4_BLOCK_16x16 && block_dim != NVFP4_BLOCK_MX32)
     return NVFP4_ERR_INVALID_ARG;
   if (rounding != NVFP4_ROUND_RNE && rounding != NVFP4_ROUND_SR) return NVFP4_ERR_INVALID_ARG;
@@ -123,6 +127,9 @@ int plan_quantize(const void* x, int64_t rows, int64_t cols, int64_t ld, int lay
   const bool mx = block_dim == NVFP4_BLOCK_MX32;
   const int rht_dim = rotation_size(rht_on_col, mx);
   if (rht_dim < 0 || (rht_dim && (block_dim == NVFP4_BLOCK_16x16 || !want_col))) return NVFP4_ERR_INVALID_ARG;
+  // A rotated row copy: NVFP4 1x16 blocks, the 16-point rotation only, both passes in this call.
+  if (row_rht && (!want_row || block_dim != NVFP4_BLOCK_1x16 || (rht_dim && rht_dim != 16) || amax_given))
+    return NVFP4_ERR_INVALID_ARG;
   if (rows <= 0 || cols <= 0 || rows % 16 || cols % 16 || ld < cols || ld % 8) return NVFP4_ERR_BAD_SHAPE;
   if (rht_dim && rows % rht_dim) return NVFP4_ERR_BAD_SHAPE;   // whole rotation groups along the rows
   if (mx && (rows % 32 || cols % 32)) return NVFP4_ERR_BAD_SHAPE;
@@ -149,7 +156,8 @@ int plan_quantize(const void* x, int64_t rows, int64_t cols, int64_t ld, int lay
   a.rht_dim = rht_dim;
   a.sr = rounding == NVFP4_ROUND_SR;
   a.block2d = block_dim == NVFP4_BLOCK_16x16;
-  fill_signs(rht_seed, rht_dim, &a.sign_mask, a.sign_words);
+  a.row_rht = row_rht;
+  fill_signs(rht_seed, row_rht ? 16 : rht_dim, &a.sign_mask, a.sign_words);
   a.key0 = static_cast<uint32_t>(sr_seed);
   a.key1 = static_cast<uint32_t>(sr_seed >> 32);
   a.ws = static_cast<uint32_t*>(workspace);
@@ -168,7 +176,8 @@ int plan_quantize(const void* x, int64_t rows, int64_t cols, int64_t ld, int lay
   p->desc.block_dim = block_dim;
   p->desc.rounding = rounding;
   p->desc.col_has_rht = rht_dim;
-  p->desc.rht_seed = a.rht ? rht_seed : 0;
+  p->desc.row_has_rht = row_rht ? 16 : 0;
+  p->desc.rht_seed = (a.rht || row_rht) ? rht_seed : 0;
   return NVFP4_OK;
 }
 
@@ -280,7 +289,7 @@ static int plan_gemm(const nvfp4_qtensor* a, const nvfp4_qtensor* b, int op, voi
     return NVFP4_ERR_INVALID_ARG;
   g.mx = a_mx;
   // Rotated operands only make sense in pairs that rotate the same way (App. C).
-  const int a_rot = a_col ? a->col_has_rht : 0, b_rot = b_col ? b->col_has_rht : 0;   // rotation sizes
+  const int a_rot = a_col ? a->col_has_rht : a->row_has_rht, b_rot = b_col ? b->col_has_rht : b->row_has_rht;   // rotation sizes
   if (a_rot != b_rot || (a_rot && a->rht_seed != b->rht_seed)) return NVFP4_ERR_MISMATCH;
   if (ka <= 0 || ka % 16 || g.a.outer <= 0 || g.b.outer <= 0) return NVFP4_ERR_BAD_SHAPE;
   if (ldd < g.b.outer || ldd % 4) return NVFP4_ERR_BAD_SHAPE;
@@ -367,12 +376,13 @@ int nvfp4_dequantize(const nvfp4_qtensor* q, int which_copy, int undo_rht, void*
   DequantArgs d;
   int rc = pick_operand(q, which_copy == NVFP4_COPY_COL, &d.q, &d.K);
   if (rc != NVFP4_OK) return rc;
-  if (undo_rht && !(which_copy == NVFP4_COPY_COL && q->col_has_rht)) return NVFP4_ERR_MISMATCH;
+  const int copy_rht = which_copy == NVFP4_COPY_COL ? q->col_has_rht : q->row_has_rht;
+  if (undo_rht && !copy_rht) return NVFP4_ERR_MISMATCH;
   const bool mx = q->block_dim == NVFP4_BLOCK_MX32;
   if (d.K <= 0 || d.K % (mx ? 32 : 16) || ld_out < d.K || ld_out % 8) return NVFP4_ERR_BAD_SHAPE;
   if (!aligned(out, 16) || !aligned(d.q.codes, mx ? 16 : 8)) return NVFP4_ERR_INVALID_ARG;
   d.undo_rht = undo_rht != 0;
-  d.rht_dim = d.undo_rht ? q->col_has_rht : 0;
+  d.rht_dim = d.undo_rht ? copy_rht : 0;
   if (d.undo_rht && (rotation_size(d.rht_dim, mx) != d.rht_dim || d.rht_dim == 1 || d.K % d.rht_dim)) return NVFP4_ERR_MISMATCH;
   fill_signs(q->rht_seed, d.rht_dim, &d.sign_mask, d.sign_words);
   d.out = out;

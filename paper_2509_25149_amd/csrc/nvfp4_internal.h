@@ -10,11 +10,13 @@ struct QuantizeArgs {
   const void* x;
   int64_t rows, cols, ld;
   bool want_row, want_col, rht, sr, block2d;
+  bool row_rht = false;    // the row copy is rotated too (16-point, along the columns); sign_mask then holds the 16 signs
   int rht_dim;             // 0, or the rotation size: 2, 4, 16, 32, 128 (NVFP4); 32 (MXFP4)
   uint32_t sign_mask;      // the sign diagonal: d <= 16: its d bits repeated over the low 16 bits; 32: its 32 bits
   uint32_t sign_words[4];  // the sign diagonal's bits, first rht_dim of the 128 meaningful
   uint32_t key0, key1;
-  uint32_t* ws;  // device workspace: [0] raw amax bits, [1] rotated amax bits, then per-workgroup partials
+  uint32_t* ws;  // device workspace: [0] raw amax bits, [1] rotated amax bits, [2] amax bits of the row-rotated
+                 // tensor (row_rht only), then per-workgroup partials
   // The two passes can run apart: without do_amax, ws is any two device words holding the amax bits (raw, rotated);
   // without do_cast only the amax is computed, and amax_copy (if set) receives the two words as well.
   bool do_amax = true, do_cast = true;
@@ -27,6 +29,8 @@ struct QuantizeArgs {
 hipError_t launch_quantize(const QuantizeArgs& a, hipStream_t s);
 // NVFP4 with a 32- or 128-point rotation of the col copy (rotation groups span several 16-row groups)
 hipError_t launch_quantize_wide(const QuantizeArgs& a, hipStream_t s);
+// NVFP4 with the row copy rotated as well (row_rht; the col copy absent, plain or rotated with d = 16)
+hipError_t launch_quantize_rowrot(const QuantizeArgs& a, hipStream_t s);
 // MXFP4 mode (1x32 blocks, UE8M0 scales, one pass, no workspace); sign_mask holds 32 bits
 hipError_t launch_quantize_mx(const QuantizeArgs& a, hipStream_t s);
 size_t quantize_workspace_bytes(int64_t rows, int64_t cols);

@@ -175,7 +175,7 @@ __global__ __launch_bounds__(kThreads, 2) void cast_kernel(
 
 size_t quantize_workspace_bytes(int64_t rows, int64_t cols) {
   const int64_t gx = (cols + kWaveCols - 1) / kWaveCols, gy = (rows / 16 + kGroupsPerBlock - 1) / kGroupsPerBlock;
-  return static_cast<size_t>(kWsHeader + 2 * gx * gy) * sizeof(uint32_t);
+  return static_cast<size_t>(kWsHeader + 3 * gx * gy) * sizeof(uint32_t);   // raw, col-rotated, row-rotated maxima
 }
 
 template <bool kRow, bool kCol, int kRht, bool kSR, bool k2D>
@@ -210,6 +210,7 @@ hipError_t launch_quantize(const QuantizeArgs& a, hipStream_t s) {
   const dim3 grid(static_cast<unsigned>((a.cols + kWaveCols - 1) / kWaveCols),
                   static_cast<unsigned>((a.rows / 16 + kGroupsPerBlock - 1) / kGroupsPerBlock));
   const int rht = a.want_col ? a.rht_dim : 0;
+  if (a.row_rht) return launch_quantize_rowrot(a, s);
   if (rht > 16) return launch_quantize_wide(a, s);
   if (rht) {
     // the raw amax is only needed when the (never rotated) row copy is asked for as well

@@ -3,6 +3,7 @@ and rejects bad arguments synchronously (no kernel is ever enqueued here)."""
 import ctypes
 import os
 import re
+import subprocess
 
 import pytest
 
@@ -28,9 +29,21 @@ def test_every_declared_symbol_is_exported(lib):
     assert lib.nvfp4_version() >= 100
 
 
-def test_struct_layout_matches_header():
-    assert ctypes.sizeof(nv.QTensorStruct) == 2 * 8 + 6 * 8 + 4 * 4 + 8
-    assert nv.QTensorStruct.rht_seed.offset == 80
+def test_struct_layout_matches_header(tmp_path):
+    # the C compiler's view of the descriptor in include/nvfp4.h against the ctypes mirror, field by field
+    fields = [f[0] for f in nv.QTensorStruct._fields_]
+    c_names = {"row_tensor_scale": "row_tensor_scale", "col_tensor_scale": "col_tensor_scale"}
+    src = tmp_path / "layout.c"
+    src.write_text('#include <stddef.h>\n#include <stdio.h>\n#include "nvfp4.h"\nint main(void) {\n'
+                   '  printf("%zu\\n", sizeof(nvfp4_qtensor));\n' +
+                   "".join(f'  printf("%zu\\n", offsetof(nvfp4_qtensor, {c_names.get(f, f)}));\n' for f in fields) +
+                   "  return 0;\n}\n")
+    exe = tmp_path / "layout"
+    subprocess.run(["gcc", "-std=c99", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe)], check=True)
+    out = [int(v) for v in subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()]
+    assert out[0] == ctypes.sizeof(nv.QTensorStruct)
+    assert out[1:] == [getattr(nv.QTensorStruct, f).offset for f in fields]
+    assert nv.QTensorStruct.rht_seed.offset == 80 and nv.QTensorStruct.row_has_rht.offset == 88
 
 
 def test_sizes(lib):
@@ -69,7 +82,14 @@ def test_quantize_rejects_bad_arguments(lib):
     ok_tail = (ctypes.byref(d), WS, 256, None)
     assert lib.nvfp4_quantize(None, 16, 16, 16, 1, 1, 0, 0, 0, 0, *ok_tail) == -1
     assert lib.nvfp4_quantize(X, 16, 16, 16, 0, 1, 0, 0, 0, 0, *ok_tail) == -1      # empty layout mask
-    assert lib.nvfp4_quantize(X, 16, 16, 16, 4, 1, 0, 0, 0, 0, *ok_tail) == -1
+    assert lib.nvfp4_quantize(X, 16, 16, 16, 4, 1, 0, 0, 0, 0, *ok_tail) == -1      # the row-rotation bit alone
+    assert lib.nvfp4_quantize(X, 16, 16, 16, 8, 1, 0, 0, 0, 0, *ok_tail) == -1      # unknown bit
+    assert lib.nvfp4_quantize(X, 16, 16, 16, 2 | 4, 1, 0, 16, 0, 0, *ok_tail) == -1  # a rotated row copy needs a row copy,
+    assert lib.nvfp4_quantize(X, 16, 16, 16, 1 | 4, 16, 0, 0, 0, 0, *ok_tail) == -1  # 1x16 blocks,
+    assert lib.nvfp4_quantize(X, 32, 32, 32, 1 | 4, 32, 0, 0, 0, 0, *ok_tail) == -1  # NVFP4,
+    assert lib.nvfp4_quantize(X, 16, 16, 16, 3 | 4, 1, 0, 4, 0, 0, *ok_tail) == -1   # and a col copy plain or rotated by 16
+    assert lib.nvfp4_quantize(X, 24, 16, 16, 1 | 4, 1, 0, 0, 0, 0, *ok_tail) == -2   # shapes are checked as ever
+    assert lib.nvfp4_quantize_with_amax(X, 16, 16, 16, 1 | 4, 1, 0, 0, 0, 0, WS, ctypes.byref(d), None) == -1
     assert lib.nvfp4_quantize(X, 16, 16, 16, 1, 2, 0, 0, 0, 0, *ok_tail) == -1      # unknown block_dim
     assert lib.nvfp4_quantize(X, 16, 16, 16, 1, 1, 7, 0, 0, 0, *ok_tail) == -1      # unknown rounding
     assert lib.nvfp4_quantize(X, 16, 16, 16, 3, 16, 0, 1, 0, 0, *ok_tail) == -1     # rotation with 16x16 blocks
@@ -114,6 +134,14 @@ def test_gemm_and_dequantize_reject_bad_arguments(lib):
     assert lib.nvfp4_dequantize(ctypes.byref(bad), 1, 1, D, 0, 128, None) == -4
     short = _desc(64, 32, rht=128, seed=5)                                              # 64 rows cannot hold a 128-point group
     assert lib.nvfp4_dequantize(ctypes.byref(short), 1, 1, D, 0, 64, None) == -4
+    # Fprop / Dgrad read row copies: a rotated row copy needs its partner rotated alike
+    xr = _desc(32, 64)
+    xr.row_has_rht, xr.rht_seed = 16, 5
+    assert lib.nvfp4_gemm(ctypes.byref(xr), ctypes.byref(b), 0, D, 0, 48, None, 0, None) == -4     # B's col copy is plain
+    b_other = _desc(64, 48, rht=16, seed=6)
+    assert lib.nvfp4_gemm(ctypes.byref(xr), ctypes.byref(b_other), 0, D, 0, 48, None, 0, None) == -4   # other seed
+    w_row = _desc(48, 64)
+    assert lib.nvfp4_gemm(ctypes.byref(xr), ctypes.byref(w_row), 1, D, 0, 48, None, 0, None) == -4  # Dgrad, W's row copy plain
     assert lib.nvfp4_dequantize(ctypes.byref(a), 3, 0, D, 0, 64, None) == -1
     assert lib.nvfp4_dequantize(ctypes.byref(a), 0, 1, D, 0, 64, None) == -4            # undo_rht on a plain copy
     assert lib.nvfp4_dequantize(ctypes.byref(a), 0, 0, D, 0, 32, None) == -2

@@ -165,6 +165,21 @@ def test_other_rotation_sizes_at_full_size(name, d, rounding):
     assert_copy(q.col_codes, q.col_scales, q.col_ts, col, f"{name} d={d} col copy")
 
 
+@pytest.mark.parametrize("name,rounding", [("activation", nv.ROUND_RNE), ("gradient", nv.ROUND_SR)])
+def test_rotated_row_copy_at_full_size(name, rounding):
+    """Both copies of the 12B shapes with the row copy rotated too (the Fprop / Dgrad operands of App. E.4.1)."""
+    rows, cols, seed = {"activation": (8192, 5120, 521), "gradient": (8192, 20480, 522)}[name]
+    xb = synth.student_t3(rows, cols, 0.02, seed)
+    q = nv.nvfp4_quantize(to_dev(xb), nv.LAYOUT_ROW | nv.LAYOUT_COL | nv.LAYOUT_ROW_RHT, rounding=rounding, rht_on_col=16,
+                          rht_seed=RHT_SEED, sr_seed=SR_SEED)
+    orr = oracle.SR if rounding == nv.ROUND_SR else oracle.RNE
+    row = oracle.quantize(xb, oracle.ROW, oracle.BLOCK_1x16, orr, True, RHT_SEED, SR_SEED)
+    assert_copy(q.row_codes, q.row_scales, q.row_ts, row, f"{name} rotated row copy")
+    del row
+    col = oracle.quantize(xb, oracle.COL, oracle.BLOCK_1x16, orr, True, RHT_SEED, SR_SEED)
+    assert_copy(q.col_codes, q.col_scales, q.col_ts, col, f"{name} col copy")
+
+
 def test_contraction_too_long_for_the_two_pass_kernel():
     """K = 2^21: the FP16 GEMM kernel's 32-bit byte offsets inside a block of rows stop there, so the call must take
     the fused route even when a workspace is lent; results as usual."""
