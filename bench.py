@@ -191,6 +191,40 @@ def known_amax_block(torch, nv, x, w, dy, iters: int = 5):
     return res
 
 
+def matrix_pipe_context(torch, nv, reps: int = 3, iters: int = 100000):
+    """What the FP16 matrix pipe sustains on this machine, measured beside the step: the library's register-only MFMA loop
+    (no memory traffic) per operand kind, and the vendor library's FP16 GEMM (torch.matmul) at the Fprop shape on
+    random data.  Context for `roofline.frac`; outside the timed region of `value`."""
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    buf = torch.empty(nv.MFMA_PROBE_WORKGROUPS * 256, dtype=torch.float32, device="cuda")
+    res = {}
+    for kind, name in ((0, "ones"), (1, "random_fp16"), (2, "nvfp4_like_values")):
+        nv.nvfp4_selftest_mfma_rate(kind, iters // 10, buf)
+        a, b = ev(), ev()
+        a.record()
+        flops = sum(nv.nvfp4_selftest_mfma_rate(kind, iters, buf) for _ in range(reps))
+        b.record()
+        torch.cuda.synchronize()
+        res[f"register_only_mfma_{name}_TFLOPs"] = flops / (a.elapsed_time(b) * 1e-3) / 1e12
+    g = torch.Generator(device="cuda").manual_seed(5)
+    xa = torch.randn((TOKENS, D_MODEL), generator=g, device="cuda", dtype=torch.float16)
+    wb = torch.randn((D_MODEL, D_FFN), generator=g, device="cuda", dtype=torch.float16)
+    yc = torch.empty((TOKENS, D_FFN), device="cuda", dtype=torch.float16)
+    for _ in range(3):
+        torch.matmul(xa, wb, out=yc)
+    a, b = ev(), ev()
+    a.record()
+    for _ in range(10):
+        torch.matmul(xa, wb, out=yc)
+    b.record()
+    torch.cuda.synchronize()
+    res["vendor_fp16_gemm_fprop_shape_TFLOPs"] = 10 * 2.0 * TOKENS * D_MODEL * D_FFN / (a.elapsed_time(b) * 1e-3) / 1e12
+    res["note"] = ("not part of `value`: v_mfma_f32_16x16x32_f16 in a register-only loop (512 workgroups x 4 wavefronts, 16 "
+                   "independent accumulators) per operand kind -- the chip is power-limited, the rate depends on the "
+                   "operand bits; and torch.matmul FP16 [8192,5120]x[5120,20480] on N(0,1) data")
+    return res
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -199,6 +233,7 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-mxfp4", action="store_true", help="skip the MXFP4 comparison block")
     ap.add_argument("--no-rht-sweep", action="store_true", help="skip the rotation-size block")
+    ap.add_argument("--no-context", action="store_true", help="skip the matrix-pipe context block")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1",
@@ -314,8 +349,8 @@ def main() -> int:
                      "unit": "TFLOP/s", "frac": gemm_tflops / PEAK_MFMA_F16_TFLOPS,
                      "traffic": MEASURED_TRAFFIC_BYTES["gemm_call"],
                      "flops_per_launch": gemm_flops, "avg_launch_ms": gemm_avg_ms,
-                     "note": "peak is the published FP16 dense MFMA rate; a register-only MFMA loop on this box sustains "
-                             "2.27e3 TFLOP/s with constant operands and 1.65e3 with random operands (power-limited)"},
+                     "note": "peak is the published FP16 dense MFMA rate; what a register-only MFMA loop sustains on this "
+                             "box under its power limit is measured in `matrix_pipe_context`"},
         "roofline_quantize": {"kernel": "three nvfp4_quantize calls = amax_kernel + amax_finalize_kernel + cast_kernel each",
                               "bound": "hbm", "achieved": q_total_gbps,
                               "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": q_total_gbps / PEAK_HBM_GBPS,
@@ -330,6 +365,10 @@ def main() -> int:
     if not args.no_rht_sweep:
         out["rht_size_sweep"] = rht_size_sweep(torch, nv, x, dy)
         out["quantize_with_known_amax"] = known_amax_block(torch, nv, x, w, dy)
+    if not args.no_context:
+        out["matrix_pipe_context"] = matrix_pipe_context(torch, nv)
+        ctx = out["matrix_pipe_context"]
+        out["roofline"]["frac_of_register_only_rate_nvfp4_like_values"] = gemm_tflops / ctx["register_only_mfma_nvfp4_like_values_TFLOPs"]
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(torch, nv, x, w)
     print(json.dumps(out))

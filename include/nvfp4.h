@@ -260,6 +260,21 @@ uint32_t nvfp4_rht_sign_mask(uint64_t rht_seed);
  */
 int nvfp4_selftest_conversions(uint64_t* mismatches, nvfp4_stream_t stream);
 
+/*
+ * Matrix-pipe rate probe (measurement aid, not a step of the method; Sec. 2 "Hardware support" quotes FP4 math
+ * rates as multiples of the 16-bit rate, and the two-pass GEMM here runs on the FP16 matrix instruction): launches
+ * a register-only loop of that instruction, v_mfma_f32_16x16x32_f16, on NVFP4_MFMA_PROBE_WORKGROUPS workgroups of
+ * 256 threads -- no memory or LDS traffic -- so that timing the call gives the rate the chip sustains under its
+ * power limit for operands of the given kind: 0 = all ones, 1 = uniform random FP16 in [-2, 2), 2 = products of an
+ * E2M1 value and an E4M3 scale (what the NVFP4 GEMM multiplies).
+ *   iters  loop trips, 1 .. 2^24 (16 MFMAs per wavefront and trip)
+ *   out    device, float[NVFP4_MFMA_PROBE_WORKGROUPS * 256], receives one checksum per thread
+ *   flops  host, receives the flop count of the launch (2 * 16 * 16 * 32 per MFMA)
+ * Asynchronous; the caller times it.
+ */
+enum { NVFP4_MFMA_PROBE_WORKGROUPS = 512 };
+int nvfp4_selftest_mfma_rate(int operand_kind, int64_t iters, float* out, double* flops, nvfp4_stream_t stream);
+
 const char* nvfp4_status_string(int status);
 int nvfp4_version(void);
 

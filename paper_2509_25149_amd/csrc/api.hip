@@ -397,4 +397,10 @@ int nvfp4_selftest_conversions(uint64_t* mismatches, nvfp4_stream_t stream) {
   return run_selftest(mismatches, static_cast<hipStream_t>(stream)) == hipSuccess ? NVFP4_OK : NVFP4_ERR_HIP;
 }
 
+int nvfp4_selftest_mfma_rate(int operand_kind, int64_t iters, float* out, double* flops, nvfp4_stream_t stream) {
+  if (!out || !flops || !aligned(out, 4)) return NVFP4_ERR_INVALID_ARG;
+  if (operand_kind < 0 || operand_kind > 2 || iters <= 0 || iters > (1ll << 24)) return NVFP4_ERR_INVALID_ARG;
+  return run_mfma_rate(operand_kind, iters, out, flops, static_cast<hipStream_t>(stream)) == hipSuccess ? NVFP4_OK : NVFP4_ERR_HIP;
+}
+
 }  // extern "C"

@@ -73,6 +73,8 @@ hipError_t launch_dequantize(const DequantArgs& d, hipStream_t s);
 hipError_t launch_dequantize_mx(const DequantArgs& d, hipStream_t s);   // scales are UE8M0 per 32
 
 hipError_t run_selftest(uint64_t* mismatches_dev, hipStream_t s);
+constexpr int kMfmaProbeWorkgroups = 512;   // two workgroups of 4 wavefronts per CU
+hipError_t run_mfma_rate(int kind, int64_t iters, float* out, double* flops, hipStream_t s);
 
 // Host Philox4x32-10, used only to derive the sign diagonal from a seed (16 bits, or 32 for the MXFP4 mode).
 uint32_t host_rht_sign_mask(uint64_t seed);
