@@ -50,9 +50,11 @@ __device__ __forceinline__ half2v scale_h2(uint32_t e4m3_byte) {
   return r;
 }
 
-// One thread per 8 elements (one dword of codes -> 16 bytes of FP16): consecutive lanes read
-// consecutive dwords and write consecutive 16-byte pieces, so every load and store instruction of
-// a wavefront covers one contiguous span.  Both operands are decoded by one launch.
+// A thread decodes kDecodeUnroll x 8 elements (a dword of codes -> 16 bytes of FP16 each), the pieces 256 dwords
+// apart: consecutive lanes read consecutive dwords and write consecutive 16-byte pieces, so every load and store
+// instruction of a wavefront covers one contiguous span, and a thread has all its loads in flight before its first
+// store.  Both operands are decoded by one launch.
+constexpr int kDecodeUnroll = 4;
 __global__ __launch_bounds__(256) void decode_f16_kernel(const uint8_t* __restrict__ a_codes,
                                                          const uint8_t* __restrict__ a_scales, int64_t a_n8,
                                                          _Float16* __restrict__ a_out,
@@ -62,20 +64,27 @@ __global__ __launch_bounds__(256) void decode_f16_kernel(const uint8_t* __restri
                                                          unsigned int* __restrict__ tickets) {
   // The split-K tickets of the GEMM launches that follow start at zero (256 of them at most).
   if (blockIdx.x == 0 && tickets) tickets[threadIdx.x] = 0u;
-  int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
-  const uint8_t* codes = a_codes;
-  const uint8_t* scales = a_scales;
-  _Float16* out = a_out;
-  if (i >= a_n8) {
-    i -= a_n8;
-    if (i >= b_n8) return;
-    codes = b_codes;
-    scales = b_scales;
-    out = b_out;
+  const int64_t base = static_cast<int64_t>(blockIdx.x) * (256 * kDecodeUnroll) + threadIdx.x;
+  uint32_t c[kDecodeUnroll];
+  uint32_t sc[kDecodeUnroll];
+  uint4* dst[kDecodeUnroll];
+#pragma unroll
+  for (int u = 0; u < kDecodeUnroll; ++u) {
+    int64_t i = base + u * 256;
+    const bool in_a = i < a_n8;
+    if (!in_a) i -= a_n8;
+    dst[u] = nullptr;
+    c[u] = 0u;
+    sc[u] = 0u;
+    if (in_a || i < b_n8) {
+      c[u] = reinterpret_cast<const uint32_t*>(in_a ? a_codes : b_codes)[i];
+      sc[u] = (in_a ? a_scales : b_scales)[i >> 1];
+      dst[u] = reinterpret_cast<uint4*>(in_a ? a_out : b_out) + i;
+    }
   }
-  const uint32_t c = reinterpret_cast<const uint32_t*>(codes)[i];
-  const half2v h = scale_h2(scales[i >> 1]);
-  reinterpret_cast<uint4*>(out)[i] = dec8(c, h);
+#pragma unroll
+  for (int u = 0; u < kDecodeUnroll; ++u)
+    if (dst[u]) *dst[u] = dec8(c[u], scale_h2(sc[u]));
 }
 
 // ---------------------------------------------------------------- pass 2: FP16 GEMM
@@ -387,7 +396,7 @@ hipError_t launch_gemm_two_pass(const GemmArgs& g, hipStream_t s) {
   unsigned int* tickets = reinterpret_cast<unsigned int*>(ws + operand_bytes(M, N, K));
   float* partials = reinterpret_cast<float*>(ws + operand_bytes(M, N, K) + kTicketBytes);
   const int64_t na = M * K / 8, nb = N * K / 8;   // a_n8 is a multiple of 256 only if M*K is a multiple of 2048; the kernel does not need it
-  hipLaunchKernelGGL(decode_f16_kernel, dim3(static_cast<unsigned>((na + nb + 255) / 256)), dim3(256), 0, s, g.a.codes,
+  hipLaunchKernelGGL(decode_f16_kernel, dim3(static_cast<unsigned>((na + nb + 256 * kDecodeUnroll - 1) / (256 * kDecodeUnroll))), dim3(256), 0, s, g.a.codes,
                      g.a.scales, na, a16, g.b.codes, g.b.scales, nb, b16, tickets);
   const int tiles_m = static_cast<int>((M + TM - 1) / TM), tiles_n = static_cast<int>((N + TN - 1) / TN);
   const int tiles = tiles_m * tiles_n;
