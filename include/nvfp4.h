@@ -18,7 +18,8 @@
  *     an error has enqueued nothing.
  *   - Return value: NVFP4_OK (0) or a negative nvfp4_status.
  *   - Data-dependent trouble never aborts: a tensor containing Inf/NaN yields
- *     amax = Inf/NaN in tensor_scale[1] and unspecified codes.
+ *     amax = Inf/NaN in tensor_scale[1] of every copy written (rotated or not;
+ *     NVFP4 formats) and unspecified codes.
  *   - No global state; calls on different streams with disjoint buffers are
  *     independent.
  *
@@ -155,7 +156,7 @@ int nvfp4_quantize(const void* x, int64_t rows, int64_t cols, int64_t ld, int la
  * between the two calls) runs only what it needs.  NVFP4 only (MXFP4 has no tensor-level scale).
  *
  * nvfp4_amax: pass 1.  amax_out is device memory, float[2]: { max |x|, max |rotated x| } (the second is 0 without
- * rht_on_col; it is what Eq. 1 uses for a rotated col copy, App. C).  rht_on_col, rht_seed, workspace as in
+ * rht_on_col, or non-finite like the first for a tensor holding Inf/NaN; it is what Eq. 1 uses for a rotated col copy, App. C).  rht_on_col, rht_seed, workspace as in
  * nvfp4_quantize (same workspace size).
  *
  * nvfp4_quantize_with_amax: pass 2.  amax_in is device memory, float[2] laid out as nvfp4_amax writes it, read by the

@@ -27,7 +27,10 @@ namespace nvfp4 {
 // Every workgroup writes its own maxima (raw tensor / rotated tensor) into its
 // slot of the workspace; a one-workgroup kernel folds the slots.  No atomics:
 // thousands of same-address atomics serialise in L2 and cost more than the pass.
-template <bool kRaw, int kRht>   // kRht: 0, or the rotation size 2, 4 or 16 (sign_mask: the d signs repeated over 16 bits)
+// The raw maximum is always taken, also when only a rotated copy is asked for: it is the one place where a NaN in
+// the input shows (the floating-point maxima of the rotated values skip NaNs), and amax_finalize_kernel carries a
+// non-finite raw maximum over into the rotated one.
+template <int kRht>   // kRht: 0, or the rotation size 2, 4 or 16 (sign_mask: the d signs repeated over 16 bits)
 __global__ __launch_bounds__(kThreads) void amax_kernel(const uint16_t* __restrict__ x, int64_t rows,
                                                         int64_t cols, int64_t ld, uint32_t sign_mask,
                                                         uint32_t* __restrict__ ws) {
@@ -42,7 +45,7 @@ __global__ __launch_bounds__(kThreads) void amax_kernel(const uint16_t* __restri
     if (col0 < cols && group * 16 < rows) {
       Patch p;
       load_patch(x, ld, group * 16, col0, p);
-      if (kRaw) m_raw = max(m_raw, patch_amax_bits(p));
+      m_raw = max(m_raw, patch_amax_bits(p));
       if (kRht) {
         // The normalisation is applied once to the maximum: rounding is monotone, so
         // max_i fl(c v_i) = fl(c max_i v_i).
@@ -58,7 +61,7 @@ __global__ __launch_bounds__(kThreads) void amax_kernel(const uint16_t* __restri
       }
     }
   }
-  if (kRaw) m_raw = wave_max_u32(m_raw);
+  m_raw = wave_max_u32(m_raw);
   if (kRht) m_rot = wave_max_u32(__float_as_uint(rht_norm<kRht>() * f_rot));
   if (lane == 0) {
     red[0][wave] = m_raw;
@@ -200,7 +203,7 @@ template <bool kRow, int kRht>
 static void launch_rotated(const QuantizeArgs& a, dim3 grid, hipStream_t s) {
   const uint16_t* x = static_cast<const uint16_t*>(a.x);
   if (a.do_amax) {
-    hipLaunchKernelGGL((amax_kernel<kRow, kRht>), grid, dim3(kThreads), 0, s, x, a.rows, a.cols, a.ld, a.sign_mask, a.ws);
+    hipLaunchKernelGGL((amax_kernel<kRht>), grid, dim3(kThreads), 0, s, x, a.rows, a.cols, a.ld, a.sign_mask, a.ws);
     hipLaunchKernelGGL(amax_finalize_kernel, dim3(1), dim3(1024), 0, s, a.ws, grid.x * grid.y, a.amax_copy);
   }
   if (a.do_cast) dispatch_cast2<kRow, true, kRht>(a, grid, s);
@@ -226,7 +229,7 @@ hipError_t launch_quantize(const QuantizeArgs& a, hipStream_t s) {
     return hipGetLastError();
   }
   if (a.do_amax) {
-    hipLaunchKernelGGL((amax_kernel<true, 0>), grid, dim3(kThreads), 0, s, static_cast<const uint16_t*>(a.x), a.rows, a.cols,
+    hipLaunchKernelGGL((amax_kernel<0>), grid, dim3(kThreads), 0, s, static_cast<const uint16_t*>(a.x), a.rows, a.cols,
                        a.ld, a.sign_mask, a.ws);
     hipLaunchKernelGGL(amax_finalize_kernel, dim3(1), dim3(1024), 0, s, a.ws, grid.x * grid.y, a.amax_copy);
   }

@@ -55,7 +55,7 @@ __device__ __forceinline__ void rotated_row(const uint4& q, const uint32_t sgn[4
 
 // ---------------------------------------------------------------- pass 1: amax (App. B.1) of up to three spaces
 // ws slots per workgroup: raw maxima, col-rotated maxima, row-rotated maxima (three runs of nwg words).
-template <bool kRaw, int kColRht>   // kColRht: 0 or 16
+template <int kColRht>   // kColRht: 0 or 16
 __global__ __launch_bounds__(kThreads) void amax_rowrot_kernel(const uint16_t* __restrict__ x, int64_t rows, int64_t cols,
                                                                int64_t ld, uint32_t sign_mask, uint32_t* __restrict__ ws) {
   __shared__ uint32_t red[3][4];
@@ -72,7 +72,7 @@ __global__ __launch_bounds__(kThreads) void amax_rowrot_kernel(const uint16_t* _
     if (col0 < cols && group * 16 < rows) {
       Patch p;
       load_patch(x, ld, group * 16, col0, p);
-      if (kRaw) m_raw = max(m_raw, patch_amax_bits(p));
+      m_raw = max(m_raw, patch_amax_bits(p));   // always: a NaN in the input shows here only
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         float v[8];
@@ -125,8 +125,13 @@ __global__ __launch_bounds__(1024) void amax_finalize3_kernel(uint32_t* __restri
   }
   __syncthreads();
   if (threadIdx.x < 3) {
-    uint32_t f = 0;
-    for (int i = 0; i < 16; ++i) f = max(f, red[threadIdx.x][i]);
+    uint32_t f = 0, raw = 0;
+    for (int i = 0; i < 16; ++i) {
+      f = max(f, red[threadIdx.x][i]);
+      raw = max(raw, red[0][i]);
+    }
+    // a non-finite input shows in every copy's amax (the maxima of rotated values skip NaNs)
+    if (raw >= 0x7F800000u) f = max(f, raw);
     ws[threadIdx.x] = f;
   }
 }
@@ -246,11 +251,7 @@ __global__ __launch_bounds__(kThreads, 2) void cast_rowrot_kernel(
 template <bool kCol, int kColRht>
 void launch_both(const QuantizeArgs& a, dim3 grid, hipStream_t s) {
   const uint16_t* x = static_cast<const uint16_t*>(a.x);
-  // the raw amax is needed only by an unrotated col copy
-  if (kCol && !kColRht)
-    hipLaunchKernelGGL((amax_rowrot_kernel<true, 0>), grid, dim3(kThreads), 0, s, x, a.rows, a.cols, a.ld, a.sign_mask, a.ws);
-  else
-    hipLaunchKernelGGL((amax_rowrot_kernel<false, kColRht>), grid, dim3(kThreads), 0, s, x, a.rows, a.cols, a.ld, a.sign_mask, a.ws);
+  hipLaunchKernelGGL((amax_rowrot_kernel<kColRht>), grid, dim3(kThreads), 0, s, x, a.rows, a.cols, a.ld, a.sign_mask, a.ws);
   hipLaunchKernelGGL(amax_finalize3_kernel, dim3(1), dim3(1024), 0, s, a.ws, grid.x * grid.y);
   if (a.sr)
     hipLaunchKernelGGL((cast_rowrot_kernel<kCol, kColRht, true>), grid, dim3(kThreads), 0, s, x, a.rows, a.cols, a.ld, a.ws,

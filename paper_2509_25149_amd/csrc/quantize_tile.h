@@ -167,8 +167,13 @@ static __global__ __launch_bounds__(1024) void amax_finalize_kernel(uint32_t* __
   }
   __syncthreads();
   if (threadIdx.x < 2) {
-    uint32_t m = 0;
-    for (int i = 0; i < 16; ++i) m = max(m, red[threadIdx.x][i]);
+    uint32_t m = 0, raw = 0;
+    for (int i = 0; i < 16; ++i) {
+      m = max(m, red[threadIdx.x][i]);
+      raw = max(raw, red[0][i]);
+    }
+    // a non-finite input shows in the rotated amax too (the maxima of rotated values skip NaNs)
+    if (raw >= 0x7F800000u) m = max(m, raw);
     ws[threadIdx.x] = m;
     if (copy) copy[threadIdx.x] = m;
   }

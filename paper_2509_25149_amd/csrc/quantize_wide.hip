@@ -63,7 +63,7 @@ __device__ __forceinline__ uint32_t group_signs(uint4 sign_words, int64_t group)
 }
 
 // ---------------------------------------------------------------- pass 1: amax (App. B.1), raw and rotated
-template <bool kRaw, int kD>
+template <int kD>
 __global__ __launch_bounds__(kWideThreads) void amax_wide_kernel(const uint16_t* __restrict__ x, int64_t rows, int64_t cols,
                                                                  int64_t ld, uint4 sign_words, uint32_t* __restrict__ ws) {
   __shared__ float xch[8 * 16 * 64];
@@ -82,8 +82,7 @@ __global__ __launch_bounds__(kWideThreads) void amax_wide_kernel(const uint16_t*
 #pragma unroll
     for (int r = 0; r < 16; ++r) p.raw[r] = make_uint4(0u, 0u, 0u, 0u);
   }
-  uint32_t m_raw = 0;
-  if (kRaw) m_raw = wave_max_u32(patch_amax_bits(p));
+  const uint32_t m_raw = wave_max_u32(patch_amax_bits(p));   // always: see amax_kernel
 
   const uint32_t signs = group_signs<kD>(sign_words, group);
   float f_rot = 0.0f;
@@ -211,7 +210,7 @@ void launch_wide(const QuantizeArgs& a, dim3 grid, hipStream_t s) {
   const uint16_t* x = static_cast<const uint16_t*>(a.x);
   const uint4 signs = make_uint4(a.sign_words[0], a.sign_words[1], a.sign_words[2], a.sign_words[3]);
   if (a.do_amax) {
-    hipLaunchKernelGGL((amax_wide_kernel<kRow, kD>), grid, dim3(kWideThreads), 0, s, x, a.rows, a.cols, a.ld, signs, a.ws);
+    hipLaunchKernelGGL((amax_wide_kernel<kD>), grid, dim3(kWideThreads), 0, s, x, a.rows, a.cols, a.ld, signs, a.ws);
     hipLaunchKernelGGL(amax_finalize_kernel, dim3(1), dim3(1024), 0, s, a.ws, grid.x * grid.y, a.amax_copy);
   }
   if (!a.do_cast) return;

@@ -134,6 +134,31 @@ def test_nonfinite_input_is_flagged_in_amax():
     assert not np.isfinite(q.row_ts.cpu().numpy()[1])
 
 
+@pytest.mark.parametrize("bad", [np.inf, -np.inf, np.nan])
+def test_nonfinite_input_is_flagged_in_every_copy(bad):
+    # the maxima of rotated values skip NaNs, so the raw maximum is what carries a NaN into a rotated copy's amax
+    x = synth.bf16_bits_to_f32(synth.normal(256, 48, 1.0, 6))
+    x[131, 17] = bad
+    xd = to_dev(synth.f32_to_bf16_bits(x))
+    for d in (2, 4, 16, 32, 128):
+        q = nv.nvfp4_quantize(xd, nv.LAYOUT_COL, rht_on_col=d, rht_seed=3)            # a rotated copy alone
+        assert not np.isfinite(q.col_ts.cpu().numpy()[1]), d
+        q = nv.nvfp4_quantize(xd, nv.LAYOUT_ROW | nv.LAYOUT_COL, rht_on_col=d, rht_seed=3)
+        assert not np.isfinite(q.col_ts.cpu().numpy()[1]) and not np.isfinite(q.row_ts.cpu().numpy()[1]), d
+    for col in (0, 16):
+        q = nv.nvfp4_quantize(xd, nv.LAYOUT_ROW | nv.LAYOUT_COL | nv.LAYOUT_ROW_RHT, rht_on_col=col, rht_seed=3)
+        assert not np.isfinite(q.col_ts.cpu().numpy()[1]) and not np.isfinite(q.row_ts.cpu().numpy()[1]), col
+    q = nv.nvfp4_quantize(xd, nv.LAYOUT_ROW | nv.LAYOUT_ROW_RHT, rht_seed=3)
+    assert not np.isfinite(q.row_ts.cpu().numpy()[1])
+    q = nv.nvfp4_quantize(xd, nv.LAYOUT_ROW | nv.LAYOUT_COL, nv.BLOCK_16x16)
+    assert not np.isfinite(q.col_ts.cpu().numpy()[1]) and not np.isfinite(q.row_ts.cpu().numpy()[1])
+    amax = nv.nvfp4_amax(xd, 16, 3).cpu().numpy()
+    assert not np.isfinite(amax[0]) and not np.isfinite(amax[1])
+    # and a finite tensor is not flagged
+    q = nv.nvfp4_quantize(to_dev(synth.normal(256, 48, 1.0, 6)), nv.LAYOUT_COL, rht_on_col=16, rht_seed=3)
+    assert np.isfinite(q.col_ts.cpu().numpy()[1])
+
+
 def test_two_d_weight_copies_are_transposes():
     wb = synth.normal(96, 160, 0.02, 8)
     q, _ = check_quantize(wb, nv.LAYOUT_ROW | nv.LAYOUT_COL, nv.BLOCK_16x16)
