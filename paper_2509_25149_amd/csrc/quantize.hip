@@ -216,7 +216,6 @@ hipError_t launch_quantize(const QuantizeArgs& a, hipStream_t s) {
   if (a.row_rht) return launch_quantize_rowrot(a, s);
   if (rht > 16) return launch_quantize_wide(a, s);
   if (rht) {
-    // the raw amax is only needed when the (never rotated) row copy is asked for as well
     if (a.want_row) {
       if (rht == 16) launch_rotated<true, 16>(a, grid, s);
       else if (rht == 4) launch_rotated<true, 4>(a, grid, s);
