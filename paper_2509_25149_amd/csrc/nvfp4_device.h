@@ -170,6 +170,17 @@ __device__ __forceinline__ void rht16_inverse(float v[16], uint32_t sign_mask) {
     v[i] = __uint_as_float(__float_as_uint(v[i]) ^ (((sign_mask >> i) & 1u) << 31));
 }
 
+// Value held by lane ^ 1 / lane ^ 2, through a DPP quad permutation (one VALU operation; the shuffle intrinsic goes
+// through the LDS crossbar and has to be waited for).  All four lanes of a quad must be active.
+__device__ __forceinline__ uint32_t lane_xor1(uint32_t v) {
+  return static_cast<uint32_t>(__builtin_amdgcn_mov_dpp(static_cast<int>(v), 0xB1, 0xF, 0xF, true));   // quad_perm [1, 0, 3, 2]
+}
+__device__ __forceinline__ uint32_t lane_xor2(uint32_t v) {
+  return static_cast<uint32_t>(__builtin_amdgcn_mov_dpp(static_cast<int>(v), 0x4E, 0xF, 0xF, true));   // quad_perm [2, 3, 0, 1]
+}
+__device__ __forceinline__ float lane_xor1(float v) { return __uint_as_float(lane_xor1(__float_as_uint(v))); }
+__device__ __forceinline__ float lane_xor2(float v) { return __uint_as_float(lane_xor2(__float_as_uint(v))); }
+
 __device__ __forceinline__ float wave_max(float v) {
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));

@@ -138,7 +138,7 @@ __global__ __launch_bounds__(kThreads, 2) void cast_kernel(
     uint32_t tile_code = 0;
     if (k2D) {
       uint32_t m = patch_amax_bits(p);
-      m = max(m, static_cast<uint32_t>(__shfl_xor(static_cast<int>(m), 1, 64)));
+      m = max(m, lane_xor1(m));
       tile_code = e4m3_encode(div_by_6(__uint_as_float(m)) * s_enc_r);   // Eq. 2-3
       s_enc_tile = lut_row[tile_code];
     }

@@ -110,8 +110,8 @@ __global__ __launch_bounds__(kThreads) void quantize_mx_kernel(const uint16_t* _
       float m = 0.0f;
 #pragma unroll
       for (int c = 0; c < 8; ++c) m = fmaxf(m, fabsf(v[c]));
-      m = fmaxf(m, __shfl_xor(m, 1, 64));   // a 32-column block is four neighbouring lanes
-      m = fmaxf(m, __shfl_xor(m, 2, 64));
+      m = fmaxf(m, lane_xor1(m));   // a 32-column block is four neighbouring lanes
+      m = fmaxf(m, lane_xor2(m));
       float inv;
       const uint32_t sc = ue8m0_scale(m, inv);
 #pragma unroll

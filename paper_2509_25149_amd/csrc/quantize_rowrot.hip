@@ -14,11 +14,6 @@ namespace nvfp4 {
 
 namespace {
 
-// value of lane ^ 1 (quad_perm [1, 0, 3, 2])
-__device__ __forceinline__ float neighbour(float v) {
-  return __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(v), 0xB1, 0xF, 0xF, true));
-}
-
 // XOR words that apply the sign diagonal to the four packed bf16 pairs of a lane's eight columns: the lane holds
 // columns 0..7 (even lane) or 8..15 (odd lane) of its group of 16.
 __device__ __forceinline__ void lane_sign_words(uint32_t sign_mask, int lane, uint32_t sgn[4]) {
@@ -48,7 +43,7 @@ __device__ __forceinline__ void rotated_row(const uint4& q, const uint32_t sgn[4
   }
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
-    const float o = neighbour(v[i]);
+    const float o = lane_xor1(v[i]);
     v[i] = odd ? o - v[i] : v[i] + o;
   }
 }
@@ -152,7 +147,7 @@ __device__ __forceinline__ void row_pass_rotated(const Patch& p, const uint32_t 
       v[c] *= 0.25f;
       m = fmaxf(m, fabsf(v[c]));
     }
-    m = fmaxf(m, neighbour(m));
+    m = fmaxf(m, lane_xor1(m));
     const uint32_t code = e4m3_encode(div_by_6(m) * s_enc_r);          // Eq. 2-3
     const float s_enc_b = lut_row[code];
 #pragma unroll

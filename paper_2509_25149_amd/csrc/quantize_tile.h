@@ -200,7 +200,7 @@ __device__ __forceinline__ void row_pass(const Patch& p, const uint32_t (&rnd)[1
       float m = 0.0f;
 #pragma unroll
       for (int c = 0; c < 8; ++c) m = fmaxf(m, fabsf(v[c]));
-      m = fmaxf(m, __shfl_xor(m, 1, 64));
+      m = fmaxf(m, lane_xor1(m));
       code = e4m3_encode(div_by_6(m) * s_enc_r);                        // Eq. 2-3
       s_enc_b = lut_row[code];
     }
