@@ -20,8 +20,10 @@
  *   - Data-dependent trouble never aborts: a tensor containing Inf/NaN yields
  *     amax = Inf/NaN in tensor_scale[1] of every copy written (rotated or not;
  *     NVFP4 formats) and unspecified codes.
- *   - No global state; calls on different streams with disjoint buffers are
- *     independent.
+ *   - Calls on different streams with disjoint buffers are independent, from
+ *     any host thread.  The only state the library keeps is a per-device note
+ *     that a kernel's shared-memory limit has been raised (set on the first
+ *     launch of that kernel on the device; idempotent).
  *
  * Storage format (the paper fixes the number formats, not the layout)
  *   - E2M1 code: bit 3 sign, bits 2..0 index into {0, .5, 1, 1.5, 2, 3, 4, 6}
@@ -181,8 +183,10 @@ int nvfp4_quantize_with_amax(const void* x, int64_t rows, int64_t cols, int64_t 
  * For every op the two copies it reads must agree on rotation size and seed
  * (col_has_rht / row_has_rht of the copy read; App. C: the two rotations cancel
  * in the product only if they are the same), else NVFP4_ERR_MISMATCH.
- * D is device memory, [M, N] row-major with leading dimension ldd (a multiple
- * of 4), FP32 or bf16 (bf16 = round-to-nearest-even of the FP32 result).  With
+ * D is device memory, 16-byte aligned, [M, N] row-major with leading dimension
+ * ldd -- a multiple of 4 elements for FP32 and of 8 for bf16 (results leave in
+ * 16-byte pieces), else NVFP4_ERR_BAD_SHAPE -- FP32 or bf16 (bf16 =
+ * round-to-nearest-even of the FP32 result).  With
  * NVFP4_OUT_F32_ACCUMULATE, D is FP32 and is read: every element becomes
  * fp32(D_old + result), one FP32 addition after the FP32 result is formed.
  * workspace: optional device scratch, 256-byte aligned.  With at least
@@ -260,21 +264,6 @@ uint32_t nvfp4_rht_sign_mask(uint64_t rht_seed);
  * Asynchronous like every other call.
  */
 int nvfp4_selftest_conversions(uint64_t* mismatches, nvfp4_stream_t stream);
-
-/*
- * Matrix-pipe rate probe (measurement aid, not a step of the method; Sec. 2 "Hardware support" quotes FP4 math
- * rates as multiples of the 16-bit rate, and the two-pass GEMM here runs on the FP16 matrix instruction): launches
- * a register-only loop of that instruction, v_mfma_f32_16x16x32_f16, on NVFP4_MFMA_PROBE_WORKGROUPS workgroups of
- * 256 threads -- no memory or LDS traffic -- so that timing the call gives the rate the chip sustains under its
- * power limit for operands of the given kind: 0 = all ones, 1 = uniform random FP16 in [-2, 2), 2 = products of an
- * E2M1 value and an E4M3 scale (what the NVFP4 GEMM multiplies).
- *   iters  loop trips, 1 .. 2^24 (16 MFMAs per wavefront and trip)
- *   out    device, float[NVFP4_MFMA_PROBE_WORKGROUPS * 256], receives one checksum per thread
- *   flops  host, receives the flop count of the launch (2 * 16 * 16 * 32 per MFMA)
- * Asynchronous; the caller times it.
- */
-enum { NVFP4_MFMA_PROBE_WORKGROUPS = 512 };
-int nvfp4_selftest_mfma_rate(int operand_kind, int64_t iters, float* out, double* flops, nvfp4_stream_t stream);
 
 const char* nvfp4_status_string(int status);
 int nvfp4_version(void);

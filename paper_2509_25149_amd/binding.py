@@ -27,8 +27,7 @@ COPY_ROW, COPY_COL = 0, 1
 EXPORTS = ["nvfp4_quantized_sizes", "nvfp4_quantize", "nvfp4_gemm", "nvfp4_gemm_workspace_bytes", "nvfp4_dequantize",
            "nvfp4_rht_sign_mask", "nvfp4_selftest_conversions", "nvfp4_status_string", "nvfp4_version",
            "nvfp4_linear_workspace_bytes", "nvfp4_linear_forward", "nvfp4_linear_backward",
-           "nvfp4_amax", "nvfp4_quantize_with_amax", "nvfp4_selftest_mfma_rate"]
-MFMA_PROBE_WORKGROUPS = 512
+           "nvfp4_amax", "nvfp4_quantize_with_amax"]
 
 
 class QTensorStruct(ctypes.Structure):
@@ -83,8 +82,6 @@ def load_library() -> ctypes.CDLL:
         L.nvfp4_rht_sign_mask.argtypes = [u64]
         L.nvfp4_selftest_conversions.restype = ci
         L.nvfp4_selftest_conversions.argtypes = [vp, vp]
-        L.nvfp4_selftest_mfma_rate.restype = ci
-        L.nvfp4_selftest_mfma_rate.argtypes = [ci, i64, vp, ctypes.POINTER(ctypes.c_double), vp]
         L.nvfp4_status_string.restype = ctypes.c_char_p
         L.nvfp4_status_string.argtypes = [ci]
         L.nvfp4_version.restype = ci
@@ -301,15 +298,3 @@ def nvfp4_selftest_conversions() -> list:
     _check(load_library().nvfp4_selftest_conversions(counts.data_ptr(), _stream()))
     torch.cuda.synchronize()
     return [int(v) for v in counts.cpu()]
-
-
-def nvfp4_selftest_mfma_rate(operand_kind: int, iters: int, out: Optional[torch.Tensor] = None) -> float:
-    """Enqueues the register-only MFMA loop (operand_kind 0 ones, 1 random FP16, 2 NVFP4-like); returns its flop
-    count.  The caller times it."""
-    if out is None:
-        out = torch.empty(MFMA_PROBE_WORKGROUPS * 256, dtype=torch.float32, device="cuda")
-    if not out.is_cuda or out.dtype != torch.float32 or out.numel() < MFMA_PROBE_WORKGROUPS * 256 or not out.is_contiguous():
-        raise ValueError("out must be a contiguous float32 CUDA tensor of MFMA_PROBE_WORKGROUPS * 256 elements")
-    flops = ctypes.c_double(0.0)
-    _check(load_library().nvfp4_selftest_mfma_rate(operand_kind, iters, out.data_ptr(), ctypes.byref(flops), _stream()))
-    return flops.value

@@ -71,5 +71,23 @@ def kernel_resources(compiler_output: str) -> dict:
     return out
 
 
+PROBE_SRC = os.path.join(ROOT, "bench_probe.hip")
+PROBE_LIB = os.path.join(ROOT, "libbench_probe.so")
+
+
+def build_bench_probe() -> str:
+    """bench.py's measurement aids (a register-only MFMA loop, a plain copy kernel): a library of their own beside
+    bench.py, not part of libnvfp4_hip.so."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           "-fPIC", "-shared", "-o", PROBE_LIB, PROBE_SRC]
+    res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if res.returncode != 0:
+        print(res.stdout)
+        raise RuntimeError("hipcc failed building libbench_probe.so")
+    return PROBE_LIB
+
+
 if __name__ == "__main__":
     print(build_library(verbose=True))
+    print(build_bench_probe())

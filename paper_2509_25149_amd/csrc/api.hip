@@ -292,7 +292,7 @@ static int plan_gemm(const nvfp4_qtensor* a, const nvfp4_qtensor* b, int op, voi
   const int a_rot = a_col ? a->col_has_rht : a->row_has_rht, b_rot = b_col ? b->col_has_rht : b->row_has_rht;   // rotation sizes
   if (a_rot != b_rot || (a_rot && a->rht_seed != b->rht_seed)) return NVFP4_ERR_MISMATCH;
   if (ka <= 0 || ka % 16 || g.a.outer <= 0 || g.b.outer <= 0) return NVFP4_ERR_BAD_SHAPE;
-  if (ldd < g.b.outer || ldd % 4) return NVFP4_ERR_BAD_SHAPE;
+  if (ldd < g.b.outer || ldd % (out_dtype == NVFP4_OUT_BF16 ? 8 : 4)) return NVFP4_ERR_BAD_SHAPE;   // 16-byte output pieces
   if (!aligned(d, 16) || !aligned(g.a.codes, 8) || !aligned(g.b.codes, 8)) return NVFP4_ERR_INVALID_ARG;
   g.K = ka;
   g.d = d;
@@ -395,12 +395,6 @@ int nvfp4_dequantize(const nvfp4_qtensor* q, int which_copy, int undo_rht, void*
 int nvfp4_selftest_conversions(uint64_t* mismatches, nvfp4_stream_t stream) {
   if (!mismatches || !aligned(mismatches, 8)) return NVFP4_ERR_INVALID_ARG;
   return run_selftest(mismatches, static_cast<hipStream_t>(stream)) == hipSuccess ? NVFP4_OK : NVFP4_ERR_HIP;
-}
-
-int nvfp4_selftest_mfma_rate(int operand_kind, int64_t iters, float* out, double* flops, nvfp4_stream_t stream) {
-  if (!out || !flops || !aligned(out, 4)) return NVFP4_ERR_INVALID_ARG;
-  if (operand_kind < 0 || operand_kind > 2 || iters <= 0 || iters > (1ll << 24)) return NVFP4_ERR_INVALID_ARG;
-  return run_mfma_rate(operand_kind, iters, out, flops, static_cast<hipStream_t>(stream)) == hipSuccess ? NVFP4_OK : NVFP4_ERR_HIP;
 }
 
 }  // extern "C"

@@ -349,16 +349,10 @@ hipError_t launch_gemm(const GemmArgs& g, hipStream_t s) {
   const bool big = (g.K % TK == 0) && (reinterpret_cast<uintptr_t>(g.a.codes) % 16 == 0) &&
                    (reinterpret_cast<uintptr_t>(g.b.codes) % 16 == 0);
   if (big) {
-    static bool attr_set = false;
-    if (!attr_set) {
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel_256<true>),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, 2 * kStageBytes);
-      if (e == hipSuccess)
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel_256<false>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, 2 * kStageBytes);
-      if (e != hipSuccess) return e;
-      attr_set = true;
-    }
+    static PerDeviceOnce once_bf16, once_f32;
+    const hipError_t e = g.out_bf16 ? ensure_dynamic_lds(reinterpret_cast<const void*>(&gemm_kernel_256<true>), 2 * kStageBytes, once_bf16)
+                                    : ensure_dynamic_lds(reinterpret_cast<const void*>(&gemm_kernel_256<false>), 2 * kStageBytes, once_f32);
+    if (e != hipSuccess) return e;
     const int tiles_m = static_cast<int>((g.a.outer + TM - 1) / TM), tiles_n = static_cast<int>((g.b.outer + TN - 1) / TN);
     const dim3 grid(static_cast<unsigned>(tiles_m * tiles_n));
     if (g.out_bf16)

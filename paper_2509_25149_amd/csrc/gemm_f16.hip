@@ -367,13 +367,9 @@ bool gemm_two_pass_usable(const GemmArgs& g) {
 
 #define NVFP4_LAUNCH_F16(BF16)                                                                                    \
   do {                                                                                                            \
-    static bool attr_set = false;                                                                                 \
-    if (!attr_set) {                                                                                              \
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_f16_kernel<BF16>),                   \
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);            \
-      if (e != hipSuccess) return e;                                                                              \
-      attr_set = true;                                                                                            \
-    }                                                                                                             \
+    static PerDeviceOnce once;                                                                                    \
+    const hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(&gemm_f16_kernel<BF16>), kLdsBytes, once); \
+    if (e != hipSuccess) return e;                                                                                \
     hipLaunchKernelGGL((gemm_f16_kernel<BF16>), dim3(wgs), dim3(kThreads), kLdsBytes, s, a16, b16,                   \
                        g.a.outer, g.b.outer, g.K, g.a.ts, g.b.ts, g.d, g.ldd, g.accumulate, tiles_m, tiles_n,     \
                        tile_begin, tile_count, k_splits, partials, tickets);                                      \

@@ -413,13 +413,10 @@ __global__ __launch_bounds__(kThreads) void gemm_mx_kernel_k512(Operand A, Opera
 }  // namespace
 
 template <class Kernel>
-static hipError_t launch_mx(Kernel kernel, bool& attr_set, int lds_bytes, const GemmArgs& g, dim3 grid, int tiles_m, int tiles_n,
+static hipError_t launch_mx(Kernel kernel, PerDeviceOnce& once, int lds_bytes, const GemmArgs& g, dim3 grid, int tiles_m, int tiles_n,
                             hipStream_t s) {
-  if (!attr_set) {   // once per kernel: more dynamic LDS than the default limit
-    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  const hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(kernel), lds_bytes, once);   // more dynamic LDS than the default limit
+  if (e != hipSuccess) return e;
   hipLaunchKernelGGL(kernel, grid, dim3(kThreads), lds_bytes, s, g.a, g.b, g.K, g.d, g.ldd, g.accumulate, tiles_m, tiles_n);
   return hipGetLastError();
 }
@@ -430,7 +427,7 @@ hipError_t launch_gemm_mx(const GemmArgs& g, hipStream_t s) {
   const dim3 grid(static_cast<unsigned>(tiles_m) * static_cast<unsigned>(tiles_n));
   // 16-byte pieces of scale rows need K / 32 to be a multiple of 16 and the scale arrays 16-byte aligned
   const bool wide = g.K % 512 == 0 && reinterpret_cast<uintptr_t>(g.a.scales) % 16 == 0 && reinterpret_cast<uintptr_t>(g.b.scales) % 16 == 0;
-  static bool set[4] = {false, false, false, false};
+  static PerDeviceOnce set[4];
   if (wide) {
     if (g.out_bf16) return launch_mx(gemm_mx_kernel_k512<true>, set[0], kWideLdsBytes, g, grid, tiles_m, tiles_n, s);
     return launch_mx(gemm_mx_kernel_k512<false>, set[1], kWideLdsBytes, g, grid, tiles_m, tiles_n, s);

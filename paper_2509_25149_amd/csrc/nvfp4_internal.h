@@ -4,7 +4,26 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 namespace nvfp4 {
+
+// Kernels that need more dynamic LDS than the default limit have it raised once per device (the attribute belongs to
+// the kernel on the current device).  One flag bit per device ordinal; setting the attribute again is harmless, so
+// two host threads racing through here at worst both set it.
+struct PerDeviceOnce {
+  std::atomic<uint64_t> done{0};
+};
+inline hipError_t ensure_dynamic_lds(const void* kernel, int bytes, PerDeviceOnce& once) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  const uint64_t bit = uint64_t{1} << (dev & 63);
+  if (dev < 64 && (once.done.load(std::memory_order_acquire) & bit)) return hipSuccess;
+  e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  if (e == hipSuccess && dev < 64) once.done.fetch_or(bit, std::memory_order_release);
+  return e;
+}
 
 struct QuantizeArgs {
   const void* x;
@@ -73,8 +92,6 @@ hipError_t launch_dequantize(const DequantArgs& d, hipStream_t s);
 hipError_t launch_dequantize_mx(const DequantArgs& d, hipStream_t s);   // scales are UE8M0 per 32
 
 hipError_t run_selftest(uint64_t* mismatches_dev, hipStream_t s);
-constexpr int kMfmaProbeWorkgroups = 512;   // two workgroups of 4 wavefronts per CU
-hipError_t run_mfma_rate(int kind, int64_t iters, float* out, double* flops, hipStream_t s);
 
 // Host Philox4x32-10, used only to derive the sign diagonal from a seed (16 bits, or 32 for the MXFP4 mode).
 uint32_t host_rht_sign_mask(uint64_t seed);

@@ -106,66 +106,7 @@ __global__ __launch_bounds__(256) void selftest_div6_kernel(unsigned long long* 
   if (local) atomicAdd(bad, local);
 }
 
-// ---------------------------------------------------------------- matrix-pipe rate probe
-// A register-only loop of the GEMM kernels' instruction (v_mfma_f32_16x16x32_f16): no memory or LDS traffic, 16
-// independent accumulators per wavefront so no result is waited for.  What it sustains is the matrix pipe's rate
-// under the board's power limit for operand values of the given kind -- the ceiling a GEMM with those operand
-// values has on this chip, to be read beside the published peak.
-typedef _Float16 probe_half8 __attribute__((ext_vector_type(8)));
-typedef float probe_float4 __attribute__((ext_vector_type(4)));
-
-__device__ __forceinline__ uint32_t probe_hash(uint32_t x) {
-  x ^= x >> 16; x *= 0x7FEB352Du; x ^= x >> 15; x *= 0x846CA68Bu; x ^= x >> 16;
-  return x;
-}
-
-// one FP16 operand value of kind 0 (constant 1), 1 (uniform in [-2, 2) with all mantissa bits in use) or
-// 2 (an E2M1 value times an E4M3 block scale, the values the NVFP4 GEMM multiplies)
-__device__ __forceinline__ _Float16 probe_value(int kind, uint32_t h) {
-  if (kind == 0) return static_cast<_Float16>(1.0f);
-  if (kind == 1) return static_cast<_Float16>((static_cast<float>(h >> 8) - 8388608.0f) * (1.0f / 4194304.0f));
-  const float grid[8] = {0.0f, 0.5f, 1.0f, 1.5f, 2.0f, 3.0f, 4.0f, 6.0f};
-  const float v = grid[h & 7], sc = e4m3_decode(40 + ((h >> 4) & 31));   // scales 2^-2 .. 2^1.9
-  return static_cast<_Float16>(((h >> 3) & 1) ? -v * sc : v * sc);
-}
-
-__global__ __launch_bounds__(256) void mfma_rate_kernel(int kind, long long iters, float* __restrict__ out) {
-  const uint32_t tid = blockIdx.x * 256 + threadIdx.x;
-  probe_half8 a[4], b[4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      a[i][e] = probe_value(kind, probe_hash(tid * 64 + i * 8 + e));
-      b[i][e] = probe_value(kind, probe_hash(tid * 64 + 32 + i * 8 + e));
-    }
-  probe_float4 acc[4][4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int j = 0; j < 4; ++j) acc[i][j] = probe_float4{0.0f, 0.0f, 0.0f, 0.0f};
-  for (long long it = 0; it < iters; ++it) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-      for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[i], b[j], acc[i][j], 0, 0, 0);
-  }
-  probe_float4 t = probe_float4{0.0f, 0.0f, 0.0f, 0.0f};
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int j = 0; j < 4; ++j) t += acc[i][j];
-  out[tid] = t[0] + t[1] + t[2] + t[3];
-}
-
 }  // namespace
-
-hipError_t run_mfma_rate(int kind, int64_t iters, float* out, double* flops, hipStream_t s) {
-  hipLaunchKernelGGL(mfma_rate_kernel, dim3(kMfmaProbeWorkgroups), dim3(256), 0, s, kind, static_cast<long long>(iters), out);
-  // per wavefront and iteration: 16 MFMAs of 2 * 16 * 16 * 32 flop
-  *flops = static_cast<double>(kMfmaProbeWorkgroups) * 4.0 * static_cast<double>(iters) * 16.0 * 16384.0;
-  return hipGetLastError();
-}
 
 hipError_t run_selftest(uint64_t* mismatches_dev, hipStream_t s) {
   unsigned long long* dev = reinterpret_cast<unsigned long long*>(mismatches_dev);

@@ -264,14 +264,3 @@ def test_no_kernel_keeps_arrays_in_scratch_memory():
         if any(k in name for k in ("quantize_mx_kernel", "cast_kernel", "amax_kernel", "cast_wide", "amax_wide", "decode_f16",
                                    "dequantize", "gemm_mx_kernel_k512")):
             assert r["ScratchSize"] == 0 and r["VGPRs Spill"] == 0, (name, r)
-
-
-def test_mfma_rate_probe_rejects_bad_arguments(lib):
-    flops = ctypes.c_double(0.0)
-    OUT = 0x50000
-    assert lib.nvfp4_selftest_mfma_rate(0, 10, None, ctypes.byref(flops), None) == -1
-    assert lib.nvfp4_selftest_mfma_rate(0, 10, OUT, None, None) == -1
-    assert lib.nvfp4_selftest_mfma_rate(3, 10, OUT, ctypes.byref(flops), None) == -1
-    assert lib.nvfp4_selftest_mfma_rate(-1, 10, OUT, ctypes.byref(flops), None) == -1
-    assert lib.nvfp4_selftest_mfma_rate(0, 0, OUT, ctypes.byref(flops), None) == -1
-    assert lib.nvfp4_selftest_mfma_rate(0, (1 << 24) + 1, OUT, ctypes.byref(flops), None) == -1
