@@ -73,6 +73,12 @@ def lib() -> ctypes.CDLL:
         L.orc_quantize.restype = ctypes.c_int
         L.orc_quantize.argtypes = [vp, i64, i64, i64, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                    ctypes.c_int, u64, u64, vp, vp, vp, vp]
+        L.orc_quantize_row_scales.restype = ctypes.c_int
+        L.orc_quantize_row_scales.argtypes = [vp, i64, i64, i64, ctypes.c_int, ctypes.c_int, ctypes.c_int, u64, u64, vp, vp, vp]
+        L.orc_dequantize_row_scales.restype = ctypes.c_int
+        L.orc_dequantize_row_scales.argtypes = [vp, vp, vp, i64, i64, ctypes.c_int, u64, vp]
+        L.orc_gemm_f64_row_scales.restype = ctypes.c_int
+        L.orc_gemm_f64_row_scales.argtypes = [vp, vp, vp, ctypes.c_int, vp, vp, vp, ctypes.c_int, i64, i64, i64, vp]
         L.orc_dequantize.restype = ctypes.c_int
         L.orc_dequantize.argtypes = [vp, vp, f32, i64, i64, ctypes.c_int, u64, vp]
         gemm_head = [vp, vp, f32, vp, vp, f32]
@@ -198,12 +204,14 @@ def num_threads() -> int:
 # ------------------------------------------------------------------ tensors
 
 class QCopy:
-    """One quantized copy: codes [outer, inner/2] u8, scales [outer, inner/16] u8."""
+    """One quantized copy: codes [outer, inner/2] u8, scales [outer, inner/16] u8.  s_dec and amax are binary32
+    scalars, or float32 arrays [outer] for a copy quantized with one tensor-level scale per row (per_row)."""
 
-    def __init__(self, codes, scales, s_dec, amax, outer, inner):
+    def __init__(self, codes, scales, s_dec, amax, outer, inner, per_row=False):
         self.codes, self.scales = codes, scales
         self.s_dec, self.amax = s_dec, amax
         self.outer, self.inner = outer, inner
+        self.per_row = per_row
 
 
 def quantize(x_bf16_bits: np.ndarray, copy: int, block_dim: int = BLOCK_1x16, rounding: int = RNE,
@@ -224,8 +232,36 @@ def quantize(x_bf16_bits: np.ndarray, copy: int, block_dim: int = BLOCK_1x16, ro
     return QCopy(codes, scales, np.float32(ts[0]), np.float32(ts[1]), outer, inner)
 
 
+def quantize_row_scales(x_bf16_bits: np.ndarray, copy: int, rounding: int = RNE, use_rht: bool = False,
+                        rht_seed: int = 0, sr_seed: int = 0, rht_dim: int = 16) -> QCopy:
+    """1x16 blocks with one FP32 tensor-level scale per row of the copy (per logical row for ROW, per logical
+    column for COL) instead of one per tensor (App. B.1, last sentence)."""
+    x = np.ascontiguousarray(x_bf16_bits, dtype=np.uint16)
+    rows, cols = x.shape
+    outer, inner = (cols, rows) if copy == COL else (rows, cols)
+    codes = np.zeros((outer, inner // 2), dtype=np.uint8)
+    scales = np.zeros((outer, inner // 16), dtype=np.uint8)
+    ts = np.zeros(2 * outer, dtype=np.float32)
+    rc = lib().orc_quantize_row_scales(_p(x), rows, cols, cols, copy, rounding, rht_dim if use_rht else 0, rht_seed,
+                                       sr_seed, _p(codes), _p(scales), _p(ts))
+    if rc != 0:
+        raise ValueError(f"orc_quantize_row_scales rejected its arguments (rc={rc})")
+    return QCopy(codes, scales, ts[:outer].copy(), ts[outer:].copy(), outer, inner, per_row=True)
+
+
+def _sdec_array(q: QCopy) -> np.ndarray:
+    return np.ascontiguousarray(q.s_dec, dtype=np.float32).reshape(-1)
+
+
 def dequantize(q: QCopy, undo_rht: bool = False, rht_seed: int = 0, rht_dim: int = 16) -> np.ndarray:
     out = np.zeros((q.outer, q.inner), dtype=np.float32)
+    if q.per_row:
+        sd = _sdec_array(q)
+        rc = lib().orc_dequantize_row_scales(_p(q.codes), _p(q.scales), _p(sd), q.outer, q.inner,
+                                             rht_dim if undo_rht else 0, rht_seed, _p(out))
+        if rc != 0:
+            raise ValueError("orc_dequantize_row_scales rejected its arguments")
+        return out
     rc = lib().orc_dequantize(_p(q.codes), _p(q.scales), float(q.s_dec), q.outer, q.inner,
                               rht_dim if undo_rht else 0, rht_seed, _p(out))
     if rc != 0:
@@ -242,7 +278,13 @@ def gemm_f64(a: QCopy, b: QCopy, d_prev=None) -> np.ndarray:
     """Eq. 5 on the dequantized operands in binary64.  With d_prev (the FP32 gradient buffer of Sec. 4.1's
     micro-batch accumulation) the result is d_prev + product, still in binary64."""
     out = np.zeros((a.outer, b.outer), dtype=np.float64)
-    rc = lib().orc_gemm_f64(*_gemm_head(a, b), a.outer, b.outer, a.inner, _p(out))
+    if a.per_row or b.per_row:
+        assert a.inner == b.inner, "operands must share K"
+        sa, sb = _sdec_array(a), _sdec_array(b)
+        rc = lib().orc_gemm_f64_row_scales(_p(a.codes), _p(a.scales), _p(sa), int(a.per_row), _p(b.codes), _p(b.scales),
+                                           _p(sb), int(b.per_row), a.outer, b.outer, a.inner, _p(out))
+    else:
+        rc = lib().orc_gemm_f64(*_gemm_head(a, b), a.outer, b.outer, a.inner, _p(out))
     assert rc == 0
     if d_prev is not None:
         assert d_prev.shape == out.shape and d_prev.dtype == np.float32

@@ -67,6 +67,19 @@
 //     dense form of the stored values, the transposition identity with the
 //     col copy, and the cancellation in Fprop and Dgrad.
 //
+//   * Tensor-level scale of finer granularity (App. B.1, last sentence: the
+//     global scale may span a row or a block of elements instead of the whole
+//     tensor, which saves the extra pass over memory).  The granularity taken
+//     here is the one Eq. 5 allows the GEMM to pull out of the sum over k: one
+//     FP32 scale per row of the copy's K-contiguous storage (per logical row
+//     for a row copy, per logical column for a col copy).  Eq. 1 is evaluated
+//     with that row's amax; Eq. 2-4 are unchanged.  Not combined with 16x16
+//     blocks: a weight tile's scale must serve both orientations (Sec. 4.3).
+//     Pinned (tests/test_oracle_row_scales.py) by a hand-worked two-row
+//     tensor, by the row-by-row identity with the per-tensor routine, by the
+//     0x7E scale of each row's amax block, by invariance of the codes under a
+//     power-of-two scaling of single rows, and by the GEMM's closed forms.
+//
 // PARITY PINS (tests/test_oracle_*.py): E2M1/E4M3 by brute force over the whole
 // code space; Philox by the published known-answer vectors; the transform by
 // the dense matrix form, orthogonality and the GEMM-invariance identity of
@@ -354,11 +367,14 @@ int      orc_num_threads(void) {
 // Outputs: codes [outer, inner/2] bytes, scales [outer, inner/16] bytes,
 // tensor_scale[0] = s_dec, tensor_scale[1] = amax (in the rotated space for a
 // rotated copy).  Returns 0, or -1 for bad arguments.
-int orc_quantize(const uint16_t* x, int64_t rows, int64_t cols, int64_t ld,
+// per_row: one tensor-level scale per row of the copy ([outer] of them) instead of one per tensor;
+// tensor_scale then receives s_dec[0 .. outer) followed by amax[0 .. outer).
+static int quantize_impl(const uint16_t* x, int64_t rows, int64_t cols, int64_t ld,
                  int copy, int block_dim, int rounding, int rht_dim,
-                 uint64_t rht_seed, uint64_t sr_seed, const float* amax_given,
+                 uint64_t rht_seed, uint64_t sr_seed, const float* amax_given, bool per_row,
                  uint8_t* codes, uint8_t* scales, float* tensor_scale) {
   if (!x || !codes || !scales || !tensor_scale) return -1;
+  if (per_row && (block_dim != 1 || amax_given)) return -1;
   if (rows < 0 || cols < 0 || ld < cols) return -1;
   if (copy != 0 && copy != 1) return -1;
   if (block_dim != 1 && block_dim != 16) return -1;
@@ -387,26 +403,49 @@ int orc_quantize(const uint16_t* x, int64_t rows, int64_t cols, int64_t ld,
   // App. B.1, Eq. 1: tensor-level scale from the global amax -- of this tensor, or one the caller supplies
   // (an amax known beforehand or reduced over the shards of a larger tensor saves the first of the two passes
   // over memory that App. B.1 counts; nothing else changes, values beyond it saturate as in Eq. 3-4).
-  float amax = 0.0f;
-  if (amax_given) {
-    amax = *amax_given;
-    if (!(amax >= 0.0f)) return -1;
+  // With per_row the same equation is evaluated once per row of the copy, with that row's amax (App. B.1, last
+  // sentence): s_enc_of[o], s_dec_of[o] are the scales row o is quantized with in either mode.
+  auto eq1 = [](float amax, float& s_enc, float& s_dec) {
+    if (amax == 0.0f) {
+      s_enc = 1.0f;                                  // all-zero tensor: any scale encodes it
+    } else {
+      s_enc = (6.0f * 448.0f) / amax;
+      if (std::isinf(s_enc)) s_enc = std::numeric_limits<float>::max();
+    }
+    s_dec = 1.0f / s_enc;
+  };
+  std::vector<float> s_enc_of(static_cast<size_t>(outer)), s_dec_of(static_cast<size_t>(outer));
+  if (!per_row) {
+    float amax = 0.0f;
+    if (amax_given) {
+      amax = *amax_given;
+      if (!(amax >= 0.0f)) return -1;
+    } else {
+      for (size_t t = 0; t < w.size(); ++t) {
+        const float a = std::fabs(w[t]);
+        if (a > amax) amax = a;
+      }
+    }
+    float s_enc, s_dec;
+    eq1(amax, s_enc, s_dec);
+    tensor_scale[0] = s_dec;
+    tensor_scale[1] = amax;
+    for (int64_t o = 0; o < outer; ++o) {
+      s_enc_of[o] = s_enc;
+      s_dec_of[o] = s_dec;
+    }
   } else {
-    for (size_t t = 0; t < w.size(); ++t) {
-      const float a = std::fabs(w[t]);
-      if (a > amax) amax = a;
+    for (int64_t o = 0; o < outer; ++o) {
+      float amax = 0.0f;
+      for (int64_t k = 0; k < inner; ++k) {
+        const float a = std::fabs(w[o * inner + k]);
+        if (a > amax) amax = a;
+      }
+      eq1(amax, s_enc_of[o], s_dec_of[o]);
+      tensor_scale[o] = s_dec_of[o];
+      tensor_scale[outer + o] = amax;
     }
   }
-  float s_enc, s_dec;
-  if (amax == 0.0f) {
-    s_enc = 1.0f;                                  // all-zero tensor: any scale encodes it
-  } else {
-    s_enc = (6.0f * 448.0f) / amax;
-    if (std::isinf(s_enc)) s_enc = std::numeric_limits<float>::max();
-  }
-  s_dec = 1.0f / s_enc;
-  tensor_scale[0] = s_dec;
-  tensor_scale[1] = amax;
 
   // App. B.2, Eq. 2-3: per-block decode scale, stored as E4M3.
   // For 16x16 blocks the amax runs over the tile and every 1x16 slice of the
@@ -436,6 +475,7 @@ int orc_quantize(const uint16_t* x, int64_t rows, int64_t cols, int64_t ld,
 
 #pragma omp parallel for schedule(static)
   for (int64_t o = 0; o < outer; ++o) {
+    const float s_enc = s_enc_of[o], s_dec = s_dec_of[o];
     for (int64_t b = 0; b < nblk; ++b) {
       const float s_dec_b = blk_amax[o * nblk + b] / 6.0f;          // Eq. 2
       const uint32_t sc = e4m3_encode_rne_sat(s_dec_b * s_enc);     // Eq. 3
@@ -463,6 +503,23 @@ int orc_quantize(const uint16_t* x, int64_t rows, int64_t cols, int64_t ld,
     }
   }
   return 0;
+}
+
+int orc_quantize(const uint16_t* x, int64_t rows, int64_t cols, int64_t ld,
+                 int copy, int block_dim, int rounding, int rht_dim,
+                 uint64_t rht_seed, uint64_t sr_seed, const float* amax_given,
+                 uint8_t* codes, uint8_t* scales, float* tensor_scale) {
+  return quantize_impl(x, rows, cols, ld, copy, block_dim, rounding, rht_dim, rht_seed, sr_seed, amax_given, false,
+                       codes, scales, tensor_scale);
+}
+
+// The same with one tensor-level scale per row of the copy (App. B.1, last sentence): 1x16 blocks only;
+// tensor_scale: float[2 * outer] = s_dec of every row, then the amax of every row.
+int orc_quantize_row_scales(const uint16_t* x, int64_t rows, int64_t cols, int64_t ld,
+                            int copy, int rounding, int rht_dim, uint64_t rht_seed, uint64_t sr_seed,
+                            uint8_t* codes, uint8_t* scales, float* tensor_scale) {
+  return quantize_impl(x, rows, cols, ld, copy, 1, rounding, rht_dim, rht_seed, sr_seed, nullptr, true,
+                       codes, scales, tensor_scale);
 }
 
 // Decode a quantized copy [outer, inner] back to binary32:
@@ -537,6 +594,53 @@ int orc_gemm_f64_entries(const uint8_t* a_codes, const uint8_t* a_scales, float 
              deq_f64(b_codes, b_scales, b_sdec, K, n_idx[t], k);
     out[t] = acc;
   }
+  return 0;
+}
+
+// Decode, and the binary64 reference GEMM, for copies whose tensor-level scale is per row of the copy (App. B.1,
+// last sentence).  a_sdec / b_sdec point to one decode scale per row when the per-row flag of that operand is
+// set, to a single one otherwise (so a per-row activation meets a per-tensor weight).  Eq. 5's two tensor-level
+// factors become s_dec^A[m] * s_dec^B[n]: still constant along k, which is what lets them stay outside the sum.
+int orc_dequantize_row_scales(const uint8_t* codes, const uint8_t* scales, const float* s_dec,
+                              int64_t outer, int64_t inner, int undo_rht_dim, uint64_t rht_seed, float* out) {
+  if (!codes || !scales || !s_dec || !out || inner % 16) return -1;
+  if (undo_rht_dim && (!rht_dim_ok(undo_rht_dim) || inner % undo_rht_dim)) return -1;
+  uint8_t negate[128] = {0};
+  if (undo_rht_dim) rht_signs(rht_seed, undo_rht_dim, negate);
+#pragma omp parallel for schedule(static)
+  for (int64_t o = 0; o < outer; ++o) {
+    float* row = out + o * inner;
+    for (int64_t k = 0; k < inner; ++k) {
+      const float sd = e4m3_decode(scales[o * (inner / 16) + k / 16]);
+      const uint8_t byte = codes[o * (inner / 2) + k / 2];
+      const uint32_t c = (k & 1) ? (byte >> 4) : (byte & 15u);
+      const float t = e2m1_decode(c) * sd;
+      row[k] = t * s_dec[o];
+    }
+    if (undo_rht_dim)
+      for (int64_t g = 0; g < inner / undo_rht_dim; ++g) rht_inverse_d(row + undo_rht_dim * g, undo_rht_dim, negate);
+  }
+  return 0;
+}
+
+int orc_gemm_f64_row_scales(const uint8_t* a_codes, const uint8_t* a_scales, const float* a_sdec, int a_per_row,
+                            const uint8_t* b_codes, const uint8_t* b_scales, const float* b_sdec, int b_per_row,
+                            int64_t M, int64_t N, int64_t K, double* D) {
+  if (K % 16 || !a_sdec || !b_sdec) return -1;
+  std::vector<double> A(static_cast<size_t>(M) * K), B(static_cast<size_t>(N) * K);
+#pragma omp parallel for schedule(static)
+  for (int64_t m = 0; m < M; ++m)
+    for (int64_t k = 0; k < K; ++k) A[m * K + k] = deq_f64(a_codes, a_scales, a_sdec[a_per_row ? m : 0], K, m, k);
+#pragma omp parallel for schedule(static)
+  for (int64_t n = 0; n < N; ++n)
+    for (int64_t k = 0; k < K; ++k) B[n * K + k] = deq_f64(b_codes, b_scales, b_sdec[b_per_row ? n : 0], K, n, k);
+#pragma omp parallel for schedule(static)
+  for (int64_t m = 0; m < M; ++m)
+    for (int64_t n = 0; n < N; ++n) {
+      double acc = 0.0;
+      for (int64_t k = 0; k < K; ++k) acc += A[m * K + k] * B[n * K + k];
+      D[m * N + n] = acc;
+    }
   return 0;
 }
 
