@@ -152,6 +152,24 @@ int nvfp4_quantize(const void* x, int64_t rows, int64_t cols, int64_t ld, int la
                    nvfp4_stream_t stream);
 
 /*
+ * nvfp4_quantize for callers that cannot allocate device memory or carry a workspace around: code running under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and
+ * bit-identical results as nvfp4_quantize, minus the workspace: the amax pass's scratch lives in a fixed device
+ * array of NVFP4_STATIC_SCRATCH_BYTES inside the library (one copy per GPU, held until the process ends).
+ * The call allocates and frees nothing.  Tensors whose workspace need (nvfp4_quantized_sizes) exceeds
+ * NVFP4_STATIC_SCRATCH_BYTES are refused with NVFP4_ERR_WORKSPACE (enough for 87376 workgroup tiles of 128 rows x 512
+ * columns, e.g. 65536 x 81920 elements); MXFP4 needs no scratch and has no limit.  Nothing in the array has to start
+ * at zero (every word is written before it is read), and it keeps the last call's contents.  All calls on one GPU
+ * share the array: two calls that overlap in time on one GPU (different streams, or different host threads) race;
+ * calls on one stream, or ordered by events, are fine.  The first call on a device looks the array's address up
+ * (hipGetSymbolAddress) and must not be made under stream capture; later calls may be.
+ */
+enum { NVFP4_STATIC_SCRATCH_BYTES = 1 << 20 };
+int nvfp4_quantize_static(const void* x, int64_t rows, int64_t cols, int64_t ld, int layout_mask, int block_dim,
+                          int rounding, int rht_on_col, uint64_t rht_seed, uint64_t sr_seed, nvfp4_qtensor* out,
+                          nvfp4_stream_t stream);
+
+/*
  * The two passes of nvfp4_quantize as separate calls.  App. B.1 counts the global amax as an extra pass through
  * device memory; a caller that knows the amax beforehand (a weight whose amax the optimizer step tracked, an amax
  * kept from the previous iteration) or has to combine it over the shards of a larger tensor (a max all-reduce

@@ -27,7 +27,8 @@ COPY_ROW, COPY_COL = 0, 1
 EXPORTS = ["nvfp4_quantized_sizes", "nvfp4_quantize", "nvfp4_gemm", "nvfp4_gemm_workspace_bytes", "nvfp4_dequantize",
            "nvfp4_rht_sign_mask", "nvfp4_selftest_conversions", "nvfp4_status_string", "nvfp4_version",
            "nvfp4_linear_workspace_bytes", "nvfp4_linear_forward", "nvfp4_linear_backward",
-           "nvfp4_amax", "nvfp4_quantize_with_amax"]
+           "nvfp4_amax", "nvfp4_quantize_with_amax", "nvfp4_quantize_static"]
+STATIC_SCRATCH_BYTES = 1 << 20
 
 
 class QTensorStruct(ctypes.Structure):
@@ -58,6 +59,8 @@ def load_library() -> ctypes.CDLL:
         L.nvfp4_quantize.restype = ci
         L.nvfp4_quantize.argtypes = [vp, i64, i64, i64, ci, ci, ci, ci, u64, u64,
                                      ctypes.POINTER(QTensorStruct), vp, ctypes.c_size_t, vp]
+        L.nvfp4_quantize_static.restype = ci
+        L.nvfp4_quantize_static.argtypes = [vp, i64, i64, i64, ci, ci, ci, ci, u64, u64, ctypes.POINTER(QTensorStruct), vp]
         L.nvfp4_amax.restype = ci
         L.nvfp4_amax.argtypes = [vp, i64, i64, i64, ci, u64, vp, vp, ctypes.c_size_t, vp]
         L.nvfp4_quantize_with_amax.restype = ci
@@ -174,6 +177,18 @@ def nvfp4_quantize(x: torch.Tensor, layout_mask: int, block_dim: int = BLOCK_1x1
     _check(load_library().nvfp4_quantize(x.data_ptr(), rows, cols, x.stride(0), layout_mask, block_dim, rounding,
                                          int(rht_on_col), rht_seed, sr_seed, ctypes.byref(out.desc),
                                          ws.data_ptr(), ws.numel(), _stream()))
+    return out
+
+
+def nvfp4_quantize_static(x: torch.Tensor, out: QTensor, layout_mask: int, block_dim: int = BLOCK_1x16,
+                          rounding: int = ROUND_RNE, rht_on_col=False, rht_seed: int = 0, sr_seed: int = 0) -> QTensor:
+    """nvfp4_quantize without a workspace: `out` must be preallocated (alloc_qtensor); nothing is allocated here or in
+    the library."""
+    if not x.is_cuda or x.dtype != torch.bfloat16 or x.dim() != 2 or x.stride(1) != 1:
+        raise ValueError("x must be a 2-D bf16 CUDA tensor with unit inner stride")
+    rows, cols = x.shape
+    _check(load_library().nvfp4_quantize_static(x.data_ptr(), rows, cols, x.stride(0), layout_mask, block_dim, rounding,
+                                                int(rht_on_col), rht_seed, sr_seed, ctypes.byref(out.desc), _stream()))
     return out
 
 

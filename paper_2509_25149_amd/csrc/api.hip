@@ -3,6 +3,12 @@
 #include "nvfp4.h"
 #include "nvfp4_internal.h"
 
+// Scratch of nvfp4_quantize_static, the entry point for callers that cannot allocate: the quantizer's workspace (the
+// amax pass's per-workgroup maxima and their fold) in device memory that belongs to the library's code object.  Every
+// GPU the library runs on holds its own copy of this array, at its own address, until the process ends.  In host
+// code this name is only a handle for hipGetSymbolAddress -- never a device address.
+static __device__ __align__(256) unsigned char scratch[NVFP4_STATIC_SCRATCH_BYTES];   // size: include/nvfp4.h
+
 namespace nvfp4 {
 
 namespace {
@@ -229,6 +235,52 @@ int nvfp4_quantize(const void* x, int64_t rows, int64_t cols, int64_t ld, int la
   if (rc != NVFP4_OK) return rc;
   const hipError_t e = block_dim == NVFP4_BLOCK_MX32 ? launch_quantize_mx(p.a, static_cast<hipStream_t>(stream))
                                                      : launch_quantize(p.a, static_cast<hipStream_t>(stream));
+  if (e != hipSuccess) return NVFP4_ERR_HIP;
+  *out = p.desc;
+  return NVFP4_OK;
+}
+
+namespace {
+
+// Device address of `scratch` on the current device, looked up once per device (with that device current) and kept.
+constexpr int kMaxDevices = 64;
+std::atomic<void*> scratch_address[kMaxDevices];
+
+int static_scratch(void** ptr) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return NVFP4_ERR_HIP;
+  void* p = scratch_address[dev].load(std::memory_order_acquire);
+  if (!p) {
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return NVFP4_ERR_HIP;
+    scratch_address[dev].store(p, std::memory_order_release);   // two threads racing here store the same address
+  }
+  *ptr = p;
+  return NVFP4_OK;
+}
+
+}  // namespace
+
+int nvfp4_quantize_static(const void* x, int64_t rows, int64_t cols, int64_t ld, int layout_mask, int block_dim,
+                          int rounding, int rht_on_col, uint64_t rht_seed, uint64_t sr_seed, nvfp4_qtensor* out,
+                          nvfp4_stream_t stream) {
+  const bool mx = block_dim == NVFP4_BLOCK_MX32;
+  // the size limit first: it needs no GPU and no other argument
+  if (!mx && rows > 0 && cols > 0 && rows % 16 == 0 && cols % 16 == 0 &&
+      quantize_workspace_bytes(rows, cols) > NVFP4_STATIC_SCRATCH_BYTES)
+    return NVFP4_ERR_WORKSPACE;
+  // every other check with a stand-in for the workspace address, so that a bad call is refused before any HIP call
+  QuantPlan p;
+  void* const stand_in = reinterpret_cast<void*>(uintptr_t{256});
+  const int rc = plan_quantize(x, rows, cols, ld, layout_mask, block_dim, rounding, rht_on_col, rht_seed, sr_seed, out,
+                               stand_in, NVFP4_STATIC_SCRATCH_BYTES, &p);
+  if (rc != NVFP4_OK) return rc;
+  if (!mx) {
+    void* ws = nullptr;
+    const int rs = static_scratch(&ws);
+    if (rs != NVFP4_OK) return rs;
+    p.a.ws = static_cast<uint32_t*>(ws);   // the kernels take the looked-up address, as they take a caller's workspace
+  }
+  const hipError_t e = mx ? launch_quantize_mx(p.a, static_cast<hipStream_t>(stream)) : launch_quantize(p.a, static_cast<hipStream_t>(stream));
   if (e != hipSuccess) return NVFP4_ERR_HIP;
   *out = p.desc;
   return NVFP4_OK;

@@ -264,3 +264,24 @@ def test_no_kernel_keeps_arrays_in_scratch_memory():
         if any(k in name for k in ("quantize_mx_kernel", "cast_kernel", "amax_kernel", "cast_wide", "amax_wide", "decode_f16",
                                    "dequantize", "gemm_mx_kernel_k512")):
             assert r["ScratchSize"] == 0 and r["VGPRs Spill"] == 0, (name, r)
+
+
+def test_quantize_static_rejects_before_touching_the_gpu(lib):
+    """The entry point that allocates nothing: the size limit and every argument check come before any HIP call."""
+    X, OUT = 0x10000, 0x20000
+    d = _desc()
+    for f in ("row_codes", "row_scales", "row_tensor_scale", "col_codes", "col_scales", "col_tensor_scale"):
+        setattr(d, f, OUT)
+    tail = (ctypes.byref(d), None)
+    assert lib.nvfp4_quantize_static(None, 16, 16, 16, 3, 1, 0, 0, 0, 0, *tail) == -1
+    assert lib.nvfp4_quantize_static(X, 24, 16, 16, 3, 1, 0, 0, 0, 0, *tail) == -2
+    assert lib.nvfp4_quantize_static(X, 16, 16, 16, 3, 7, 0, 0, 0, 0, *tail) == -1
+    assert lib.nvfp4_quantize_static(X, 16, 16, 16, 3, 1, 0, 0, 0, 0, None, None) == -1
+    # a workspace need beyond the fixed array (1 MiB): refused, also for MXFP4-sized shapes only when NVFP4
+    rows, cols = 128 * 300, 512 * 300
+    need = ctypes.c_size_t()
+    assert lib.nvfp4_quantized_sizes(rows, cols, None, None, ctypes.addressof(need)) == 0 and need.value > nv.STATIC_SCRATCH_BYTES
+    assert lib.nvfp4_quantize_static(X, rows, cols, cols, 3, 1, 0, 0, 0, 0, *tail) == -6
+    header = open(os.path.join(ROOT, "include", "nvfp4.h")).read()
+    assert "NVFP4_STATIC_SCRATCH_BYTES = 1 << 20" in header and nv.STATIC_SCRATCH_BYTES == 1 << 20
+
