@@ -260,6 +260,61 @@ def known_amax_block(torch, nv, x, w, dy, iters: int = 5):
     return res
 
 
+def row_scale_block(torch, nv, sets, qw, gemm_ws, iters: int = 6):
+    """The quantizer with one tensor-level scale per row of each copy (NVFP4_LAYOUT_ROW_SCALES; App. B.1, last sentence:
+    a global scale of finer granularity saves the extra pass over memory).  The row copy alone is ONE pass over the
+    tensor (a workgroup holds its row in registers), so its bytes are counted once; calls that also emit the col copy
+    read the tensor twice (a column's amax spans all rows) and are counted so.  Inputs rotate over the buffer sets.
+    Outside the timed region of `value`."""
+    RS, ROW, RC = nv.LAYOUT_ROW_SCALES, nv.LAYOUT_ROW, nv.LAYOUT_ROW | nv.LAYOUT_COL
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    res = {}
+    cases = (("X_8192x5120_rne", 0, nv.ROUND_RNE), ("dY_8192x20480_sr", 2, nv.ROUND_SR))
+    for name, which, rnd in cases:
+        rows, cols = sets[0][which].shape
+        n = rows * cols
+        for layout, tag, nbytes in ((ROW, "row_copy_one_pass", 2.0 * n + n / 2.0 + n / 16.0 + 8.0 * rows),
+                                    (RC, "both_copies_two_pass", 4.0 * n + 2 * (n / 2.0 + n / 16.0) + 8.0 * (rows + cols))):
+            q = nv.alloc_qtensor(rows, cols, layout | RS)
+            ms = []
+            for it in range(iters + 1):
+                t = sets[it % len(sets)][which]
+                a, b = ev(), ev()
+                a.record()
+                nv.nvfp4_quantize(t, layout | RS, nv.BLOCK_1x16, rnd, layout == RC, 2025, 77 + it, out=q)
+                b.record()
+                torch.cuda.synchronize()
+                if it:
+                    ms.append(a.elapsed_time(b))
+            ms.sort()
+            med = ms[len(ms) // 2]
+            res[f"{name}_{tag}"] = {"ms_median": med, "ms_min": ms[0], "bytes_algorithmic": nbytes,
+                                    "GBps": nbytes / (med * 1e-3) / 1e9, "frac_of_hbm_peak": nbytes / (med * 1e-3) / 1e9 / PEAK_HBM_GBPS}
+    # Fprop with per-row activation scales against the per-tensor weight: the output stage multiplies by s_dec[m]
+    x = sets[0][0]
+    qx = nv.nvfp4_quantize(x, ROW | RS)
+    y = torch.empty((TOKENS, D_FFN), dtype=torch.bfloat16, device="cuda")
+    ms = []
+    for it in range(iters + 1):
+        a, b = ev(), ev()
+        a.record()
+        nv.nvfp4_gemm(qx, qw, nv.OP_FPROP, nv.OUT_BF16, out=y, workspace=gemm_ws)
+        b.record()
+        torch.cuda.synchronize()
+        if it:
+            ms.append(a.elapsed_time(b))
+    ms.sort()
+    res["fprop_gemm_with_per_row_activation_scales_ms_median"] = ms[len(ms) // 2]
+    rows_total = sum(res[k]["bytes_algorithmic"] for k in res if k.endswith("row_copy_one_pass"))
+    rows_ms = sum(res[k]["ms_median"] for k in res if k.endswith("row_copy_one_pass"))
+    res["roofline_row_copies"] = {"kernel": "rowscale_row_kernel (X RNE + dY SR row copies, one pass each)", "bound": "hbm",
+                                  "achieved": rows_total / (rows_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBPS, "unit": "GB/s",
+                                  "frac": rows_total / (rows_ms * 1e-3) / 1e9 / PEAK_HBM_GBPS}
+    res["note"] = ("not part of `value`: nvfp4_quantize with NVFP4_LAYOUT_ROW_SCALES; row copy alone = one pass (bf16 read once + "
+                   "codes + scales + the scale vectors), both copies = two passes (bf16 counted twice)")
+    return res
+
+
 def matrix_pipe_context(torch, nv, reps: int = 3, iters: int = 100000):
     """What the FP16 matrix pipe sustains on this machine, measured beside the step: bench_probe.hip's register-only MFMA
     loop (no memory traffic) per operand kind, and the vendor library's FP16 GEMM (torch.matmul) at the Fprop shape on
@@ -353,6 +408,7 @@ def main() -> int:
     ap.add_argument("--no-rht-sweep", action="store_true", help="skip the rotation-size block")
     ap.add_argument("--no-context", action="store_true", help="skip the matrix-pipe context block")
     ap.add_argument("--no-layer-calls", action="store_true", help="skip the per-layer entry point block")
+    ap.add_argument("--no-row-scales", action="store_true", help="skip the per-row tensor scale block")
     ap.add_argument("--buffer-sets", type=int, default=3, help="distinct input/output sets the steps rotate over")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -515,6 +571,8 @@ def main() -> int:
         out["layer_calls"] = layer_calls_block(torch, nv, sets, bufs[0]["qw"], gemm_ws_bytes)
         out["layer_calls"]["separate_calls_same_work_ms"] = (step_ms[len(step_ms) // 2] - q_med[1]
                                                              - sorted(a.elapsed_time(b) for a, b in deq_events)[len(deq_events) // 2])
+    if not args.no_row_scales:
+        out["row_scale_mode"] = row_scale_block(torch, nv, sets, bufs[0]["qw"], gemm_ws)
     if not args.no_mxfp4:
         out["mxfp4_comparison"] = mxfp4_comparison(torch, nv, x, w, dy)
     if not args.no_rht_sweep:

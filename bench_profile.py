@@ -5,9 +5,9 @@ profiles/measured_counters.json, which bench.py reads back (HBM-side traffic per
 rocprofv3 is run on the GPU machine (from /tmp with TMPDIR=/tmp; R = repository root), one run per counter group, the
 program directly after `--`:
 
-  B="python3 $R/bench.py --steps 2 --warmup 1 --no-cpu-baseline --no-layer-calls --no-rht-sweep --no-context"
+  B="python3 $R/bench.py --steps 2 --warmup 1 --no-cpu-baseline --no-layer-calls --no-row-scales --no-rht-sweep --no-context"
   rocprofv3 --kernel-trace --stats -d $R/gpurun_out/prof/trace -o bench -- python3 $R/bench.py --steps 5 --warmup 1 \
-            --no-cpu-baseline --no-layer-calls --no-rht-sweep --no-context
+            --no-cpu-baseline --no-layer-calls --no-row-scales --no-rht-sweep --no-context
   rocprofv3 --pmc FETCH_SIZE -d $R/gpurun_out/prof/fetch -o bench -- $B
   rocprofv3 --pmc WRITE_SIZE -d $R/gpurun_out/prof/write -o bench -- $B
   rocprofv3 --pmc SQ_VALU_MFMA_BUSY_CYCLES SQ_BUSY_CU_CYCLES SQ_INSTS_VALU_MFMA_MOPS_F16 SQ_INSTS_VALU_MFMA_MOPS_F6F4 \
@@ -15,9 +15,9 @@ program directly after `--`:
   rocprofv3 --pmc SQ_LDS_BANK_CONFLICT SQ_LDS_IDX_ACTIVE SQ_INSTS_LDS SQ_INSTS_VALU SQ_ACTIVE_INST_VALU SQ_WAVE_CYCLES \
             SQ_WAIT_INST_ANY SQ_WAVES GRBM_GUI_ACTIVE -d $R/gpurun_out/prof/sq -o bench -- $B
 
-then, anywhere the databases are:
+then, anywhere the databases are (they are large; on the GPU machine itself is simplest):
 
-  python3 bench_profile.py gpurun_out/prof
+  python3 bench_profile.py gpurun_out/prof [--out DIR]        # DIR defaults to profiles/
 
 Only this file, bench.py and the library are involved.  Nothing here runs on the GPU.
 """
@@ -34,9 +34,9 @@ import sys
 ROOT = os.path.dirname(os.path.abspath(__file__))
 OUT_DIR = os.path.join(ROOT, "profiles")
 GEMM_FLOPS = 2.0 * 8192 * 5120 * 20480
-CUS, SIMDS_PER_CU = 256, 4
+CUS, SIMDS_PER_CU, XCDS = 256, 4, 8
 
-BENCH_TAIL = "--no-cpu-baseline --no-layer-calls --no-rht-sweep --no-context"
+BENCH_TAIL = "--no-cpu-baseline --no-layer-calls --no-row-scales --no-rht-sweep --no-context"
 COMMANDS = {
     "trace": f"rocprofv3 --kernel-trace --stats -d $R/gpurun_out/prof/trace -o bench -- python3 $R/bench.py --steps 5 --warmup 1 {BENCH_TAIL}",
     "fetch": f"rocprofv3 --pmc FETCH_SIZE -d $R/gpurun_out/prof/fetch -o bench -- python3 $R/bench.py --steps 2 --warmup 1 {BENCH_TAIL}",
@@ -129,10 +129,16 @@ def git_head() -> str:
 
 
 def main() -> int:
-    if len(sys.argv) != 2:
+    global OUT_DIR
+    argv = sys.argv[1:]
+    if "--out" in argv:
+        i = argv.index("--out")
+        OUT_DIR = os.path.abspath(argv[i + 1])
+        del argv[i:i + 2]
+    if len(argv) != 1:
         print(__doc__)
         return 2
-    base = sys.argv[1]
+    base = argv[0]
     dbs = {k: find_db(os.path.join(base, k)) for k in COMMANDS}
     os.makedirs(OUT_DIR, exist_ok=True)
     measured = {"source": f"rocprofv3 runs of bench.py summarised by bench_profile.py (tree at or after commit {git_head()}); "
@@ -195,11 +201,12 @@ def main() -> int:
         with open(os.path.join(OUT_DIR, "bench_linear_layer_12B_mfma_pmc.txt"), "w") as fh:
             fh.write("rocprofv3 PMC summary (matrix pipe): " + head)
             fh.write("Command:\n  " + COMMANDS["mfma"] + "\n")
-            fh.write("Counters are sums over the chip per dispatch.  SQ_VALU_MFMA_BUSY_CYCLES counts cycles the matrix pipe of a SIMD is busy\n"
-                     "(summed over the SIMDs, in units the ratio below is taken in); GRBM_GUI_ACTIVE = GPU clock cycles of the dispatch.\n"
-                     f"mfma busy fraction = SQ_VALU_MFMA_BUSY_CYCLES / (GRBM_GUI_ACTIVE x {CUS} CUs x {SIMDS_PER_CU} SIMDs); the counter's own unit is\n"
-                     "checked on the register-only loop of the side block, if profiled.  MOPS counters count 512 flop each: MOPS x 512 against 2 M N K\n"
-                     "proves the timed kernel does the whole contraction.\n\n")
+            fh.write("Counters are sums over the chip per dispatch.  SQ_VALU_MFMA_BUSY_CYCLES = cycles the matrix pipe of a SIMD is busy, summed\n"
+                     "over the 1024 SIMDs: exactly 16 per v_mfma_f32_16x16x32_f16 and per v_mfma_scale_f32_16x16x128_f8f6f4 with FP4 operands\n"
+                     "(BUSY / (MOPS x 512 / flop per instruction) below).  GRBM_GUI_ACTIVE = GPU clock cycles of the dispatch, here summed over\n"
+                     f"the {XCDS} XCDs (each counts on its own: divided by {XCDS} and by the duration it gives the clock, 2.1 - 2.5 GHz).\n"
+                     f"mfma busy fraction = SQ_VALU_MFMA_BUSY_CYCLES / (GRBM_GUI_ACTIVE / {XCDS} x {CUS} CUs x {SIMDS_PER_CU} SIMDs), rocprofv3's own MfmaUtil formula.\n"
+                     "MOPS counters count 512 flop each: MOPS x 512 against 2 M N K proves the timed kernels do the whole contraction.\n\n")
             for cn in sorted(m):
                 fh.write("\n".join(fmt_pmc(m, cn)) + "\n\n")
             busy, act = m.get("SQ_VALU_MFMA_BUSY_CYCLES", {}), m.get("GRBM_GUI_ACTIVE", {})
@@ -207,8 +214,11 @@ def main() -> int:
             fh.write("Derived:\n")
             for kern in busy:
                 if kern in act and act[kern][1] > 0:
-                    frac = busy[kern][1] / (act[kern][1] * CUS * SIMDS_PER_CU)
-                    fh.write(f"  {kern}: mfma busy fraction {frac:.3f}")
+                    if busy[kern][1] == 0:
+                        continue
+                    cycles = act[kern][1] / XCDS
+                    frac = busy[kern][1] / (cycles * CUS * SIMDS_PER_CU)
+                    fh.write(f"  {kern}: mfma busy fraction {frac:.3f} (average over its dispatches), clock {cycles / act[kern][4] :.2f} GHz")
                     if kern in mops and mops[kern][1] > 0:
                         fh.write(f"; MOPS_F16 x 512 = {mops[kern][1] * 512:.4e} flop per dispatch (avg)")
                     fh.write("\n")

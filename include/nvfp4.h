@@ -74,6 +74,21 @@ enum { NVFP4_LAYOUT_ROW = 1, NVFP4_LAYOUT_COL = 2 };       /* layout mask bits *
  * that way.  NVFP4 with 1x16 blocks only, NVFP4_LAYOUT_ROW required, the col copy (if asked for) plain or rotated
  * with d = 16; not accepted by nvfp4_quantize_with_amax.  The descriptor records it as row_has_rht = 16. */
 enum { NVFP4_LAYOUT_ROW_RHT = 4 };
+/* Extra layout mask bit of nvfp4_quantize: a tensor-level scale of finer granularity.  App. B.1 (last sentence) notes
+ * that the global scale may span a row or a block instead of the whole tensor, which saves the extra pass over device
+ * memory that the tensor's amax costs.  With this bit Eq. 1 is evaluated once per row of each emitted copy's
+ * K-contiguous storage, with that row's amax: per logical row for the row copy, per logical column (over the rotated
+ * values, App. C) for the col copy -- the one granularity that stays constant along the contraction, so that
+ * nvfp4_gemm can still apply the two tensor-level factors after the sum (Eq. 5): D[m, n] gets s_dec^A[m] * s_dec^B[n].
+ * Eq. 2-4 are unchanged.  tensor_scale of a copy then is float[2 * outer] (outer = rows for the row copy, cols for
+ * the col copy): s_dec of every row, then the amax of every row.  A row copy asked for alone (up to 32768 columns) is
+ * produced in ONE pass over the tensor -- a workgroup holds its row in registers; a col copy's amax spans all rows of
+ * the tensor, so calls that emit it still read the tensor twice.  NVFP4 with 1x16 blocks only (a 16x16 weight tile's
+ * scale has to serve both orientations, Sec. 4.3), rht_on_col 0, 1 or 16, not with NVFP4_LAYOUT_ROW_RHT, not accepted
+ * by nvfp4_quantize_with_amax.  Operands of either granularity mix freely in nvfp4_gemm (per-row activations with a
+ * per-tensor 16x16 weight).  Non-finite input is reported in the amax of the rows (row copy) it occurs in; the col
+ * copy's rotated maxima skip NaNs.  The descriptor records it as scale_per_row = 1. */
+enum { NVFP4_LAYOUT_ROW_SCALES = 8 };
 /* block_dim.  NVFP4_BLOCK_MX32 selects the paper's comparison format MXFP4 instead of NVFP4 (Sec. 2, App. B.4,
  * Sec. 5): blocks of 32 along the copy's contiguous dimension, one UE8M0 byte per block (2^(byte - 127), amax_b / 6
  * rounded up to a power of two), no tensor-level scale (tensor_scale = {1, 0}), scales [.., ../32] bytes, a 32-point
@@ -107,6 +122,7 @@ typedef struct nvfp4_qtensor {
   int32_t col_has_rht;      /* 0, or the size d of the rotation applied to the col copy */
   uint64_t rht_seed;        /* seed of the sign diagonal, if rotated */
   int32_t row_has_rht;      /* 0, or 16: the row copy is rotated along its columns (NVFP4_LAYOUT_ROW_RHT) */
+  int32_t scale_per_row;    /* 0: tensor_scale is float[2]; 1: float[2 * outer] per copy (NVFP4_LAYOUT_ROW_SCALES) */
 } nvfp4_qtensor;
 
 /*
@@ -121,7 +137,8 @@ int nvfp4_quantized_sizes(int64_t rows, int64_t cols, size_t* codes_bytes, size_
  * Quantize a bf16 tensor to NVFP4 (App. B Eq. 1-4).
  *   x            device, bf16 [rows, cols], row-major with leading dimension ld (elements)
  *   layout_mask  NVFP4_LAYOUT_ROW | NVFP4_LAYOUT_COL: which copies to emit
- *                (| NVFP4_LAYOUT_ROW_RHT: the row copy rotated as well)
+ *                (| NVFP4_LAYOUT_ROW_RHT: the row copy rotated as well;
+ *                 | NVFP4_LAYOUT_ROW_SCALES: one tensor-level scale per row of each copy)
  *   block_dim    1x16 (activations, gradients) or 16x16 (weights, Sec. 4.3)
  *   rounding     RNE (weights, activations) or SR (gradients), Sec. 4.4
  *   rht_on_col   rotate the col copy: every aligned group of d consecutive
@@ -193,7 +210,8 @@ int nvfp4_quantize_with_amax(const void* x, int64_t rows, int64_t cols, int64_t 
 
 /*
  * Block-scaled GEMM (Eq. 5): D[m, n] = s_dec^A s_dec^B sum_b sA[m,b] sB[n,b]
- * sum_{k in b} A[m,k] B[n,k], FP32 accumulation.  `op` picks the copies:
+ * sum_{k in b} A[m,k] B[n,k], FP32 accumulation (s_dec^A[m] s_dec^B[n] for operands
+ * quantized with NVFP4_LAYOUT_ROW_SCALES).  `op` picks the copies:
  *   FPROP  Y  = X W      A = row copy of X [M,K],   B = col copy of W [K,N] (-> [N,K])
  *   DGRAD  dX = dY W^T   A = row copy of dY [M,K],  B = row copy of W [N,K]
  *   WGRAD  dW = A^T B    A = col copy of the first tensor [K,M] (-> [M,K]),

@@ -18,6 +18,7 @@ LIB_PATH = os.path.join(_PKG, "libnvfp4_hip.so")
 
 LAYOUT_ROW, LAYOUT_COL = 1, 2
 LAYOUT_ROW_RHT = 4   # with LAYOUT_ROW: the row copy is rotated too (16-point, along its columns)
+LAYOUT_ROW_SCALES = 8   # one tensor-level scale per row of each copy; tensor scales are float[2 * outer]
 BLOCK_1x16, BLOCK_16x16, BLOCK_MX32 = 1, 16, 32
 ROUND_RNE, ROUND_SR = 0, 1
 OP_FPROP, OP_DGRAD, OP_WGRAD = 0, 1, 2
@@ -40,7 +41,7 @@ class QTensorStruct(ctypes.Structure):
                 ("col_tensor_scale", ctypes.c_void_p),
                 ("layout_mask", ctypes.c_int32), ("block_dim", ctypes.c_int32),
                 ("rounding", ctypes.c_int32), ("col_has_rht", ctypes.c_int32),
-                ("rht_seed", ctypes.c_uint64), ("row_has_rht", ctypes.c_int32)]
+                ("rht_seed", ctypes.c_uint64), ("row_has_rht", ctypes.c_int32), ("scale_per_row", ctypes.c_int32)]
 
 
 _lib = None
@@ -136,18 +137,19 @@ class QTensor:
 def alloc_qtensor(rows: int, cols: int, layout_mask: int, device="cuda", block_dim: int = BLOCK_1x16) -> QTensor:
     quantized_sizes(rows, cols)                       # shape check
     blk = 32 if block_dim == BLOCK_MX32 else 16     # elements per scale byte
+    per_row = bool(layout_mask & LAYOUT_ROW_SCALES)   # tensor scales: float[2], or s_dec and amax per row of the copy
     q = QTensor(QTensorStruct(), rows, cols)
     q.desc.rows, q.desc.cols = rows, cols
     if layout_mask & LAYOUT_ROW:
         q.row_codes = torch.empty((rows, cols // 2), dtype=torch.uint8, device=device)
         q.row_scales = torch.empty((rows, cols // blk), dtype=torch.uint8, device=device)
-        q.row_ts = torch.empty(2, dtype=torch.float32, device=device)
+        q.row_ts = torch.empty(2 * rows if per_row else 2, dtype=torch.float32, device=device)
         q.desc.row_codes, q.desc.row_scales = q.row_codes.data_ptr(), q.row_scales.data_ptr()
         q.desc.row_tensor_scale = q.row_ts.data_ptr()
     if layout_mask & LAYOUT_COL:
         q.col_codes = torch.empty((cols, rows // 2), dtype=torch.uint8, device=device)
         q.col_scales = torch.empty((cols, rows // blk), dtype=torch.uint8, device=device)
-        q.col_ts = torch.empty(2, dtype=torch.float32, device=device)
+        q.col_ts = torch.empty(2 * cols if per_row else 2, dtype=torch.float32, device=device)
         q.desc.col_codes, q.desc.col_scales = q.col_codes.data_ptr(), q.col_scales.data_ptr()
         q.desc.col_tensor_scale = q.col_ts.data_ptr()
     return q

@@ -14,7 +14,7 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libnvfp4_hip.so")
 RESOURCES = os.path.join(PKG, "libnvfp4_hip.resources.json")   # per-kernel register / scratch use, written by the build
-SOURCES = ["api.hip", "quantize.hip", "quantize_wide.hip", "quantize_rowrot.hip", "quantize_mx.hip", "gemm.hip", "gemm_f16.hip", "gemm_mx.hip", "dequantize.hip", "selftest.hip"]
+SOURCES = ["api.hip", "quantize.hip", "quantize_wide.hip", "quantize_rowrot.hip", "quantize_rowscale.hip", "quantize_mx.hip", "gemm.hip", "gemm_f16.hip", "gemm_mx.hip", "dequantize.hip", "selftest.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-fPIC",

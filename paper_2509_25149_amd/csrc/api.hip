@@ -121,9 +121,10 @@ int plan_quantize(const void* x, int64_t rows, int64_t cols, int64_t ld, int lay
                   int rht_on_col, uint64_t rht_seed, uint64_t sr_seed, const nvfp4_qtensor* out, void* workspace,
                   size_t workspace_bytes, QuantPlan* p, bool amax_given = false) {
   if (!x || !out) return NVFP4_ERR_INVALID_ARG;
-  if (layout_mask <= 0 || (layout_mask & ~(NVFP4_LAYOUT_ROW | NVFP4_LAYOUT_COL | NVFP4_LAYOUT_ROW_RHT)))
+  if (layout_mask <= 0 || (layout_mask & ~(NVFP4_LAYOUT_ROW | NVFP4_LAYOUT_COL | NVFP4_LAYOUT_ROW_RHT | NVFP4_LAYOUT_ROW_SCALES)))
     return NVFP4_ERR_INVALID_ARG;
   const bool row_rht = layout_mask & NVFP4_LAYOUT_ROW_RHT;
+  const bool scale_per_row = layout_mask & NVFP4_LAYOUT_ROW_SCALES;
   layout_mask &= NVFP4_LAYOUT_ROW | NVFP4_LAYOUT_COL;
   if (layout_mask == 0) return NVFP4_ERR_INVALID_ARG;
   if (block_dim != NVFP4_BLOCK_1x16 && block_dim != NVFP4_BLOCK_16x16 && block_dim != NVFP4_BLOCK_MX32)
@@ -136,12 +137,18 @@ int plan_quantize(const void* x, int64_t rows, int64_t cols, int64_t ld, int lay
   // A rotated row copy: NVFP4 1x16 blocks, the 16-point rotation only, both passes in this call.
   if (row_rht && (!want_row || block_dim != NVFP4_BLOCK_1x16 || (rht_dim && rht_dim != 16) || amax_given))
     return NVFP4_ERR_INVALID_ARG;
+  // One tensor-level scale per row of each copy: NVFP4 1x16 blocks (a 16x16 weight tile's scale must serve both
+  // orientations, Sec. 4.3), the recipe's rotation or none, both passes in this call.
+  if (scale_per_row && (block_dim != NVFP4_BLOCK_1x16 || row_rht || (rht_dim && rht_dim != 16) || amax_given))
+    return NVFP4_ERR_INVALID_ARG;
   if (rows <= 0 || cols <= 0 || rows % 16 || cols % 16 || ld < cols || ld % 8) return NVFP4_ERR_BAD_SHAPE;
   if (rht_dim && rows % rht_dim) return NVFP4_ERR_BAD_SHAPE;   // whole rotation groups along the rows
   if (mx && (rows % 32 || cols % 32)) return NVFP4_ERR_BAD_SHAPE;
   if (!aligned(x, 16)) return NVFP4_ERR_INVALID_ARG;
   if (want_row && (!out->row_codes || !out->row_scales || !out->row_tensor_scale)) return NVFP4_ERR_INVALID_ARG;
   if (want_col && (!out->col_codes || !out->col_scales || !out->col_tensor_scale)) return NVFP4_ERR_INVALID_ARG;
+  if (scale_per_row && ((want_row && !aligned(out->row_tensor_scale, 16)) || (want_col && !aligned(out->col_tensor_scale, 16))))
+    return NVFP4_ERR_INVALID_ARG;   // the GEMM reads the scale vectors in 16-byte pieces
   if (want_row && (!aligned(out->row_codes, 16) || !aligned(out->row_scales, 16))) return NVFP4_ERR_INVALID_ARG;
   if (want_col && (!aligned(out->col_codes, 16) || !aligned(out->col_scales, 16))) return NVFP4_ERR_INVALID_ARG;
   // the MXFP4 mode is a single pass and needs no workspace
@@ -163,6 +170,7 @@ int plan_quantize(const void* x, int64_t rows, int64_t cols, int64_t ld, int lay
   a.sr = rounding == NVFP4_ROUND_SR;
   a.block2d = block_dim == NVFP4_BLOCK_16x16;
   a.row_rht = row_rht;
+  a.scale_per_row = scale_per_row;
   fill_signs(rht_seed, row_rht ? 16 : rht_dim, &a.sign_mask, a.sign_words);
   a.key0 = static_cast<uint32_t>(sr_seed);
   a.key1 = static_cast<uint32_t>(sr_seed >> 32);
@@ -183,6 +191,7 @@ int plan_quantize(const void* x, int64_t rows, int64_t cols, int64_t ld, int lay
   p->desc.rounding = rounding;
   p->desc.col_has_rht = rht_dim;
   p->desc.row_has_rht = row_rht ? 16 : 0;
+  p->desc.scale_per_row = scale_per_row ? 1 : 0;
   p->desc.rht_seed = (a.rht || row_rht) ? rht_seed : 0;
   return NVFP4_OK;
 }
@@ -294,6 +303,7 @@ static int pick_operand(const nvfp4_qtensor* q, bool col_copy, Operand* op, int6
     op->scales = static_cast<const uint8_t*>(q->col_scales);
     op->ts = q->col_tensor_scale;
     op->outer = q->cols;
+    op->ts_per_row = q->scale_per_row ? 1 : 0;
     *K = q->rows;
   } else {
     if (!(q->layout_mask & NVFP4_LAYOUT_ROW) || !q->row_codes || !q->row_scales || !q->row_tensor_scale)
@@ -302,6 +312,7 @@ static int pick_operand(const nvfp4_qtensor* q, bool col_copy, Operand* op, int6
     op->scales = static_cast<const uint8_t*>(q->row_scales);
     op->ts = q->row_tensor_scale;
     op->outer = q->rows;
+    op->ts_per_row = q->scale_per_row ? 1 : 0;
     *K = q->cols;
   }
   return NVFP4_OK;
@@ -336,6 +347,8 @@ static int plan_gemm(const nvfp4_qtensor* a, const nvfp4_qtensor* b, int op, voi
   // Both operands in the same format: NVFP4 (E4M3 scale per 16) or MXFP4 (UE8M0 scale per 32).
   const bool a_mx = a->block_dim == NVFP4_BLOCK_MX32, b_mx = b->block_dim == NVFP4_BLOCK_MX32;
   if (a_mx != b_mx) return NVFP4_ERR_MISMATCH;
+  if (a_mx && (a->scale_per_row || b->scale_per_row)) return NVFP4_ERR_INVALID_ARG;   // MXFP4 has no tensor-level scale
+  if ((g.a.ts_per_row && !aligned(g.a.ts, 16)) || (g.b.ts_per_row && !aligned(g.b.ts, 16))) return NVFP4_ERR_INVALID_ARG;
   if (a_mx && (ka % 128 || g.a.outer % 32 || g.b.outer % 32)) return NVFP4_ERR_BAD_SHAPE;   // one scaled MFMA is 128 deep
   if (a_mx && (!aligned(g.a.codes, 16) || !aligned(g.b.codes, 16) || !aligned(g.a.scales, 4) || !aligned(g.b.scales, 4)))
     return NVFP4_ERR_INVALID_ARG;

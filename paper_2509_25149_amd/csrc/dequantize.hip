@@ -25,7 +25,7 @@ __global__ __launch_bounds__(256) void dequantize_kernel(Operand q, int64_t K, b
   const int64_t o = idx / nblk, b = idx % nblk;
   const uint2 c = *reinterpret_cast<const uint2*>(q.codes + o * (K / 2) + b * 8);
   const float sd = e4m3_decode(q.scales[o * nblk + b]);
-  const float s_dec = q.ts[0];
+  const float s_dec = q.ts[q.ts_per_row ? o : 0];   // per tensor, or this row's own (App. B.1, last sentence)
   float v[16];
   decode_pair_f32<0>(c.x, v + 0);
   decode_pair_f32<1>(c.x, v + 2);
@@ -118,7 +118,7 @@ __global__ __launch_bounds__(256) void dequantize_rot_kernel(Operand q, int64_t 
   const int64_t idx = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
   if (idx >= q.outer * nper) return;
   const int64_t o = idx / nper, b = idx % nper;
-  const float s_dec = q.ts[0];
+  const float s_dec = q.ts[q.ts_per_row ? o : 0];
   float v[kE];
 #pragma unroll
   for (int blk = 0; blk < kE / 16; ++blk) {

@@ -15,6 +15,7 @@
 // tensor-level decode scales are applied to the finished sums.
 #include "nvfp4_internal.h"
 #include "nvfp4_device.h"
+#include "gemm_epilogue.h"
 
 namespace nvfp4 {
 
@@ -120,7 +121,9 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_kernel(Operand A, Operand B
   }
 
   // Tensor-level decode scales on the finished sums (App. B.3, after Eq. 5).
-  const float out_scale = A.ts[0] * B.ts[0];
+  const TensorScales ts{A.ts, B.ts, A.ts_per_row != 0, B.ts_per_row != 0};
+  const bool vec = ts.a_per_row || ts.b_per_row;
+  const float out_scale = vec ? 0.0f : A.ts[0] * B.ts[0];
   const int M = static_cast<int>(A.outer - m0 < BM ? A.outer - m0 : BM);
   const int N = static_cast<int>(B.outer - n0 < BN ? B.outer - n0 : BN);
 #pragma unroll
@@ -132,9 +135,10 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_kernel(Operand A, Operand B
       for (int q = 0; q < 4; ++q) {
         const int n = wn * 64 + j * 32 + q * 8 + (lane >> 5) * 4;
         if (m < M && n < N) {  // N is a multiple of 16, so the 4 columns are in or out together
+          const float4v sc = scale4(ts, out_scale, vec, true, m0 + m, n0 + n);
           float4v v;
 #pragma unroll
-          for (int t = 0; t < 4; ++t) v[t] = acc[i][j][q * 4 + t] * out_scale;
+          for (int t = 0; t < 4; ++t) v[t] = acc[i][j][q * 4 + t] * sc[t];
           if (kBf16Out) {
             uint16_t* d = static_cast<uint16_t*>(Dv) + (m0 + m) * ldd + n0 + n;
             uint2 o;
@@ -313,7 +317,9 @@ __global__ __launch_bounds__(kBigThreads) void gemm_kernel_256(Operand A, Operan
     cur = nxt;
   }
 
-  const float out_scale = A.ts[0] * B.ts[0];
+  const TensorScales ts{A.ts, B.ts, A.ts_per_row != 0, B.ts_per_row != 0};
+  const bool vec = ts.a_per_row || ts.b_per_row;
+  const float out_scale = vec ? 0.0f : A.ts[0] * B.ts[0];
   const int M = static_cast<int>(A.outer - m0 < TM ? A.outer - m0 : TM);
   const int N = static_cast<int>(B.outer - n0 < TN ? B.outer - n0 : TN);
 #pragma unroll
@@ -323,7 +329,7 @@ __global__ __launch_bounds__(kBigThreads) void gemm_kernel_256(Operand A, Operan
     for (int j = 0; j < 4; ++j) {
       const int n = wn * 64 + j * 16 + lq * 4;
       if (m < M && n < N) {  // N is a multiple of 16, so the 4 columns are in or out together
-        float4v v = acc[i][j] * out_scale;
+        float4v v = acc[i][j] * scale4(ts, out_scale, vec, true, m0 + m, n0 + n);
         if (kBf16Out) {
           uint16_t* d = static_cast<uint16_t*>(Dv) + (m0 + m) * ldd + n0 + n;
           uint2 o;

@@ -24,17 +24,59 @@ namespace nvfp4 {
 // 256-byte row pieces was tried with ordinary stores and measured no faster.)
 typedef uint32_t u32x4v __attribute__((ext_vector_type(4)));
 
-template <bool kBf16Out>
-__device__ __forceinline__ void store_wave_block(float4v (&acc)[8][8], float out_scale, void* __restrict__ Dv, int64_t ldd,
-                                                 bool accumulate, int64_t row0, int64_t col0, int rows, int cols, int lane) {
+// The two operands' tensor-level decode scales.  Per tensor: a[0] * b[0] for every output.  With a scale per row of an
+// operand (App. B.1, last sentence) output (m, n) takes a[m] * b[n]: still constant along k, so still outside the sum.
+struct TensorScales {
+  const float* a;
+  const float* b;
+  bool a_per_row, b_per_row;
+};
+
+// scale of the four outputs (row m, columns n .. n + 3); m, n global indices inside the matrix (used by the kernels
+// with small tiles; the 128 x 128 wave block below loads its scale vectors once)
+__device__ __forceinline__ float4v scale4(const TensorScales& ts, float uniform, bool vec, bool in, int64_t m, int64_t n) {
+  float4v s = {uniform, uniform, uniform, uniform};
+  if (vec && in) {
+    const float sa = ts.a[ts.a_per_row ? m : 0];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) s[r] = sa * ts.b[ts.b_per_row ? n + r : 0];
+  }
+  return s;
+}
+
+// kVec: an operand carries one scale per row; the lane's 8 rows (m = 16 i + l16) and 8 x 4 columns (n = 16 j + 4 lq + r)
+// then take their factors from the vectors, loaded once.  Otherwise the product a[0] * b[0] serves every output.
+template <bool kBf16Out, bool kVec>
+__device__ __forceinline__ void store_wave_block_impl(float4v (&acc)[8][8], const TensorScales ts, void* __restrict__ Dv, int64_t ldd,
+                                                      bool accumulate, int64_t row0, int64_t col0, int rows, int cols, int lane) {
   const int l16 = lane & 15, lq = lane >> 4;
+  const float out_scale = ts.a[0] * ts.b[0];
+  float sa[kVec ? 8 : 1];
+  float4v sb[kVec ? 8 : 1];
+  if (kVec) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) sa[kVec ? i : 0] = ts.a[ts.a_per_row && i * 16 + l16 < rows ? row0 + i * 16 + l16 : 0];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      if (ts.b_per_row && j * 16 + lq * 4 < cols) {
+        sb[kVec ? j : 0] = *reinterpret_cast<const float4v*>(ts.b + col0 + j * 16 + lq * 4);
+      } else {
+        const float b0 = ts.b[0];
+        sb[kVec ? j : 0] = float4v{b0, b0, b0, b0};
+      }
+    }
+  }
+  auto scale = [&](int i, int j) -> float4v {
+    if (kVec) return sb[kVec ? j : 0] * sa[kVec ? i : 0];
+    return float4v{out_scale, out_scale, out_scale, out_scale};
+  };
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
     const int m = i * 16 + l16;
     if (kBf16Out) {
 #pragma unroll
       for (int j = 0; j < 8; j += 2) {
-        const float4v va = acc[i][j] * out_scale, vb = acc[i][j + 1] * out_scale;
+        const float4v va = acc[i][j] * scale(i, j), vb = acc[i][j + 1] * scale(i, j + 1);
         const uint32_t a0 = f32_to_bf16(va[0]) | (f32_to_bf16(va[1]) << 16), a1 = f32_to_bf16(va[2]) | (f32_to_bf16(va[3]) << 16);
         const uint32_t b0 = f32_to_bf16(vb[0]) | (f32_to_bf16(vb[1]) << 16), b1 = f32_to_bf16(vb[2]) | (f32_to_bf16(vb[3]) << 16);
         // first result: lanes of odd groups now hold the second block's dword of the group below; second result: lanes of
@@ -53,7 +95,7 @@ __device__ __forceinline__ void store_wave_block(float4v (&acc)[8][8], float out
       for (int j = 0; j < 8; ++j) {
         const int n = j * 16 + lq * 4;
         if (m < rows && n < cols) {  // columns come in multiples of 16, so the 4 columns are in or out together
-          float4v v = acc[i][j] * out_scale;
+          float4v v = acc[i][j] * scale(i, j);
           float* d = static_cast<float*>(Dv) + (row0 + m) * ldd + col0 + n;
           if (accumulate) v += *reinterpret_cast<const float4v*>(d);
           __builtin_nontemporal_store(v, reinterpret_cast<float4v*>(d));
@@ -61,6 +103,15 @@ __device__ __forceinline__ void store_wave_block(float4v (&acc)[8][8], float out
       }
     }
   }
+}
+
+template <bool kBf16Out>
+__device__ __forceinline__ void store_wave_block(float4v (&acc)[8][8], const TensorScales ts, void* __restrict__ Dv, int64_t ldd,
+                                                 bool accumulate, int64_t row0, int64_t col0, int rows, int cols, int lane) {
+  if (ts.a_per_row || ts.b_per_row)   // uniform over the launch
+    store_wave_block_impl<kBf16Out, true>(acc, ts, Dv, ldd, accumulate, row0, col0, rows, cols, lane);
+  else
+    store_wave_block_impl<kBf16Out, false>(acc, ts, Dv, ldd, accumulate, row0, col0, rows, cols, lane);
 }
 
 }  // namespace nvfp4

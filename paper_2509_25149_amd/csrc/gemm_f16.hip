@@ -177,7 +177,7 @@ __global__ __launch_bounds__(kThreads) void gemm_f16_kernel(const _Float16* __re
                                                             const float* __restrict__ b_ts, void* __restrict__ Dv,
                                                             int64_t ldd, bool accumulate, int tiles_m, int tiles_n,
                                                             int tile_begin, int tile_count, int k_splits, float* partials,
-                                                            unsigned int* tickets) {
+                                                            unsigned int* tickets, bool a_ts_per_row, bool b_ts_per_row) {
   extern __shared__ __attribute__((aligned(16))) char lds[];
 
   // Workgroup -> tile: consecutive ids go to different XCDs (round robin over 8, one L2 each);
@@ -317,7 +317,7 @@ __global__ __launch_bounds__(kThreads) void gemm_f16_kernel(const _Float16* __re
   }
 
   // Tensor-level decode scales on the finished sums (App. B.3, after Eq. 5).
-  const float out_scale = a_ts[0] * b_ts[0];
+  const TensorScales out_scale{a_ts, b_ts, a_ts_per_row, b_ts_per_row};
   const int Mt = static_cast<int>(M - m0 < TM ? M - m0 : TM);
   const int Nt = static_cast<int>(N - n0 < TN ? N - n0 : TN);
   store_wave_block<kBf16Out>(acc, out_scale, Dv, ldd, accumulate, m0 + wm * 128, n0 + wn * 128, Mt - wm * 128, Nt - wn * 128,
@@ -372,7 +372,7 @@ bool gemm_two_pass_usable(const GemmArgs& g) {
     if (e != hipSuccess) return e;                                                                                \
     hipLaunchKernelGGL((gemm_f16_kernel<BF16>), dim3(wgs), dim3(kThreads), kLdsBytes, s, a16, b16,                   \
                        g.a.outer, g.b.outer, g.K, g.a.ts, g.b.ts, g.d, g.ldd, g.accumulate, tiles_m, tiles_n,     \
-                       tile_begin, tile_count, k_splits, partials, tickets);                                      \
+                       tile_begin, tile_count, k_splits, partials, tickets, g.a.ts_per_row != 0, g.b.ts_per_row != 0);    \
   } while (0)
 
 static hipError_t launch_f16(bool bf16_out, const _Float16* a16, const _Float16* b16, const GemmArgs& g, int tiles_m,

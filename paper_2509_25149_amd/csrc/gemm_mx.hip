@@ -248,7 +248,7 @@ __global__ __launch_bounds__(kThreads) void gemm_mx_kernel_any_k(Operand A, Oper
   // statements to insert these wait states itself).
   asm volatile("s_waitcnt vmcnt(0)\n\ts_nop 15\n\ts_nop 15" ::: "memory");
 
-  const float out_scale = A.ts[0] * B.ts[0];    // both are 1 for MXFP4 (no tensor-level scale)
+  const TensorScales out_scale{A.ts, B.ts, false, false};    // both are 1 for MXFP4 (no tensor-level scale)
   const int Mt = static_cast<int>(A.outer - m0 < TM ? A.outer - m0 : TM);
   const int Nt = static_cast<int>(B.outer - n0 < TN ? B.outer - n0 : TN);
   store_wave_block<kBf16Out>(acc, out_scale, Dv, ldd, accumulate, m0 + wm * 128, n0 + wn * 128, Mt - wm * 128, Nt - wn * 128,
@@ -403,7 +403,7 @@ __global__ __launch_bounds__(kThreads) void gemm_mx_kernel_k512(Operand A, Opera
   }
   asm volatile("s_waitcnt vmcnt(0)\n\ts_nop 15\n\ts_nop 15" ::: "memory");
 
-  const float out_scale = A.ts[0] * B.ts[0];    // both are 1 for MXFP4 (no tensor-level scale)
+  const TensorScales out_scale{A.ts, B.ts, false, false};    // both are 1 for MXFP4 (no tensor-level scale)
   const int Mt = static_cast<int>(A.outer - m0 < TM ? A.outer - m0 : TM);
   const int Nt = static_cast<int>(B.outer - n0 < TN ? B.outer - n0 : TN);
   store_wave_block<kBf16Out>(acc, out_scale, Dv, ldd, accumulate, m0 + wm * 128, n0 + wn * 128, Mt - wm * 128, Nt - wn * 128,

@@ -30,6 +30,8 @@ struct QuantizeArgs {
   int64_t rows, cols, ld;
   bool want_row, want_col, rht, sr, block2d;
   bool row_rht = false;    // the row copy is rotated too (16-point, along the columns); sign_mask then holds the 16 signs
+  bool scale_per_row = false;   // one tensor-level scale per row of each copy (App. B.1, last sentence); row_ts / col_ts
+                                // then hold 2 * outer floats, ws the words of quantize_rowscale_workspace_words
   int rht_dim;             // 0, or the rotation size: 2, 4, 16, 32, 128 (NVFP4); 32 (MXFP4)
   uint32_t sign_mask;      // the sign diagonal: d <= 16: its d bits repeated over the low 16 bits; 32: its 32 bits
   uint32_t sign_words[4];  // the sign diagonal's bits, first rht_dim of the 128 meaningful
@@ -52,6 +54,9 @@ hipError_t launch_quantize_wide(const QuantizeArgs& a, hipStream_t s);
 hipError_t launch_quantize_rowrot(const QuantizeArgs& a, hipStream_t s);
 // MXFP4 mode (1x32 blocks, UE8M0 scales, one pass, no workspace); sign_mask holds 32 bits
 hipError_t launch_quantize_mx(const QuantizeArgs& a, hipStream_t s);
+// NVFP4 with one tensor-level scale per row of each copy (1x16 blocks, col copy plain or rotated with d = 16)
+hipError_t launch_quantize_rowscale(const QuantizeArgs& a, hipStream_t s);
+size_t quantize_rowscale_workspace_words(int64_t rows, int64_t cols);
 size_t quantize_workspace_bytes(int64_t rows, int64_t cols);
 
 // One K-contiguous operand: codes [outer, K/2], scales [outer, K/16], ts = {s_dec, amax}.
@@ -60,6 +65,7 @@ struct Operand {
   const uint8_t* scales;
   const float* ts;
   int64_t outer;
+  int ts_per_row = 0;   // 0: ts = {s_dec, amax}; 1: ts = s_dec of every row, then the amax of every row (App. B.1, last sentence)
 };
 struct GemmArgs {
   Operand a, b;  // D[m, n] = sum_k A[m, k] B[n, k]

@@ -84,16 +84,17 @@ __global__ __launch_bounds__(kThreads, 2) void cast_kernel(
     const uint16_t* __restrict__ x, int64_t rows, int64_t cols, int64_t ld,
     const uint32_t* __restrict__ ws, uint32_t sign_mask, uint32_t key0, uint32_t key1,
     uint8_t* __restrict__ row_codes, uint8_t* __restrict__ row_scales, float* __restrict__ row_ts,
-    uint8_t* __restrict__ col_codes, uint8_t* __restrict__ col_scales, float* __restrict__ col_ts) {
+    uint8_t* __restrict__ col_codes, uint8_t* __restrict__ col_scales, float* __restrict__ col_ts, int reverse) {
   __shared__ __attribute__((aligned(16))) uint8_t st_col_codes[kCol ? kColCodesBytes : 16];
   __shared__ __attribute__((aligned(16))) uint8_t st_col_scales[kCol ? kColScalesBytes : 16];
   __shared__ __attribute__((aligned(16))) uint8_t st_row_scales[kRow ? kRowScalesBytes : 16];
   __shared__ float lut_row[128], lut_col[128];  // block encode scale per stored E4M3 code
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int64_t colblk = static_cast<int64_t>(blockIdx.x) * kWaveCols;
+  const unsigned bx = reverse ? gridDim.x - 1 - blockIdx.x : blockIdx.x, by = reverse ? gridDim.y - 1 - blockIdx.y : blockIdx.y;
+  const int64_t colblk = static_cast<int64_t>(bx) * kWaveCols;
   const int64_t col0 = colblk + lane * 8;
-  const int64_t group0 = static_cast<int64_t>(blockIdx.y) * kGroupsPerBlock;
+  const int64_t group0 = static_cast<int64_t>(by) * kGroupsPerBlock;
   const int64_t ngroups = rows / 16;
 
   // App. B.1 Eq. 1, from the amax of pass 1.
@@ -102,7 +103,7 @@ __global__ __launch_bounds__(kThreads, 2) void cast_kernel(
   float s_enc_r, s_dec_r, s_enc_c, s_dec_c;
   tensor_scales(amax_raw, s_enc_r, s_dec_r);
   tensor_scales(amax_col, s_enc_c, s_dec_c);
-  if (blockIdx.x == 0 && blockIdx.y == 0 && tid == 0) {
+  if (bx == 0 && by == 0 && tid == 0) {
     if (kRow) { row_ts[0] = s_dec_r; row_ts[1] = amax_raw; }
     if (kCol) { col_ts[0] = s_dec_c; col_ts[1] = amax_col; }
   }
@@ -178,14 +179,22 @@ __global__ __launch_bounds__(kThreads, 2) void cast_kernel(
 
 size_t quantize_workspace_bytes(int64_t rows, int64_t cols) {
   const int64_t gx = (cols + kWaveCols - 1) / kWaveCols, gy = (rows / 16 + kGroupsPerBlock - 1) / kGroupsPerBlock;
-  return static_cast<size_t>(kWsHeader + 3 * gx * gy) * sizeof(uint32_t);   // raw, col-rotated, row-rotated maxima
+  // raw, col-rotated, row-rotated maxima per workgroup; or, with one scale per row of each copy, amax and encode scale
+  // per row and per column
+  const size_t per_tensor = static_cast<size_t>(kWsHeader + 3 * gx * gy), per_row = quantize_rowscale_workspace_words(rows, cols);
+  return (per_tensor > per_row ? per_tensor : per_row) * sizeof(uint32_t);
 }
+
+// The cast pass walks a large tensor from its end: the amax pass has just streamed it front to back, so its tail is
+// what the 256 MB memory-side cache still holds (measured at the 12B shapes: W 124 -> 121 us, dY 250 -> 245 us per
+// call; a tensor that fits the cache whole gains nothing either way).
+static int cast_reverse(const QuantizeArgs& a) { return a.do_amax && a.rows * a.cols * 2 > (int64_t{128} << 20); }
 
 template <bool kRow, bool kCol, int kRht, bool kSR, bool k2D>
 static void launch_cast(const QuantizeArgs& a, dim3 grid, hipStream_t s) {
   hipLaunchKernelGGL((cast_kernel<kRow, kCol, kRht, kSR, k2D>), grid, dim3(kThreads), 0, s,
                      static_cast<const uint16_t*>(a.x), a.rows, a.cols, a.ld, a.ws, a.sign_mask, a.key0,
-                     a.key1, a.row_codes, a.row_scales, a.row_ts, a.col_codes, a.col_scales, a.col_ts);
+                     a.key1, a.row_codes, a.row_scales, a.row_ts, a.col_codes, a.col_scales, a.col_ts, cast_reverse(a));
 }
 
 template <bool kRow, bool kCol, int kRht>
@@ -213,6 +222,7 @@ hipError_t launch_quantize(const QuantizeArgs& a, hipStream_t s) {
   const dim3 grid(static_cast<unsigned>((a.cols + kWaveCols - 1) / kWaveCols),
                   static_cast<unsigned>((a.rows / 16 + kGroupsPerBlock - 1) / kGroupsPerBlock));
   const int rht = a.want_col ? a.rht_dim : 0;
+  if (a.scale_per_row) return launch_quantize_rowscale(a, s);
   if (a.row_rht) return launch_quantize_rowrot(a, s);
   if (rht > 16) return launch_quantize_wide(a, s);
   if (rht) {

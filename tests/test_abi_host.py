@@ -44,11 +44,12 @@ def test_struct_layout_matches_header(tmp_path):
     assert out[0] == ctypes.sizeof(nv.QTensorStruct)
     assert out[1:] == [getattr(nv.QTensorStruct, f).offset for f in fields]
     assert nv.QTensorStruct.rht_seed.offset == 80 and nv.QTensorStruct.row_has_rht.offset == 88
+    assert nv.QTensorStruct.scale_per_row.offset == 92 and ctypes.sizeof(nv.QTensorStruct) == 96
 
 
 def test_sizes(lib):
     assert nv.quantized_sizes(256, 512)[:2] == (256 * 512 // 2, 256 * 512 // 16)
-    assert 64 <= nv.quantized_sizes(256, 512)[2] <= 4096
+    assert 64 <= nv.quantized_sizes(256, 512)[2] <= 8192          # small: a few words per workgroup tile, or per row and column
     assert nv.quantized_sizes(8192, 20480)[2] >= 2 * 40 * 64 * 4
     for bad in ((0, 16), (16, 0), (24, 16), (16, 40), (-16, 16)):
         with pytest.raises(nv.NVFP4Error) as e:
@@ -285,3 +286,24 @@ def test_quantize_static_rejects_before_touching_the_gpu(lib):
     header = open(os.path.join(ROOT, "include", "nvfp4.h")).read()
     assert "NVFP4_STATIC_SCRATCH_BYTES = 1 << 20" in header and nv.STATIC_SCRATCH_BYTES == 1 << 20
 
+
+def test_row_scale_mode_argument_checks(lib):
+    """NVFP4_LAYOUT_ROW_SCALES (8): 1x16 blocks, rotation 0 / 16, no rotated row copy, no supplied amax."""
+    X, OUT, WS = 0x10000, 0x20000, 0x30000
+    d = _desc()
+    for f in ("row_codes", "row_scales", "row_tensor_scale", "col_codes", "col_scales", "col_tensor_scale"):
+        setattr(d, f, OUT)
+    tail = (ctypes.byref(d), WS, 1 << 20, None)
+    assert lib.nvfp4_quantize(X, 16, 16, 16, 3 | 8, 16, 0, 0, 0, 0, *tail) == -1      # 16x16 blocks
+    assert lib.nvfp4_quantize(X, 32, 32, 32, 3 | 8, 32, 0, 0, 0, 0, *tail) == -1      # MXFP4
+    assert lib.nvfp4_quantize(X, 16, 16, 16, 3 | 8, 1, 0, 4, 0, 0, *tail) == -1       # 4-point rotation
+    assert lib.nvfp4_quantize(X, 16, 16, 16, 1 | 4 | 8, 1, 0, 0, 0, 0, *tail) == -1   # rotated row copy
+    assert lib.nvfp4_quantize(X, 16, 16, 16, 8, 1, 0, 0, 0, 0, *tail) == -1           # no copy asked for
+    assert lib.nvfp4_quantize(X, 16, 24, 24, 1 | 8, 1, 0, 0, 0, 0, *tail) == -2
+    amax = 0x40000
+    assert lib.nvfp4_quantize_with_amax(X, 16, 16, 16, 1 | 8, 1, 0, 0, 0, 0, amax, ctypes.byref(d), None) == -1
+    # the workspace query covers the per-row mode: amax and encode scale per row and per column
+    need = ctypes.c_size_t()
+    assert lib.nvfp4_quantized_sizes(8192, 20480, None, None, ctypes.addressof(need)) == 0
+    assert need.value >= 2 * (8192 + 20480) * 4
+    assert lib.nvfp4_quantize(X, 8192, 20480, 20480, 3 | 8, 1, 0, 0, 0, 0, ctypes.byref(d), WS, need.value - 1, None) == -6
