@@ -315,6 +315,54 @@ def row_scale_block(torch, nv, sets, qw, gemm_ws, iters: int = 6):
     return res
 
 
+def micro_batch_block(torch, nv, sets, gemm_ws, n_micro: int = 4, iters: int = 4):
+    """One optimizer step of n_micro micro-batches (Sec. 4.1: weight gradients accumulate over micro-batches in FP32): W is
+    quantized once and serves every Fprop and Dgrad (Sec. 4.3).  With nvfp4_predecode its two copies are also decoded to
+    FP16 once instead of inside every nvfp4_gemm call.  Outside the timed region of `value`."""
+    RC = nv.LAYOUT_ROW | nv.LAYOUT_COL
+    qw = nv.alloc_qtensor(D_MODEL, D_FFN, RC)
+    qx = nv.alloc_qtensor(TOKENS, D_MODEL, RC)
+    qdy = nv.alloc_qtensor(TOKENS, D_FFN, RC)
+    y = torch.empty((TOKENS, D_FFN), dtype=torch.bfloat16, device="cuda")
+    dx = torch.empty((TOKENS, D_MODEL), dtype=torch.bfloat16, device="cuda")
+    dw = torch.zeros((D_MODEL, D_FFN), dtype=torch.float32, device="cuda")
+    w16 = [torch.empty((D_FFN, D_MODEL), dtype=torch.float16, device="cuda"), torch.empty((D_MODEL, D_FFN), dtype=torch.float16, device="cuda")]
+
+    def optimizer_step(predecode: bool, it: int):
+        nv.nvfp4_quantize(sets[0][1], RC, nv.BLOCK_16x16, nv.ROUND_RNE, False, 0, 0, out=qw)
+        if predecode:
+            nv.nvfp4_predecode(qw, nv.COPY_COL, out=w16[0])
+            nv.nvfp4_predecode(qw, nv.COPY_ROW, out=w16[1])
+        for mb in range(n_micro):
+            x, _, dy = sets[(it + mb) % len(sets)]
+            nv.nvfp4_quantize(x, RC, nv.BLOCK_1x16, nv.ROUND_RNE, True, 2025, 0, out=qx)
+            nv.nvfp4_gemm(qx, qw, nv.OP_FPROP, nv.OUT_BF16, out=y, workspace=gemm_ws)
+            nv.nvfp4_quantize(dy, RC, nv.BLOCK_1x16, nv.ROUND_SR, True, 2025, 99 + it * n_micro + mb, out=qdy)
+            nv.nvfp4_gemm(qdy, qw, nv.OP_DGRAD, nv.OUT_BF16, out=dx, workspace=gemm_ws)
+            nv.nvfp4_gemm(qx, qdy, nv.OP_WGRAD, nv.OUT_F32 if mb == 0 else nv.OUT_F32_ACCUMULATE, out=dw, workspace=gemm_ws)
+
+    res = {}
+    for predecode in (False, True):
+        ms = []
+        for it in range(iters + 1):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            optimizer_step(predecode, it)
+            b.record()
+            torch.cuda.synchronize()
+            if it:
+                ms.append(a.elapsed_time(b))
+        ms.sort()
+        med = ms[len(ms) // 2]
+        res["weight_decoded_once" if predecode else "weight_decoded_in_every_gemm_call"] = {
+            "ms_per_optimizer_step_median": med, "ms_per_micro_batch": med / n_micro,
+            "TFLOPs": n_micro * 3 * 2.0 * TOKENS * D_MODEL * D_FFN / (med * 1e-3) / 1e12}
+    res["micro_batches"] = n_micro
+    res["note"] = ("not part of `value`: quantize W once, then per micro-batch quantize X, Fprop, quantize dY, Dgrad, Wgrad added "
+                   "into one FP32 dW; second entry: W's two copies decoded to FP16 once by nvfp4_predecode")
+    return res
+
+
 def matrix_pipe_context(torch, nv, reps: int = 3, iters: int = 100000):
     """What the FP16 matrix pipe sustains on this machine, measured beside the step: bench_probe.hip's register-only MFMA
     loop (no memory traffic) per operand kind, and the vendor library's FP16 GEMM (torch.matmul) at the Fprop shape on
@@ -349,7 +397,7 @@ def matrix_pipe_context(torch, nv, reps: int = 3, iters: int = 100000):
     return res
 
 
-def layer_calls_block(torch, nv, sets, qw, gemm_ws_bytes, iters: int = 6):
+def layer_calls_block(torch, nv, sets, qw, gemm_ws_bytes, iters: int = 10):
     """The same layer step issued through the two per-layer entry points (nvfp4_linear_forward / nvfp4_linear_backward:
     every step validated up front, one shared workspace), eagerly and as a replayed HIP graph.  W is quantized
     outside, once, as the entry points expect (its cost is reported on its own).  Outside the timed region of `value`."""
@@ -369,15 +417,13 @@ def layer_calls_block(torch, nv, sets, qw, gemm_ws_bytes, iters: int = 6):
     def timed(fn):
         fn()
         torch.cuda.synchronize()
-        ms = []
-        for _ in range(iters):
-            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            a.record()
+        marks = [torch.cuda.Event(enable_timing=True) for _ in range(iters + 1)]
+        marks[0].record()
+        for i in range(iters):                      # back to back, like the timed steps of `value`
             fn()
-            b.record()
-            torch.cuda.synchronize()
-            ms.append(a.elapsed_time(b))
-        ms.sort()
+            marks[i + 1].record()
+        torch.cuda.synchronize()
+        ms = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(iters))
         return {"ms_median": ms[len(ms) // 2], "ms_min": ms[0]}
 
     res = {"eager": timed(layer_step)}
@@ -571,6 +617,8 @@ def main() -> int:
         out["layer_calls"] = layer_calls_block(torch, nv, sets, bufs[0]["qw"], gemm_ws_bytes)
         out["layer_calls"]["separate_calls_same_work_ms"] = (step_ms[len(step_ms) // 2] - q_med[1]
                                                              - sorted(a.elapsed_time(b) for a, b in deq_events)[len(deq_events) // 2])
+    if not args.no_layer_calls:
+        out["micro_batches"] = micro_batch_block(torch, nv, sets, gemm_ws)
     if not args.no_row_scales:
         out["row_scale_mode"] = row_scale_block(torch, nv, sets, bufs[0]["qw"], gemm_ws)
     if not args.no_mxfp4:

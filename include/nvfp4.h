@@ -123,6 +123,8 @@ typedef struct nvfp4_qtensor {
   uint64_t rht_seed;        /* seed of the sign diagonal, if rotated */
   int32_t row_has_rht;      /* 0, or 16: the row copy is rotated along its columns (NVFP4_LAYOUT_ROW_RHT) */
   int32_t scale_per_row;    /* 0: tensor_scale is float[2]; 1: float[2 * outer] per copy (NVFP4_LAYOUT_ROW_SCALES) */
+  void* row_fp16;           /* NULL, or the row copy decoded to FP16 by nvfp4_predecode: [rows, cols] */
+  void* col_fp16;           /* NULL, or the col copy decoded to FP16 by nvfp4_predecode: [cols, rows] */
 } nvfp4_qtensor;
 
 /*
@@ -236,6 +238,21 @@ int nvfp4_quantize_with_amax(const void* x, int64_t rows, int64_t cols, int64_t 
  */
 int nvfp4_gemm(const nvfp4_qtensor* a, const nvfp4_qtensor* b, int op, void* d, int out_dtype,
                int64_t ldd, void* workspace, size_t workspace_bytes, nvfp4_stream_t stream);
+
+/*
+ * Decode one copy of an NVFP4 tensor to FP16 once (value * block scale, exact), for the nvfp4_gemm calls that follow.
+ * A weight is quantized once per optimizer step and then serves Fprop and Dgrad of every micro-batch (Sec. 4.3: the
+ * same quantized weight in both passes; Sec. 4.1: gradients accumulate over micro-batches): without this every
+ * nvfp4_gemm call on its two-pass route decodes the operand again.
+ *   q           host descriptor of a quantized NVFP4 tensor (not MXFP4); on success its row_fp16 / col_fp16 field
+ *               is set to fp16_out, and nvfp4_gemm reads that instead of decoding (its workspace then only has to
+ *               hold the operands still to decode, the counters and the partial tiles)
+ *   fp16_out    device, 16-byte aligned, outer * K * 2 bytes ([rows, cols] for the row copy, [cols, rows] for the col
+ *               copy, K-contiguous); owned by the caller, must stay valid while the descriptor points to it
+ *   fp16_bytes  its size; NVFP4_ERR_WORKSPACE if too small
+ * nvfp4_quantize into the same descriptor clears both fields (the codes change), as does any call that rewrites it.
+ */
+int nvfp4_predecode(nvfp4_qtensor* q, int which_copy, void* fp16_out, size_t fp16_bytes, nvfp4_stream_t stream);
 
 /* Scratch bytes that let nvfp4_gemm take its faster two-pass route (host pointer out):
  * (M + N) * K * 2 for the FP16 operands, 1 KiB of counters, and up to 64 MiB of FP32 partial

@@ -28,7 +28,7 @@ COPY_ROW, COPY_COL = 0, 1
 EXPORTS = ["nvfp4_quantized_sizes", "nvfp4_quantize", "nvfp4_gemm", "nvfp4_gemm_workspace_bytes", "nvfp4_dequantize",
            "nvfp4_rht_sign_mask", "nvfp4_selftest_conversions", "nvfp4_status_string", "nvfp4_version",
            "nvfp4_linear_workspace_bytes", "nvfp4_linear_forward", "nvfp4_linear_backward",
-           "nvfp4_amax", "nvfp4_quantize_with_amax", "nvfp4_quantize_static"]
+           "nvfp4_amax", "nvfp4_quantize_with_amax", "nvfp4_quantize_static", "nvfp4_predecode"]
 STATIC_SCRATCH_BYTES = 1 << 20
 
 
@@ -41,7 +41,8 @@ class QTensorStruct(ctypes.Structure):
                 ("col_tensor_scale", ctypes.c_void_p),
                 ("layout_mask", ctypes.c_int32), ("block_dim", ctypes.c_int32),
                 ("rounding", ctypes.c_int32), ("col_has_rht", ctypes.c_int32),
-                ("rht_seed", ctypes.c_uint64), ("row_has_rht", ctypes.c_int32), ("scale_per_row", ctypes.c_int32)]
+                ("rht_seed", ctypes.c_uint64), ("row_has_rht", ctypes.c_int32), ("scale_per_row", ctypes.c_int32),
+                ("row_fp16", ctypes.c_void_p), ("col_fp16", ctypes.c_void_p)]
 
 
 _lib = None
@@ -70,6 +71,8 @@ def load_library() -> ctypes.CDLL:
         L.nvfp4_gemm.restype = ci
         L.nvfp4_gemm.argtypes = [ctypes.POINTER(QTensorStruct), ctypes.POINTER(QTensorStruct), ci, vp, ci, i64,
                                  vp, ctypes.c_size_t, vp]
+        L.nvfp4_predecode.restype = ci
+        L.nvfp4_predecode.argtypes = [ctypes.POINTER(QTensorStruct), ci, vp, ctypes.c_size_t, vp]
         L.nvfp4_gemm_workspace_bytes.restype = ci
         L.nvfp4_gemm_workspace_bytes.argtypes = [i64, i64, i64, vp]
         qp = ctypes.POINTER(QTensorStruct)
@@ -132,6 +135,8 @@ class QTensor:
     col_codes: Optional[torch.Tensor] = None
     col_scales: Optional[torch.Tensor] = None
     col_ts: Optional[torch.Tensor] = None
+    row_fp16: Optional[torch.Tensor] = None     # decoded copies (nvfp4_predecode); kept alive here while the descriptor points to them
+    col_fp16: Optional[torch.Tensor] = None
 
 
 def alloc_qtensor(rows: int, cols: int, layout_mask: int, device="cuda", block_dim: int = BLOCK_1x16) -> QTensor:
@@ -179,6 +184,7 @@ def nvfp4_quantize(x: torch.Tensor, layout_mask: int, block_dim: int = BLOCK_1x1
     _check(load_library().nvfp4_quantize(x.data_ptr(), rows, cols, x.stride(0), layout_mask, block_dim, rounding,
                                          int(rht_on_col), rht_seed, sr_seed, ctypes.byref(out.desc),
                                          ws.data_ptr(), ws.numel(), _stream()))
+    out.row_fp16 = out.col_fp16 = None          # the library cleared the descriptor's pointers: the codes changed
     return out
 
 
@@ -222,6 +228,23 @@ def nvfp4_quantize_with_amax(x: torch.Tensor, amax: torch.Tensor, layout_mask: i
     _check(load_library().nvfp4_quantize_with_amax(x.data_ptr(), rows, cols, x.stride(0), layout_mask, block_dim, rounding,
                                                    int(rht_on_col), rht_seed, sr_seed, amax.data_ptr(),
                                                    ctypes.byref(out.desc), _stream()))
+    return out
+
+
+def nvfp4_predecode(q: QTensor, which_copy: int, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Decode one copy to FP16 once; later nvfp4_gemm calls on `q` read it instead of decoding again.  Returns the
+    float16 CUDA tensor [outer, K], which `q` keeps alive."""
+    outer, inner = (q.cols, q.rows) if which_copy == COPY_COL else (q.rows, q.cols)
+    if out is None:
+        dev = (q.row_codes if q.row_codes is not None else q.col_codes).device
+        out = torch.empty((outer, inner), dtype=torch.float16, device=dev)
+    if not out.is_cuda or out.dtype != torch.float16 or not out.is_contiguous():
+        raise ValueError("out must be a contiguous float16 CUDA tensor")
+    _check(load_library().nvfp4_predecode(ctypes.byref(q.desc), which_copy, out.data_ptr(), out.numel() * 2, _stream()))
+    if which_copy == COPY_COL:
+        q.col_fp16 = out
+    else:
+        q.row_fp16 = out
     return out
 
 

@@ -192,6 +192,8 @@ int plan_quantize(const void* x, int64_t rows, int64_t cols, int64_t ld, int lay
   p->desc.col_has_rht = rht_dim;
   p->desc.row_has_rht = row_rht ? 16 : 0;
   p->desc.scale_per_row = scale_per_row ? 1 : 0;
+  p->desc.row_fp16 = nullptr;   // decoded copies of the previous contents are stale
+  p->desc.col_fp16 = nullptr;
   p->desc.rht_seed = (a.rht || row_rht) ? rht_seed : 0;
   return NVFP4_OK;
 }
@@ -303,6 +305,7 @@ static int pick_operand(const nvfp4_qtensor* q, bool col_copy, Operand* op, int6
     op->scales = static_cast<const uint8_t*>(q->col_scales);
     op->ts = q->col_tensor_scale;
     op->outer = q->cols;
+    op->fp16 = q->col_fp16;
     op->ts_per_row = q->scale_per_row ? 1 : 0;
     *K = q->rows;
   } else {
@@ -312,9 +315,26 @@ static int pick_operand(const nvfp4_qtensor* q, bool col_copy, Operand* op, int6
     op->scales = static_cast<const uint8_t*>(q->row_scales);
     op->ts = q->row_tensor_scale;
     op->outer = q->rows;
+    op->fp16 = q->row_fp16;
     op->ts_per_row = q->scale_per_row ? 1 : 0;
     *K = q->cols;
   }
+  return NVFP4_OK;
+}
+
+int nvfp4_predecode(nvfp4_qtensor* q, int which_copy, void* fp16_out, size_t fp16_bytes, nvfp4_stream_t stream) {
+  if (!q || !fp16_out || !aligned(fp16_out, 16)) return NVFP4_ERR_INVALID_ARG;
+  if (which_copy != NVFP4_COPY_ROW && which_copy != NVFP4_COPY_COL) return NVFP4_ERR_INVALID_ARG;
+  if (q->block_dim == NVFP4_BLOCK_MX32) return NVFP4_ERR_INVALID_ARG;   // MXFP4 operands feed the matrix pipe as they are
+  Operand op;
+  int64_t K = 0;
+  const int rc = pick_operand(q, which_copy == NVFP4_COPY_COL, &op, &K);
+  if (rc != NVFP4_OK) return rc;
+  if (K <= 0 || K % 16 || op.outer <= 0) return NVFP4_ERR_BAD_SHAPE;
+  if (!aligned(op.codes, 4) || !aligned(op.scales, 1)) return NVFP4_ERR_INVALID_ARG;
+  if (fp16_bytes < static_cast<size_t>(op.outer) * static_cast<size_t>(K) * 2) return NVFP4_ERR_WORKSPACE;
+  if (launch_predecode(op, K, fp16_out, static_cast<hipStream_t>(stream)) != hipSuccess) return NVFP4_ERR_HIP;
+  if (which_copy == NVFP4_COPY_COL) q->col_fp16 = fp16_out; else q->row_fp16 = fp16_out;
   return NVFP4_OK;
 }
 

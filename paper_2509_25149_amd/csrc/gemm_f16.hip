@@ -347,8 +347,10 @@ static TailPlan plan_tail(int64_t M, int64_t N, int64_t K) {
   return p;
 }
 
-static size_t operand_bytes(int64_t M, int64_t N, int64_t K) {
-  const size_t b = static_cast<size_t>(M + N) * static_cast<size_t>(K) * 2;
+// FP16 bytes of the operands that still have to be decoded into the workspace (rows_a / rows_b: 0 for an operand the
+// caller has decoded beforehand)
+static size_t operand_bytes(int64_t rows_a, int64_t rows_b, int64_t K) {
+  const size_t b = static_cast<size_t>(rows_a + rows_b) * static_cast<size_t>(K) * 2;
   return (b + 255) & ~static_cast<size_t>(255);
 }
 
@@ -357,8 +359,15 @@ size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t K) {
   return operand_bytes(M, N, K) + kTicketBytes + static_cast<size_t>(p.tail) * p.splits * kPartialTileBytes;
 }
 
+static size_t workspace_need(const GemmArgs& g) {
+  const TailPlan p = plan_tail(g.a.outer, g.b.outer, g.K);
+  return operand_bytes(g.a.fp16 ? 0 : g.a.outer, g.b.fp16 ? 0 : g.b.outer, g.K) + kTicketBytes +
+         static_cast<size_t>(p.tail) * p.splits * kPartialTileBytes;
+}
+
 bool gemm_two_pass_usable(const GemmArgs& g) {
-  return g.workspace && g.workspace_bytes >= gemm_workspace_bytes(g.a.outer, g.b.outer, g.K) && (g.K % TK) == 0 &&
+  return g.workspace && g.workspace_bytes >= workspace_need(g) && (g.K % TK) == 0 &&
+         reinterpret_cast<uintptr_t>(g.a.fp16) % 16 == 0 && reinterpret_cast<uintptr_t>(g.b.fp16) % 16 == 0 &&
          g.K < (int64_t{1} << 21) &&   // the kernel's 32-bit byte offsets inside a 256-row tile
          reinterpret_cast<uintptr_t>(g.workspace) % 256 == 0 && reinterpret_cast<uintptr_t>(g.a.codes) % 16 == 0 &&
          reinterpret_cast<uintptr_t>(g.b.codes) % 16 == 0 && reinterpret_cast<uintptr_t>(g.a.scales) % 2 == 0 &&
@@ -384,16 +393,31 @@ static hipError_t launch_f16(bool bf16_out, const _Float16* a16, const _Float16*
 }
 #undef NVFP4_LAUNCH_F16
 
+hipError_t launch_predecode(const Operand& op, int64_t K, void* fp16_out, hipStream_t s) {
+  const int64_t n8 = op.outer * K / 8;
+  hipLaunchKernelGGL(decode_f16_kernel, dim3(static_cast<unsigned>((n8 + 256 * kDecodeUnroll - 1) / (256 * kDecodeUnroll))), dim3(256), 0, s,
+                     op.codes, op.scales, n8, static_cast<_Float16*>(fp16_out), op.codes, op.scales, int64_t{0},
+                     static_cast<_Float16*>(fp16_out), static_cast<unsigned int*>(nullptr));
+  return hipGetLastError();
+}
+
 hipError_t launch_gemm_two_pass(const GemmArgs& g, hipStream_t s) {
   const int64_t M = g.a.outer, N = g.b.outer, K = g.K;
+  // Workspace: [A as FP16 unless decoded beforehand][B likewise][tickets][partial tiles]
   char* ws = static_cast<char*>(g.workspace);
-  _Float16* a16 = reinterpret_cast<_Float16*>(ws);
-  _Float16* b16 = a16 + M * K;
-  unsigned int* tickets = reinterpret_cast<unsigned int*>(ws + operand_bytes(M, N, K));
-  float* partials = reinterpret_cast<float*>(ws + operand_bytes(M, N, K) + kTicketBytes);
-  const int64_t na = M * K / 8, nb = N * K / 8;   // a_n8 is a multiple of 256 only if M*K is a multiple of 2048; the kernel does not need it
-  hipLaunchKernelGGL(decode_f16_kernel, dim3(static_cast<unsigned>((na + nb + 256 * kDecodeUnroll - 1) / (256 * kDecodeUnroll))), dim3(256), 0, s, g.a.codes,
-                     g.a.scales, na, a16, g.b.codes, g.b.scales, nb, b16, tickets);
+  const int64_t rows_a = g.a.fp16 ? 0 : M, rows_b = g.b.fp16 ? 0 : N;
+  _Float16* a_ws = reinterpret_cast<_Float16*>(ws);
+  _Float16* b_ws = a_ws + rows_a * K;
+  const _Float16* a16 = g.a.fp16 ? static_cast<const _Float16*>(g.a.fp16) : a_ws;
+  const _Float16* b16 = g.b.fp16 ? static_cast<const _Float16*>(g.b.fp16) : b_ws;
+  unsigned int* tickets = reinterpret_cast<unsigned int*>(ws + operand_bytes(rows_a, rows_b, K));
+  float* partials = reinterpret_cast<float*>(ws + operand_bytes(rows_a, rows_b, K) + kTicketBytes);
+  // One launch decodes what is still to decode and zeroes the tickets (with both operands decoded beforehand it is one
+  // workgroup that only does the latter).
+  const int64_t na = rows_a * K / 8, nb = rows_b * K / 8;   // a_n8 is a multiple of 256 only if M*K is a multiple of 2048; the kernel does not need it
+  const int64_t nwg = (na + nb + 256 * kDecodeUnroll - 1) / (256 * kDecodeUnroll);
+  hipLaunchKernelGGL(decode_f16_kernel, dim3(static_cast<unsigned>(nwg > 0 ? nwg : 1)), dim3(256), 0, s, g.a.codes,
+                     g.a.scales, na, a_ws, g.b.codes, g.b.scales, nb, b_ws, tickets);
   const int tiles_m = static_cast<int>((M + TM - 1) / TM), tiles_n = static_cast<int>((N + TN - 1) / TN);
   const int tiles = tiles_m * tiles_n;
   // One 256x256 tile keeps one CU busy (its LDS fits one workgroup).  Whole rounds of kCUs tiles

@@ -66,6 +66,7 @@ struct Operand {
   const float* ts;
   int64_t outer;
   int ts_per_row = 0;   // 0: ts = {s_dec, amax}; 1: ts = s_dec of every row, then the amax of every row (App. B.1, last sentence)
+  const void* fp16 = nullptr;   // the copy already decoded to FP16 [outer, K] (nvfp4_predecode), or null
 };
 struct GemmArgs {
   Operand a, b;  // D[m, n] = sum_k A[m, k] B[n, k]
@@ -82,6 +83,8 @@ hipError_t launch_gemm(const GemmArgs& g, hipStream_t s);
 size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
 bool gemm_two_pass_usable(const GemmArgs& g);
 hipError_t launch_gemm_two_pass(const GemmArgs& g, hipStream_t s);
+// Decodes one operand (codes [outer, K/2], scales [outer, K/16]) to FP16 [outer, K]
+hipError_t launch_predecode(const Operand& op, int64_t K, void* fp16_out, hipStream_t s);
 
 struct DequantArgs {
   Operand q;

@@ -44,7 +44,8 @@ def test_struct_layout_matches_header(tmp_path):
     assert out[0] == ctypes.sizeof(nv.QTensorStruct)
     assert out[1:] == [getattr(nv.QTensorStruct, f).offset for f in fields]
     assert nv.QTensorStruct.rht_seed.offset == 80 and nv.QTensorStruct.row_has_rht.offset == 88
-    assert nv.QTensorStruct.scale_per_row.offset == 92 and ctypes.sizeof(nv.QTensorStruct) == 96
+    assert nv.QTensorStruct.scale_per_row.offset == 92 and nv.QTensorStruct.row_fp16.offset == 96
+    assert nv.QTensorStruct.col_fp16.offset == 104 and ctypes.sizeof(nv.QTensorStruct) == 112
 
 
 def test_sizes(lib):
@@ -307,3 +308,18 @@ def test_row_scale_mode_argument_checks(lib):
     assert lib.nvfp4_quantized_sizes(8192, 20480, None, None, ctypes.addressof(need)) == 0
     assert need.value >= 2 * (8192 + 20480) * 4
     assert lib.nvfp4_quantize(X, 8192, 20480, 20480, 3 | 8, 1, 0, 0, 0, 0, ctypes.byref(d), WS, need.value - 1, None) == -6
+
+
+def test_predecode_rejects_bad_arguments(lib):
+    OUT, F16 = 0x20000, 0x80000
+    d = _desc(rows=32, cols=64, mask=1)
+    d.row_codes, d.row_scales, d.row_tensor_scale = OUT, OUT, OUT
+    assert lib.nvfp4_predecode(None, 0, F16, 1 << 20, None) == -1
+    assert lib.nvfp4_predecode(ctypes.byref(d), 0, None, 1 << 20, None) == -1
+    assert lib.nvfp4_predecode(ctypes.byref(d), 2, F16, 1 << 20, None) == -1
+    assert lib.nvfp4_predecode(ctypes.byref(d), 0, F16 + 8, 1 << 20, None) == -1          # 16-byte alignment
+    assert lib.nvfp4_predecode(ctypes.byref(d), 1, F16, 1 << 20, None) == -3              # no col copy
+    assert lib.nvfp4_predecode(ctypes.byref(d), 0, F16, 32 * 64 * 2 - 1, None) == -6      # room for [rows, cols] FP16
+    d.block_dim = 32
+    assert lib.nvfp4_predecode(ctypes.byref(d), 0, F16, 1 << 20, None) == -1              # MXFP4 is not decoded
+    assert d.row_fp16 is None and d.col_fp16 is None                                      # nothing was recorded

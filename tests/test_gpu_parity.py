@@ -414,3 +414,46 @@ def test_quantize_with_a_supplied_amax_matches_the_oracle(factor):
     assert_copy_equal(q.row_codes, q.row_scales, q.row_ts, oracle.quantize(xb, oracle.ROW, amax=float(g[0])), "row copy")
     assert_copy_equal(q.col_codes, q.col_scales, q.col_ts,
                       oracle.quantize(xb, oracle.COL, use_rht=True, rht_seed=5, amax=float(g[1])), "col copy")
+
+
+def test_predecoded_operands_give_the_same_bits():
+    """nvfp4_predecode: a weight decoded to FP16 once serves Fprop and Dgrad of every micro-batch (Sec. 4.3, Sec. 4.1);
+    the GEMM on the decoded copy runs the same kernel on the same FP16 values, so the results are identical.  Shapes
+    with a split-K last round; a workspace sized only for the operands still to decode must be enough."""
+    tokens, d_in, d_out = 4352, 1024, 4096
+    wb = synth.normal(d_in, d_out, 0.02, 2101)
+    qw = nv.nvfp4_quantize(to_dev(wb), nv.LAYOUT_ROW | nv.LAYOUT_COL, nv.BLOCK_16x16)
+    qx = nv.nvfp4_quantize(to_dev(synth.normal_with_outliers(tokens, d_in, 1.0, 2102)), nv.LAYOUT_ROW | nv.LAYOUT_COL,
+                           rht_on_col=True, rht_seed=3)
+    qdy = nv.nvfp4_quantize(to_dev(synth.student_t3(tokens, d_out, 1e-3, 2103)), nv.LAYOUT_ROW | nv.LAYOUT_COL,
+                            rounding=nv.ROUND_SR, rht_on_col=True, rht_seed=3, sr_seed=5)
+    ws = gemm_ws(tokens, d_out, d_in)
+    ws2 = gemm_ws(tokens, d_in, d_out)
+    y0 = nv.nvfp4_gemm(qx, qw, nv.OP_FPROP, nv.OUT_F32, workspace=ws)
+    dx0 = nv.nvfp4_gemm(qdy, qw, nv.OP_DGRAD, nv.OUT_F32, workspace=ws2)
+    w_col16 = nv.nvfp4_predecode(qw, nv.COPY_COL)
+    w_row16 = nv.nvfp4_predecode(qw, nv.COPY_ROW)
+    assert w_col16.shape == (d_out, d_in) and w_row16.shape == (d_in, d_out)
+    # the decoded copy is value * block scale (no tensor scale): times s_dec it is the dequantized tensor, up to FP32 rounding
+    deq = nv.nvfp4_dequantize(qw, nv.COPY_COL)
+    assert torch.allclose(w_col16.float() * qw.col_ts[0], deq, rtol=1e-6, atol=0)
+    # less scratch is enough now: only X (or dY), the counters and the partial tiles
+    small = torch.empty(nv.gemm_workspace_bytes(tokens, d_out, d_in) - d_out * d_in * 2, dtype=torch.uint8, device="cuda")
+    y1 = nv.nvfp4_gemm(qx, qw, nv.OP_FPROP, nv.OUT_F32, workspace=small)
+    assert torch.equal(y1, y0)
+    small2 = torch.empty(nv.gemm_workspace_bytes(tokens, d_in, d_out) - d_in * d_out * 2, dtype=torch.uint8, device="cuda")
+    dx1 = nv.nvfp4_gemm(qdy, qw, nv.OP_DGRAD, nv.OUT_F32, workspace=small2)
+    assert torch.equal(dx1, dx0)
+    # both operands decoded beforehand (Wgrad): only counters and partial tiles remain in the workspace
+    dw0 = nv.nvfp4_gemm(qx, qdy, nv.OP_WGRAD, nv.OUT_F32, workspace=gemm_ws(d_in, d_out, tokens))
+    nv.nvfp4_predecode(qx, nv.COPY_COL)
+    nv.nvfp4_predecode(qdy, nv.COPY_COL)
+    tiny = torch.empty(nv.gemm_workspace_bytes(d_in, d_out, tokens) - (d_in + d_out) * tokens * 2, dtype=torch.uint8, device="cuda")
+    assert torch.equal(nv.nvfp4_gemm(qx, qdy, nv.OP_WGRAD, nv.OUT_F32, workspace=tiny), dw0)
+    # the fused route ignores decoded copies
+    assert torch.equal(nv.nvfp4_gemm(qx, qw, nv.OP_FPROP, nv.OUT_F32), nv.nvfp4_gemm(qx, qw, nv.OP_FPROP, nv.OUT_F32))
+    # requantizing into the descriptor drops the decoded copies (they would be stale)
+    nv.nvfp4_quantize(to_dev(wb), nv.LAYOUT_ROW | nv.LAYOUT_COL, nv.BLOCK_16x16, out=qw)
+    assert qw.desc.row_fp16 is None and qw.desc.col_fp16 is None and qw.row_fp16 is None
+    y2 = nv.nvfp4_gemm(qx, qw, nv.OP_FPROP, nv.OUT_F32, workspace=ws)
+    assert torch.equal(y2, y0)
