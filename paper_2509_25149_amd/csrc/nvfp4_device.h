@@ -97,6 +97,16 @@ __device__ __forceinline__ uint32_t cvt_sr_single(float v, uint32_t rand_hi16) {
   return __builtin_amdgcn_cvt_scalef32_sr_pk_fp4_f32(0u, p, rand_hi16, 1.0f, kSel);
 }
 
+// The same conversion written into byte kSel of `acc`, the other three bytes kept: the instruction only writes the byte
+// it is told to, but the builtin does not say so to the compiler (see above), so the accumulating form is spelled in
+// assembly with the destination tied.  Four of these fill a dword without any merging.
+template <int kSel>
+__device__ __forceinline__ void cvt_sr_single_into(uint32_t& acc, float v, uint32_t rand_hi16) {
+  float2v p;   // the pair's second value is never looked at
+  p.x = v;
+  asm("v_cvt_scalef32_sr_pk_fp4_f32 %0, %1, %2, 1.0 op_sel:[0,0,%3,%4]" : "+v"(acc) : "v"(p), "v"(rand_hi16), "n"(kSel & 1), "n"(kSel >> 1));
+}
+
 // (a & mask) | (b & ~mask) in one v_bitop3_b32 (truth table: the expression evaluated on
 // a = 0xF0, b = 0xCC, mask = 0xAA).  Spelled with the builtin so that the compiler keeps it one
 // instruction instead of re-deriving the nibble masks term by term.

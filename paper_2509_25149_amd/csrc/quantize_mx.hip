@@ -52,10 +52,15 @@ __device__ __forceinline__ uint32_t encode8(const float v[8], const uint32_t dra
     d = cvt_rne_pair<3>(d, v[6], v[7]);
     return d;
   } else {
-    const uint32_t e = merge_bytes(cvt_sr_single<0>(v[0], draws_hi16[0]), cvt_sr_single<1>(v[2], draws_hi16[2]),
-                                   cvt_sr_single<2>(v[4], draws_hi16[4]), cvt_sr_single<3>(v[6], draws_hi16[6]));
-    const uint32_t o = merge_bytes(cvt_sr_single<0>(v[1], draws_hi16[1]), cvt_sr_single<1>(v[3], draws_hi16[3]),
-                                   cvt_sr_single<2>(v[5], draws_hi16[5]), cvt_sr_single<3>(v[7], draws_hi16[7]));
+    uint32_t e = 0u, o = 0u;
+    cvt_sr_single_into<0>(e, v[0], draws_hi16[0]);
+    cvt_sr_single_into<1>(e, v[2], draws_hi16[2]);
+    cvt_sr_single_into<2>(e, v[4], draws_hi16[4]);
+    cvt_sr_single_into<3>(e, v[6], draws_hi16[6]);
+    cvt_sr_single_into<0>(o, v[1], draws_hi16[1]);
+    cvt_sr_single_into<1>(o, v[3], draws_hi16[3]);
+    cvt_sr_single_into<2>(o, v[5], draws_hi16[5]);
+    cvt_sr_single_into<3>(o, v[7], draws_hi16[7]);
     return interleave_nibbles(e, o);
   }
 }

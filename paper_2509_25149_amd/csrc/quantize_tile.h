@@ -108,10 +108,15 @@ __device__ __forceinline__ uint32_t encode8(const float v[8], const uint32_t rnd
     d = cvt_rne_pair<3>(d, v[6], v[7]);
     return d;
   } else {
-    const uint32_t e = merge_bytes(cvt_sr_single<0>(v[0], rnd[0] << 16), cvt_sr_single<1>(v[2], rnd[1] << 16),
-                                   cvt_sr_single<2>(v[4], rnd[2] << 16), cvt_sr_single<3>(v[6], rnd[3] << 16));
-    const uint32_t o = merge_bytes(cvt_sr_single<0>(v[1], rnd[0] & 0xFFFF0000u), cvt_sr_single<1>(v[3], rnd[1] & 0xFFFF0000u),
-                                   cvt_sr_single<2>(v[5], rnd[2] & 0xFFFF0000u), cvt_sr_single<3>(v[7], rnd[3] & 0xFFFF0000u));
+    uint32_t e = 0u, o = 0u;   // low nibble of byte t: element 2t (e) / 2t + 1 (o)
+    cvt_sr_single_into<0>(e, v[0], rnd[0] << 16);
+    cvt_sr_single_into<1>(e, v[2], rnd[1] << 16);
+    cvt_sr_single_into<2>(e, v[4], rnd[2] << 16);
+    cvt_sr_single_into<3>(e, v[6], rnd[3] << 16);
+    cvt_sr_single_into<0>(o, v[1], rnd[0] & 0xFFFF0000u);
+    cvt_sr_single_into<1>(o, v[3], rnd[1] & 0xFFFF0000u);
+    cvt_sr_single_into<2>(o, v[5], rnd[2] & 0xFFFF0000u);
+    cvt_sr_single_into<3>(o, v[7], rnd[3] & 0xFFFF0000u);
     return interleave_nibbles(e, o);
   }
 }
@@ -130,10 +135,15 @@ __device__ __forceinline__ uint32_t encode8_col(const float* v, const uint32_t r
     const uint32_t none[4] = {0, 0, 0, 0};
     return encode8<false>(v, none);
   } else {
-    const uint32_t e = merge_bytes(cvt_sr_single<0>(v[0], draw_hi16(rnd, r0 + 0, c)), cvt_sr_single<1>(v[2], draw_hi16(rnd, r0 + 2, c)),
-                                   cvt_sr_single<2>(v[4], draw_hi16(rnd, r0 + 4, c)), cvt_sr_single<3>(v[6], draw_hi16(rnd, r0 + 6, c)));
-    const uint32_t o = merge_bytes(cvt_sr_single<0>(v[1], draw_hi16(rnd, r0 + 1, c)), cvt_sr_single<1>(v[3], draw_hi16(rnd, r0 + 3, c)),
-                                   cvt_sr_single<2>(v[5], draw_hi16(rnd, r0 + 5, c)), cvt_sr_single<3>(v[7], draw_hi16(rnd, r0 + 7, c)));
+    uint32_t e = 0u, o = 0u;
+    cvt_sr_single_into<0>(e, v[0], draw_hi16(rnd, r0 + 0, c));
+    cvt_sr_single_into<1>(e, v[2], draw_hi16(rnd, r0 + 2, c));
+    cvt_sr_single_into<2>(e, v[4], draw_hi16(rnd, r0 + 4, c));
+    cvt_sr_single_into<3>(e, v[6], draw_hi16(rnd, r0 + 6, c));
+    cvt_sr_single_into<0>(o, v[1], draw_hi16(rnd, r0 + 1, c));
+    cvt_sr_single_into<1>(o, v[3], draw_hi16(rnd, r0 + 3, c));
+    cvt_sr_single_into<2>(o, v[5], draw_hi16(rnd, r0 + 5, c));
+    cvt_sr_single_into<3>(o, v[7], draw_hi16(rnd, r0 + 7, c));
     return interleave_nibbles(e, o);
   }
 }
