@@ -17,7 +17,7 @@ program directly after `--`:
 
 then, anywhere the databases are (they are large; on the GPU machine itself is simplest):
 
-  python3 bench_profile.py gpurun_out/prof [--out DIR]        # DIR defaults to profiles/
+  python3 bench_profile.py gpurun_out/prof [--out DIR] [--commit ID]     # DIR defaults to profiles/
 
 Only this file, bench.py and the library are involved.  Nothing here runs on the GPU.
 """
@@ -58,11 +58,15 @@ def short_name(n: str) -> str:
     m = re.search(r"gemm_f16_kernelILb(\d)E", n)
     if m:
         return "nvfp4::gemm_f16_kernel<%s>" % ("true" if m.group(1) == "1" else "false")
+    if "decode_f16_kernel" in n:
+        return "nvfp4::decode_f16_kernel"
     n = re.sub(r"\(.*", "", n.replace("void ", "").replace("(anonymous namespace)::", ""))
     return n[:110]
 
 
 def ours(n: str) -> bool:
+    if "amax_finalize_kernel" in n or "mx_tensor_scale_kernel" in n:
+        return False                                  # a few microseconds each: left out to keep the summaries short
     return "nvfp4" in n or "stream_copy_kernel" in n or "mfma_rate_kernel" in n
 
 
@@ -117,6 +121,8 @@ def pmc_sum_by_kernel(db: str, counter: str):
 def fmt_pmc(table, counter):
     lines = [f"{'calls':>5} {'avg':>16} {'min':>16} {'max':>16} {'avg_us':>9}  {counter}  kernel"]
     for kern, (k, a, mi, ma, d) in sorted(table.get(counter, {}).items(), key=lambda kv: -kv[1][1]):
+        if ma == 0:
+            continue                                  # kernels the counter does not concern
         lines.append(f"{k:5d} {a:16.1f} {mi:16.1f} {ma:16.1f} {d / 1e3:9.1f}  {counter}  {kern}")
     return lines
 
@@ -131,6 +137,11 @@ def git_head() -> str:
 def main() -> int:
     global OUT_DIR
     argv = sys.argv[1:]
+    commit = git_head()
+    if "--commit" in argv:                            # where the tree is not a git checkout (the GPU machine)
+        i = argv.index("--commit")
+        commit = argv[i + 1]
+        del argv[i:i + 2]
     if "--out" in argv:
         i = argv.index("--out")
         OUT_DIR = os.path.abspath(argv[i + 1])
@@ -141,7 +152,7 @@ def main() -> int:
     base = argv[0]
     dbs = {k: find_db(os.path.join(base, k)) for k in COMMANDS}
     os.makedirs(OUT_DIR, exist_ok=True)
-    measured = {"source": f"rocprofv3 runs of bench.py summarised by bench_profile.py (tree at or after commit {git_head()}); "
+    measured = {"source": f"rocprofv3 runs of bench.py summarised by bench_profile.py (tree at commit {commit}); "
                           "see profiles/bench_linear_layer_12B_*.txt for the commands"}
     head = ("bench.py, one NVFP4 linear layer fwd+bwd at the 12B MLP up-projection shape (8192 tokens, 5120 -> 20480), one MI355X;\n"
             "the MXFP4 comparison block of bench.py runs in the same process (gemm_mx_kernel_*, quantize_mx_kernel).\n"
