@@ -264,7 +264,7 @@ def test_no_kernel_keeps_arrays_in_scratch_memory():
         assert r["Dynamic Stack"] == "False", name
         assert r["ScratchSize"] <= 32, (name, r["ScratchSize"])
         if any(k in name for k in ("quantize_mx_kernel", "cast_kernel", "amax_kernel", "cast_wide", "amax_wide", "decode_f16",
-                                   "dequantize", "gemm_mx_kernel_k512")):
+                                   "dequantize", "gemm_mx_kernel_k512", "gemm_f16_kernel", "rowscale_")):
             assert r["ScratchSize"] == 0 and r["VGPRs Spill"] == 0, (name, r)
 
 
