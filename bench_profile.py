@@ -2,22 +2,22 @@
 """Turns rocprofv3 result databases of bench.py runs into the short text summaries under profiles/ and into
 profiles/measured_counters.json, which bench.py reads back (HBM-side traffic per call, matrix-pipe utilisation).
 
-rocprofv3 is run on the GPU machine (from /tmp with TMPDIR=/tmp; R = repository root), one run per counter group, the
+rocprofv3 is run on the GPU machine (from /tmp with TMPDIR=/tmp; R = repository root, P = any scratch directory), one run per counter group, the
 program directly after `--`:
 
   B="python3 $R/bench.py --steps 2 --warmup 1 --no-cpu-baseline --no-layer-calls --no-row-scales --no-rht-sweep --no-context"
-  rocprofv3 --kernel-trace --stats -d $R/gpurun_out/prof/trace -o bench -- python3 $R/bench.py --steps 5 --warmup 1 \
+  rocprofv3 --kernel-trace --stats -d $P/trace -o bench -- python3 $R/bench.py --steps 5 --warmup 1 \
             --no-cpu-baseline --no-layer-calls --no-row-scales --no-rht-sweep --no-context
-  rocprofv3 --pmc FETCH_SIZE -d $R/gpurun_out/prof/fetch -o bench -- $B
-  rocprofv3 --pmc WRITE_SIZE -d $R/gpurun_out/prof/write -o bench -- $B
+  rocprofv3 --pmc FETCH_SIZE -d $P/fetch -o bench -- $B
+  rocprofv3 --pmc WRITE_SIZE -d $P/write -o bench -- $B
   rocprofv3 --pmc SQ_VALU_MFMA_BUSY_CYCLES SQ_BUSY_CU_CYCLES SQ_INSTS_VALU_MFMA_MOPS_F16 SQ_INSTS_VALU_MFMA_MOPS_F6F4 \
-            SQ_VALU_MFMA_COEXEC_CYCLES GRBM_GUI_ACTIVE -d $R/gpurun_out/prof/mfma -o bench -- $B
+            SQ_VALU_MFMA_COEXEC_CYCLES GRBM_GUI_ACTIVE -d $P/mfma -o bench -- $B
   rocprofv3 --pmc SQ_LDS_BANK_CONFLICT SQ_LDS_IDX_ACTIVE SQ_INSTS_LDS SQ_INSTS_VALU SQ_ACTIVE_INST_VALU SQ_WAVE_CYCLES \
-            SQ_WAIT_INST_ANY SQ_WAVES GRBM_GUI_ACTIVE -d $R/gpurun_out/prof/sq -o bench -- $B
+            SQ_WAIT_INST_ANY SQ_WAVES GRBM_GUI_ACTIVE -d $P/sq -o bench -- $B
 
 then, anywhere the databases are (they are large; on the GPU machine itself is simplest):
 
-  python3 bench_profile.py gpurun_out/prof [--out DIR] [--commit ID]     # DIR defaults to profiles/
+  python3 bench_profile.py $P [--out DIR] [--commit ID]     # DIR defaults to profiles/
 
 Only this file, bench.py and the library are involved.  Nothing here runs on the GPU.
 """
@@ -38,13 +38,13 @@ CUS, SIMDS_PER_CU, XCDS = 256, 4, 8
 
 BENCH_TAIL = "--no-cpu-baseline --no-layer-calls --no-row-scales --no-rht-sweep --no-context"
 COMMANDS = {
-    "trace": f"rocprofv3 --kernel-trace --stats -d $R/gpurun_out/prof/trace -o bench -- python3 $R/bench.py --steps 5 --warmup 1 {BENCH_TAIL}",
-    "fetch": f"rocprofv3 --pmc FETCH_SIZE -d $R/gpurun_out/prof/fetch -o bench -- python3 $R/bench.py --steps 2 --warmup 1 {BENCH_TAIL}",
-    "write": f"rocprofv3 --pmc WRITE_SIZE -d $R/gpurun_out/prof/write -o bench -- python3 $R/bench.py --steps 2 --warmup 1 {BENCH_TAIL}",
+    "trace": f"rocprofv3 --kernel-trace --stats -d $P/trace -o bench -- python3 $R/bench.py --steps 5 --warmup 1 {BENCH_TAIL}",
+    "fetch": f"rocprofv3 --pmc FETCH_SIZE -d $P/fetch -o bench -- python3 $R/bench.py --steps 2 --warmup 1 {BENCH_TAIL}",
+    "write": f"rocprofv3 --pmc WRITE_SIZE -d $P/write -o bench -- python3 $R/bench.py --steps 2 --warmup 1 {BENCH_TAIL}",
     "mfma": "rocprofv3 --pmc SQ_VALU_MFMA_BUSY_CYCLES SQ_BUSY_CU_CYCLES SQ_INSTS_VALU_MFMA_MOPS_F16 SQ_INSTS_VALU_MFMA_MOPS_F6F4 SQ_VALU_MFMA_COEXEC_CYCLES GRBM_GUI_ACTIVE "
-            f"-d $R/gpurun_out/prof/mfma -o bench -- python3 $R/bench.py --steps 2 --warmup 1 {BENCH_TAIL}",
+            f"-d $P/mfma -o bench -- python3 $R/bench.py --steps 2 --warmup 1 {BENCH_TAIL}",
     "sq": "rocprofv3 --pmc SQ_LDS_BANK_CONFLICT SQ_LDS_IDX_ACTIVE SQ_INSTS_LDS SQ_INSTS_VALU SQ_ACTIVE_INST_VALU SQ_WAVE_CYCLES SQ_WAIT_INST_ANY SQ_WAVES GRBM_GUI_ACTIVE "
-          f"-d $R/gpurun_out/prof/sq -o bench -- python3 $R/bench.py --steps 2 --warmup 1 {BENCH_TAIL}",
+          f"-d $P/sq -o bench -- python3 $R/bench.py --steps 2 --warmup 1 {BENCH_TAIL}",
 }
 
 
@@ -156,7 +156,7 @@ def main() -> int:
                           "see profiles/bench_linear_layer_12B_*.txt for the commands"}
     head = ("bench.py, one NVFP4 linear layer fwd+bwd at the 12B MLP up-projection shape (8192 tokens, 5120 -> 20480), one MI355X;\n"
             "the MXFP4 comparison block of bench.py runs in the same process (gemm_mx_kernel_*, quantize_mx_kernel).\n"
-            "Run from /tmp with TMPDIR=/tmp on the GPU box, R = repository root.  Summarised by bench_profile.py.\n")
+            "Run from /tmp with TMPDIR=/tmp on the GPU box, R = repository root, P = a scratch directory.  Summarised by bench_profile.py.\n")
 
     if dbs["trace"]:
         rows = kernel_trace(dbs["trace"])
