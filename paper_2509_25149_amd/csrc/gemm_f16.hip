@@ -161,6 +161,12 @@ __device__ __forceinline__ void load_1k_to_lds(uint32_t lane_offset, const char*
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_dst), "v"(lane_offset), "s"(base)
                : "memory", "m0");
 }
+// The same with M0 (the LDS destination) left as the previous call set it: the instruction's immediate offset kOff is
+// added to the LDS address and to the global address alike, so the caller passes a base that is kOff too low.
+template <int kOff>
+__device__ __forceinline__ void load_1k_to_lds_next(uint32_t lane_offset, const char* base_minus_off) {
+  asm volatile("global_load_lds_dwordx4 %0, %1 offset:%2" ::"v"(lane_offset), "s"(base_minus_off), "n"(kOff) : "memory");
+}
 
 // Tiles [tile_begin, tile_begin + count) of the 256x256 tiling are covered.
 //
@@ -227,6 +233,30 @@ __global__ __launch_bounds__(kThreads) void gemm_f16_kernel(const _Float16* __re
     const uint32_t dst = fill0 + stage * kStageBytes + (q < 8 ? 0 : kOperandBytes) + (q & 7) * 1024;
     load_1k_to_lds((q & 1) ? off_odd : off_even, (q < 8 ? blk_a[q & 7] : blk_b[q & 7]) + static_cast<int64_t>(kt) * kRowBytes, dst);
   };
+  // The loads inside the loop, one instruction each where the prologue's form takes three plus address arithmetic
+  // (a single wavefront per SIMD issues in order: what it spends on anything else, the matrix pipe waits):
+  //   - the K step enters through the per-lane offsets, advanced once per step (ve, vo below), so the sixteen 64-bit
+  //     row-block bases stay constant in scalar registers;
+  //   - M0 (the LDS destination) is written once per four loads; loads q % 4 = 1, 2, 3 reach the next KiB through
+  //     the instruction's immediate offset, which moves the LDS and the global address alike, hence bases that are
+  //     (q % 4) KiB too low.
+  const char* adj_a[8];
+  const char* adj_b[8];
+#pragma unroll
+  for (int q = 0; q < 8; ++q) {
+    adj_a[q] = blk_a[q] - (q & 3) * 1024;
+    adj_b[q] = blk_b[q] - (q & 3) * 1024;
+  }
+  uint32_t ve = 0, vo = 0;   // off_even / off_odd + the byte offset of the K step being fetched
+  auto issue_in_loop = [&](auto qc, int stage) {
+    constexpr int q = decltype(qc)::value;
+    const uint32_t voff = (q & 1) ? vo : ve;
+    const char* base = q < 8 ? adj_a[q & 7] : adj_b[q & 7];
+    if constexpr ((q & 3) == 0)
+      load_1k_to_lds(voff, base, fill0 + stage * kStageBytes + (q < 8 ? 0 : kOperandBytes) + (q & 4) * 1024);
+    else
+      load_1k_to_lds_next<(q & 3) * 1024>(voff, base);
+  };
   // fragment addresses in stage 0: first / second 32 k of the step
   const uint32_t a_lo = lds0 + swz(arow, lq), a_hi = lds0 + swz(arow, 4 + lq);
   const uint32_t b_lo = lds0 + kOperandBytes + swz(brow, lq), b_hi = lds0 + kOperandBytes + swz(brow, 4 + lq);
@@ -254,6 +284,8 @@ __global__ __launch_bounds__(kThreads) void gemm_f16_kernel(const _Float16* __re
     const uint32_t cur = ((kt - kt_begin) & 1) * kStageBytes, nxt = cur ^ kStageBytes;
     // Past the end the last K step is fetched again, into a buffer nobody reads any more: no branches in the loop.
     const int kt2 = min(kt + 2, kt_end - 1);
+    ve = off_even + static_cast<uint32_t>(kt2) * kRowBytes;
+    vo = off_odd + static_cast<uint32_t>(kt2) * kRowBytes;
     static_for<0, 64>([&](auto ic) {
       constexpr int n = decltype(ic)::value;
       mfma(acc[n >> 3][n & 7], f0.b[n & 7], f0.a[n >> 3]);
@@ -265,7 +297,7 @@ __global__ __launch_bounds__(kThreads) void gemm_f16_kernel(const _Float16* __re
       constexpr int n = decltype(ic)::value;
       mfma(acc[n >> 3][n & 7], f1.b[n & 7], f1.a[n >> 3]);
       if constexpr ((n & 3) == 1) read_frag<(n >> 2)>(f0, a_lo + nxt, b_lo + nxt);
-      if constexpr ((n & 3) == 3) issue_one(n >> 2, kt2, (kt - kt_begin) & 1);
+      if constexpr ((n & 3) == 3) issue_in_loop(std::integral_constant<int, (n >> 2)>{}, (kt - kt_begin) & 1);
     });
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
   }
