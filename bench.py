@@ -260,7 +260,7 @@ def known_amax_block(torch, nv, x, w, dy, iters: int = 5):
     return res
 
 
-def row_scale_block(torch, nv, sets, qw, gemm_ws, iters: int = 6):
+def row_scale_block(torch, nv, sets, qw, gemm_ws, iters: int = 9):
     """The quantizer with one tensor-level scale per row of each copy (NVFP4_LAYOUT_ROW_SCALES; App. B.1, last sentence:
     a global scale of finer granularity saves the extra pass over memory).  The row copy alone is ONE pass over the
     tensor (a workgroup holds its row in registers), so its bytes are counted once; calls that also emit the col copy
@@ -276,17 +276,13 @@ def row_scale_block(torch, nv, sets, qw, gemm_ws, iters: int = 6):
         for layout, tag, nbytes in ((ROW, "row_copy_one_pass", 2.0 * n + n / 2.0 + n / 16.0 + 8.0 * rows),
                                     (RC, "both_copies_two_pass", 4.0 * n + 2 * (n / 2.0 + n / 16.0) + 8.0 * (rows + cols))):
             q = nv.alloc_qtensor(rows, cols, layout | RS)
-            ms = []
-            for it in range(iters + 1):
-                t = sets[it % len(sets)][which]
-                a, b = ev(), ev()
-                a.record()
-                nv.nvfp4_quantize(t, layout | RS, nv.BLOCK_1x16, rnd, layout == RC, 2025, 77 + it, out=q)
-                b.record()
-                torch.cuda.synchronize()
-                if it:
-                    ms.append(a.elapsed_time(b))
-            ms.sort()
+            marks = [ev() for _ in range(iters + 2)]
+            for it in range(iters + 1):               # back to back on the stream, like the timed steps; the first is warm-up
+                marks[it].record()
+                nv.nvfp4_quantize(sets[it % len(sets)][which], layout | RS, nv.BLOCK_1x16, rnd, layout == RC, 2025, 77 + it, out=q)
+            marks[iters + 1].record()
+            torch.cuda.synchronize()
+            ms = sorted(marks[it].elapsed_time(marks[it + 1]) for it in range(1, iters + 1))
             med = ms[len(ms) // 2]
             res[f"{name}_{tag}"] = {"ms_median": med, "ms_min": ms[0], "bytes_algorithmic": nbytes,
                                     "GBps": nbytes / (med * 1e-3) / 1e9, "frac_of_hbm_peak": nbytes / (med * 1e-3) / 1e9 / PEAK_HBM_GBPS}

@@ -309,11 +309,13 @@ uint32_t nvfp4_rht_sign_mask(uint64_t rht_seed);
 /*
  * Device self-test of the gfx950 conversion instructions the quantizer relies
  * on, against explicit integer/compare implementations run on the device.
- * mismatches: DEVICE pointer to uint64[4], zeroed by the caller; the kernels
+ * mismatches: DEVICE pointer to uint64[5], zeroed by the caller; the kernels
  * add their mismatch counts: [0] FP32->E2M1 RNE over all 2^32 bit patterns,
- * [1] FP32->E2M1 SR over a grid of values x all 2^16 random values,
+ * [1] FP32->E2M1 SR over a grid of values x all 2^16 random values (the plain
+ * and the accumulating form of the conversion),
  * [2] FP32->E4M3 (and back) over all non-negative finite patterns,
- * [3] the division-free x/6 against IEEE division over the same patterns.
+ * [3] the division-free x/6 against IEEE division over the same patterns,
+ * [4] FP32->bf16 (the GEMM and dequantize outputs) over all finite patterns.
  * Asynchronous like every other call.
  */
 int nvfp4_selftest_conversions(uint64_t* mismatches, nvfp4_stream_t stream);

@@ -334,7 +334,7 @@ def nvfp4_dequantize(q: QTensor, which_copy: int, undo_rht: bool = False, out_dt
 
 
 def nvfp4_selftest_conversions() -> list:
-    counts = torch.zeros(4, dtype=torch.int64, device="cuda")
+    counts = torch.zeros(5, dtype=torch.int64, device="cuda")
     _check(load_library().nvfp4_selftest_conversions(counts.data_ptr(), _stream()))
     torch.cuda.synchronize()
     return [int(v) for v in counts.cpu()]

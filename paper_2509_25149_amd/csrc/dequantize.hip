@@ -44,7 +44,7 @@ __global__ __launch_bounds__(256) void dequantize_kernel(Operand q, int64_t K, b
   if (kBf16Out) {
     uint32_t w[8];
 #pragma unroll
-    for (int k = 0; k < 8; ++k) w[k] = f32_to_bf16(v[2 * k]) | (f32_to_bf16(v[2 * k + 1]) << 16);
+    for (int k = 0; k < 8; ++k) w[k] = f32x2_to_bf16(v[2 * k], v[2 * k + 1]);
     uint4* dst = reinterpret_cast<uint4*>(static_cast<uint16_t*>(outv) + o * ld_out + b * 16);
     dst[0] = make_uint4(w[0], w[1], w[2], w[3]);
     dst[1] = make_uint4(w[4], w[5], w[6], w[7]);
@@ -90,7 +90,7 @@ __global__ __launch_bounds__(256) void dequantize_mx_kernel(Operand q, int64_t K
     for (int t = 0; t < 4; ++t) {
       uint32_t w[4];
 #pragma unroll
-      for (int k = 0; k < 4; ++k) w[k] = f32_to_bf16(v[8 * t + 2 * k]) | (f32_to_bf16(v[8 * t + 2 * k + 1]) << 16);
+      for (int k = 0; k < 4; ++k) w[k] = f32x2_to_bf16(v[8 * t + 2 * k], v[8 * t + 2 * k + 1]);
       dst[t] = make_uint4(w[0], w[1], w[2], w[3]);
     }
   } else {
@@ -163,7 +163,7 @@ __global__ __launch_bounds__(256) void dequantize_rot_kernel(Operand q, int64_t 
     for (int t = 0; t < kE / 8; ++t) {
       uint32_t w[4];
 #pragma unroll
-      for (int k = 0; k < 4; ++k) w[k] = f32_to_bf16(v[8 * t + 2 * k]) | (f32_to_bf16(v[8 * t + 2 * k + 1]) << 16);
+      for (int k = 0; k < 4; ++k) w[k] = f32x2_to_bf16(v[8 * t + 2 * k], v[8 * t + 2 * k + 1]);
       dst[t] = make_uint4(w[0], w[1], w[2], w[3]);
     }
   } else {

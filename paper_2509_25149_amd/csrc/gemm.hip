@@ -142,8 +142,8 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_kernel(Operand A, Operand B
           if (kBf16Out) {
             uint16_t* d = static_cast<uint16_t*>(Dv) + (m0 + m) * ldd + n0 + n;
             uint2 o;
-            o.x = f32_to_bf16(v[0]) | (f32_to_bf16(v[1]) << 16);
-            o.y = f32_to_bf16(v[2]) | (f32_to_bf16(v[3]) << 16);
+            o.x = f32x2_to_bf16(v[0], v[1]);
+            o.y = f32x2_to_bf16(v[2], v[3]);
             *reinterpret_cast<uint2*>(d) = o;
           } else {
             float* d = static_cast<float*>(Dv) + (m0 + m) * ldd + n0 + n;
@@ -333,8 +333,8 @@ __global__ __launch_bounds__(kBigThreads) void gemm_kernel_256(Operand A, Operan
         if (kBf16Out) {
           uint16_t* d = static_cast<uint16_t*>(Dv) + (m0 + m) * ldd + n0 + n;
           uint2 o;
-          o.x = f32_to_bf16(v[0]) | (f32_to_bf16(v[1]) << 16);
-          o.y = f32_to_bf16(v[2]) | (f32_to_bf16(v[3]) << 16);
+          o.x = f32x2_to_bf16(v[0], v[1]);
+          o.y = f32x2_to_bf16(v[2], v[3]);
           *reinterpret_cast<uint2*>(d) = o;
         } else {
           float* d = static_cast<float*>(Dv) + (m0 + m) * ldd + n0 + n;

@@ -77,8 +77,8 @@ __device__ __forceinline__ void store_wave_block_impl(float4v (&acc)[8][8], cons
 #pragma unroll
       for (int j = 0; j < 8; j += 2) {
         const float4v va = acc[i][j] * scale(i, j), vb = acc[i][j + 1] * scale(i, j + 1);
-        const uint32_t a0 = f32_to_bf16(va[0]) | (f32_to_bf16(va[1]) << 16), a1 = f32_to_bf16(va[2]) | (f32_to_bf16(va[3]) << 16);
-        const uint32_t b0 = f32_to_bf16(vb[0]) | (f32_to_bf16(vb[1]) << 16), b1 = f32_to_bf16(vb[2]) | (f32_to_bf16(vb[3]) << 16);
+        const uint32_t a0 = f32x2_to_bf16(va[0], va[1]), a1 = f32x2_to_bf16(va[2], va[3]);
+        const uint32_t b0 = f32x2_to_bf16(vb[0], vb[1]), b1 = f32x2_to_bf16(vb[2], vb[3]);
         // first result: lanes of odd groups now hold the second block's dword of the group below; second result: lanes of
         // even groups now hold the first block's dword of the group above
         const auto s0 = __builtin_amdgcn_permlane16_swap(a0, b0, false, false);

@@ -79,6 +79,14 @@ __global__ __launch_bounds__(256) void selftest_sr_kernel(unsigned long long* ba
     const uint32_t hw_neg = cvt_sr_single<0>(-v, r << 16) & 0xFu;
     local += hw_pos != ref_e2m1_sr(v, r);
     local += hw_neg != ref_e2m1_sr(-v, r);
+    // the accumulating form the quantizer uses: the code lands in the low nibble of the chosen byte, the other three
+    // bytes of the destination are kept
+    uint32_t acc = 0xA5C3F00Fu;
+    cvt_sr_single_into<2>(acc, v, r << 16);
+    local += ((acc >> 16) & 0xFu) != hw_pos || (acc & 0xFF00FFFFu) != 0xA500F00Fu;
+    acc = 0x12345678u;
+    cvt_sr_single_into<0>(acc, -v, r << 16);
+    local += (acc & 0xFu) != hw_neg || (acc & 0xFFFFFF00u) != 0x12345600u;
   }
   if (local) atomicAdd(bad, local);
 }
@@ -92,6 +100,21 @@ __global__ __launch_bounds__(256) void selftest_e4m3_kernel(unsigned long long* 
     local += code != ref_e4m3(u);
     local += (code < 0x7Fu) && (e4m3_decode(code) != __uint_as_float(
         (code >> 3) ? (((code >> 3) + 120u) << 23) | ((code & 7u) << 20) : __float_as_uint(static_cast<float>(code & 7u) * 0.001953125f)));
+  }
+  if (local) atomicAdd(bad, local);
+}
+
+// FP32 -> bf16 through the packed conversion instruction against the integer formulation of round-to-nearest-even,
+// over every finite pattern (both halves of the pair).
+__global__ __launch_bounds__(256) void selftest_bf16_kernel(unsigned long long* bad) {
+  unsigned long long local = 0;
+  const uint64_t stride = static_cast<uint64_t>(gridDim.x) * blockDim.x;
+  for (uint64_t w = static_cast<uint64_t>(blockIdx.x) * blockDim.x + threadIdx.x; w < 0x100000000ull; w += stride) {
+    const uint32_t bits = static_cast<uint32_t>(w);
+    if ((bits & 0x7F800000u) == 0x7F800000u) continue;     // Inf / NaN: outside the kernels' precondition
+    const float x = __uint_as_float(bits);
+    const float y = __uint_as_float(bits ^ 0x80000000u);
+    local += f32x2_to_bf16(x, y) != (f32_to_bf16(x) | (f32_to_bf16(y) << 16));
   }
   if (local) atomicAdd(bad, local);
 }
@@ -114,6 +137,7 @@ hipError_t run_selftest(uint64_t* mismatches_dev, hipStream_t s) {
   hipLaunchKernelGGL(selftest_sr_kernel, dim3(0x40E1u * 5u), dim3(256), 0, s, dev + 1);
   hipLaunchKernelGGL(selftest_e4m3_kernel, dim3(4096), dim3(256), 0, s, dev + 2);
   hipLaunchKernelGGL(selftest_div6_kernel, dim3(4096), dim3(256), 0, s, dev + 3);
+  hipLaunchKernelGGL(selftest_bf16_kernel, dim3(4096), dim3(256), 0, s, dev + 4);
   return hipGetLastError();
 }
 
