@@ -14,14 +14,16 @@ namespace nvfp4 {
 //   bf16  a lane's 4 columns are only 8 bytes, so two neighbouring 16-column blocks are stored together: lanes
 //         16 apart (column groups 4q.. and 4(q+1)..) trade halves with v_permlane16_swap_b32, after which an
 //         even group holds 8 consecutive columns of the first block and an odd group 8 of the second.
-// FP32 results (weight gradients: large, read again only by the optimizer) leave with non-temporal stores: lines
-// left dirty in the caches are written back during whatever runs next, a bandwidth-bound kernel (the quantizer
-// call after a Wgrad took 63 us behind ordinary stores, 60 us behind these, and the Wgrad itself 0.5 % less).
-// bf16 results (activations and their gradients, which the caller reads next) use ordinary stores: non-temporal
-// ones made the amax pass behind Fprop a third faster (96 -> 62 us) but Fprop itself 4 % slower -- every workgroup
-// of a round finishes its tile at the same moment and the burst drains at memory speed instead of into the caches
-// (12 % slower with 32-byte pieces).  Must be called by all 64 lanes.  (Reordering the bf16 block through LDS into
-// 256-byte row pieces was tried with ordinary stores and measured no faster.)
+// Ordinary stores throughout.  Non-temporal ones were measured both ways: for bf16 results (activations and their
+// gradients, which the caller reads next) they made the amax pass behind Fprop a third faster (96 -> 62 us) but Fprop
+// itself 4 % slower; for FP32 results (weight gradients) they took 3 us off the quantizer call that follows a Wgrad,
+// but a wavefront's output stage issues them at two thirds of the rate (11.7 against 8.2 us for its 64 stores, by
+// timestamps inside the kernel; the Wgrad call 1.359 against 1.347 ms).  A wavefront's stores leave at about 1 KiB per
+// 150 cycles whatever else the chip does (the four wavefronts of a CU share one path to the L2: 128 KiB of bf16 per
+// tile take 2.3 us, another 2.6 us go to reading, scaling and converting the 256 sums), so what bounds
+// the output stage is what a wavefront has to issue, not memory bandwidth: hence no predicates and no address
+// arithmetic per store when the whole block exists.  Must be called by all 64 lanes.  (Reordering the bf16 block through LDS into 256-byte row pieces was tried
+// with ordinary stores and measured no faster.)
 typedef uint32_t u32x4v __attribute__((ext_vector_type(4)));
 
 // The two operands' tensor-level decode scales.  Per tensor: a[0] * b[0] for every output.  With a scale per row of an
@@ -46,7 +48,9 @@ __device__ __forceinline__ float4v scale4(const TensorScales& ts, float uniform,
 
 // kVec: an operand carries one scale per row; the lane's 8 rows (m = 16 i + l16) and 8 x 4 columns (n = 16 j + 4 lq + r)
 // then take their factors from the vectors, loaded once.  Otherwise the product a[0] * b[0] serves every output.
-template <bool kBf16Out, bool kVec>
+// kFull: all 128 x 128 exist, so no store is predicated.  Either way a lane's addresses are one pointer (its row l16,
+// its first column) plus i * 16 rows plus a constant per j, which the stores carry as their immediate offsets.
+template <bool kBf16Out, bool kVec, bool kFull>
 __device__ __forceinline__ void store_wave_block_impl(float4v (&acc)[8][8], const TensorScales ts, void* __restrict__ Dv, int64_t ldd,
                                                       bool accumulate, int64_t row0, int64_t col0, int rows, int cols, int lane) {
   const int l16 = lane & 15, lq = lane >> 4;
@@ -70,10 +74,15 @@ __device__ __forceinline__ void store_wave_block_impl(float4v (&acc)[8][8], cons
     if (kVec) return sb[kVec ? j : 0] * sa[kVec ? i : 0];
     return float4v{out_scale, out_scale, out_scale, out_scale};
   };
+  // bf16: after the exchange a lane of an even column group holds 8 consecutive columns of block j, a lane of an odd
+  // group 8 of block j + 1: column 16 j + nl, nl = 0, 16, 8, 24 for lq = 0 .. 3.
+  const int nl = kBf16Out ? (lq & 1) * 16 + (lq >> 1) * 8 : lq * 4;
+  const int64_t lane_first = (row0 + l16) * ldd + col0 + nl;
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
-    const int m = i * 16 + l16;
+    const bool row_in = kFull || i * 16 + l16 < rows;
     if (kBf16Out) {
+      uint16_t* d_row = static_cast<uint16_t*>(Dv) + lane_first + i * 16 * ldd;
 #pragma unroll
       for (int j = 0; j < 8; j += 2) {
         const float4v va = acc[i][j] * scale(i, j), vb = acc[i][j + 1] * scale(i, j + 1);
@@ -84,21 +93,18 @@ __device__ __forceinline__ void store_wave_block_impl(float4v (&acc)[8][8], cons
         const auto s0 = __builtin_amdgcn_permlane16_swap(a0, b0, false, false);
         const auto s1 = __builtin_amdgcn_permlane16_swap(a1, b1, false, false);
         const u32x4v o = {s0[0], s1[0], s0[1], s1[1]};
-        const int n = (lq & 1) ? (j + 1) * 16 + (lq - 1) * 4 : j * 16 + lq * 4;   // 8 columns from here
-        if (m < rows && n < cols) {   // columns come in multiples of 16, so the 8 columns are in or out together
-          uint16_t* d = static_cast<uint16_t*>(Dv) + (row0 + m) * ldd + col0 + n;
-          *reinterpret_cast<u32x4v*>(d) = o;
-        }
+        // columns come in multiples of 16, so the 8 columns are in or out together
+        if (row_in && (kFull || j * 16 + nl < cols)) *reinterpret_cast<u32x4v*>(d_row + j * 16) = o;
       }
     } else {
+      float* d_row = static_cast<float*>(Dv) + lane_first + i * 16 * ldd;
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
-        const int n = j * 16 + lq * 4;
-        if (m < rows && n < cols) {  // columns come in multiples of 16, so the 4 columns are in or out together
+        if (row_in && (kFull || j * 16 + nl < cols)) {  // columns come in multiples of 16, so the 4 columns are in or out together
           float4v v = acc[i][j] * scale(i, j);
-          float* d = static_cast<float*>(Dv) + (row0 + m) * ldd + col0 + n;
+          float* d = d_row + j * 16;
           if (accumulate) v += *reinterpret_cast<const float4v*>(d);
-          __builtin_nontemporal_store(v, reinterpret_cast<float4v*>(d));
+          *reinterpret_cast<float4v*>(d) = v;
         }
       }
     }
@@ -108,10 +114,14 @@ __device__ __forceinline__ void store_wave_block_impl(float4v (&acc)[8][8], cons
 template <bool kBf16Out>
 __device__ __forceinline__ void store_wave_block(float4v (&acc)[8][8], const TensorScales ts, void* __restrict__ Dv, int64_t ldd,
                                                  bool accumulate, int64_t row0, int64_t col0, int rows, int cols, int lane) {
-  if (ts.a_per_row || ts.b_per_row)   // uniform over the launch
-    store_wave_block_impl<kBf16Out, true>(acc, ts, Dv, ldd, accumulate, row0, col0, rows, cols, lane);
-  else
-    store_wave_block_impl<kBf16Out, false>(acc, ts, Dv, ldd, accumulate, row0, col0, rows, cols, lane);
+  const bool full = rows >= 128 && cols >= 128;
+  if (ts.a_per_row || ts.b_per_row) {   // uniform over the launch
+    store_wave_block_impl<kBf16Out, true, false>(acc, ts, Dv, ldd, accumulate, row0, col0, rows, cols, lane);
+  } else if (full) {                    // uniform over the wavefront
+    store_wave_block_impl<kBf16Out, false, true>(acc, ts, Dv, ldd, accumulate, row0, col0, rows, cols, lane);
+  } else {
+    store_wave_block_impl<kBf16Out, false, false>(acc, ts, Dv, ldd, accumulate, row0, col0, rows, cols, lane);
+  }
 }
 
 }  // namespace nvfp4

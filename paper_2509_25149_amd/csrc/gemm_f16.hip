@@ -168,9 +168,37 @@ __device__ __forceinline__ void load_1k_to_lds_next(uint32_t lane_offset, const 
   asm volatile("global_load_lds_dwordx4 %0, %1 offset:%2" ::"v"(lane_offset), "s"(base_minus_off), "n"(kOff) : "memory");
 }
 
-// Tiles [tile_begin, tile_begin + count) of the 256x256 tiling are covered.
+// The lane's number within its wavefront, asked of the hardware at the place of the call: the compiler can neither
+// move the question nor keep an earlier answer in a register.
+__device__ __forceinline__ int lane_id() {
+  int lane;
+  asm volatile("v_mbcnt_lo_u32_b32 %0, -1, 0\n\tv_mbcnt_hi_u32_b32 %0, -1, %0" : "=v"(lane));
+  return lane;
+}
+
+// The first MFMA of an accumulator in a work item: C = 0, so the 256 accumulation registers are never cleared.
+__device__ __forceinline__ void mfma_first(float4v& acc, const half8v& b, const half8v& a) {
+  asm volatile("v_mfma_f32_16x16x32_f16 %0, %1, %2, 0" : "=a"(acc) : "v"(b), "v"(a));
+}
+
+// A wavefront's output stage issues 32 (bf16) or 64 (FP32) stores for a full 256 x 256 tile (store_wave_block: 16 bytes
+// per lane and instruction).  Three quarters of them: the number of its memory operations that may still be
+// outstanding when the loads issued before it are needed, with a margin against a store more or less.
+template <bool kBf16Out>
+constexpr int kTileStores = kBf16Out ? 24 : 48;
+
+// Tiles [tile_begin, tile_begin + tile_count) of the 256x256 tiling are covered.
 //
-// k_splits > 1 fills the chip during a last, partial round of tiles: a tile is shared by
+// k_splits == 1: a workgroup takes tiles blockIdx.x, blockIdx.x + gridDim.x, ... of the launch (the host launches one
+// workgroup per CU when there are more tiles than CUs) and runs them as ONE stream of K steps: the loads issued during a
+// tile's last two steps already fetch the next tile's first two, so that the pipeline neither drains nor refills at
+// a tile boundary -- what remains there is reading the 256 sums out, scaling, converting and issuing the stores,
+// which then drain under the next tile's MFMAs (measured with timestamps in the one-tile-per-workgroup form: 4.2 us
+// of pipeline fill, 5.5 us of output stage, most of it waiting for the stores of all CUs at once, and 0.6 us between
+// workgroups, per 118 us of main loop at K = 5120).  Needs K >= 2 steps; the host launches one workgroup per tile
+// otherwise.
+//
+// k_splits > 1 (one work item per workgroup) fills the chip during a last, partial round of tiles: a tile is shared by
 // k_splits workgroups, each summing one contiguous range of K steps.  Every one of
 // them stores its FP32 partial tile to `partials`, then takes a ticket from the tile's counter
 // (zeroed by the decode pass of the same call); the workgroup that draws the last ticket adds the
@@ -186,174 +214,232 @@ __global__ __launch_bounds__(kThreads) void gemm_f16_kernel(const _Float16* __re
                                                             unsigned int* tickets, bool a_ts_per_row, bool b_ts_per_row) {
   extern __shared__ __attribute__((aligned(16))) char lds[];
 
-  // Workgroup -> tile: consecutive ids go to different XCDs (round robin over 8, one L2 each);
-  // give every XCD a contiguous range of tiles, walked in bands of 8 tile rows.
-  int wg = blockIdx.x, split = 0;
-  if (k_splits > 1) {
-    split = wg % k_splits;
-    wg /= k_splits;
-  }
-  if ((tile_count & 7) == 0) wg = (wg & 7) * (tile_count >> 3) + (wg >> 3);
-  const int tile_local = wg;
-  const int pid = tile_begin + wg;
-  constexpr int kBand = 8;
-  const int band = pid / (kBand * tiles_n);
-  const int band_rows = min(kBand, tiles_m - band * kBand);
-  const int in_band = pid - band * kBand * tiles_n;
-  const int tm = band * kBand + in_band % band_rows, tn = in_band / band_rows;
-  const int64_t m0 = static_cast<int64_t>(tm) * TM, n0 = static_cast<int64_t>(tn) * TN;
+  const int wave = __builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x) >> 6);
 
-  const int tid = threadIdx.x, lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wm = wave >> 1, wn = wave & 1, l16 = lane & 15, lq = lane >> 4;
-  const int arow = wm * 128 + l16, brow = wn * 128 + l16;
+  // Work item -> tile: consecutive workgroup ids go to different XCDs (round robin over 8, one L2 each);
+  // give every XCD a contiguous range of tiles, walked in bands of 8 tile rows.  (With one workgroup per CU the ids
+  // of a later round continue the first round's, 8 | gridDim.x, so the low three bits stay the XCD.)
+  auto locate = [&](int wg, int& tm, int& tn) -> int {
+    if ((tile_count & 7) == 0) wg = (wg & 7) * (tile_count >> 3) + (wg >> 3);
+    const int pid = tile_begin + wg;
+    constexpr int kBand = 8;
+    const int band = pid / (kBand * tiles_n);
+    const int band_rows = min(kBand, tiles_m - band * kBand);
+    const int in_band = pid - band * kBand * tiles_n;
+    tm = band * kBand + in_band % band_rows;
+    tn = in_band / band_rows;
+    return wg;   // the tile's number within the launch
+  };
 
   // Direct-load sources: instruction q of wavefront w fills rows w * 64 + 8 q .. + 7 of a tile (lane -> row lane / 8,
   // position lane % 8, i.e. chunk (lane % 8) ^ ((row >> 1) & 7); adding 8 q to the row leaves that term alone for even
-  // q and flips its bit 2 for odd q).  Wave-uniform 64-bit base per 8-row block + one per-lane 32-bit offset for
-  // even and one for odd q, shared by both operands (8 rows of K * 2 bytes: K < 2^21, checked on the host).  A block
-  // past the end of an operand is replaced by the operand's last block (rows come in multiples of 16); it only
-  // feeds outputs that are never stored.
-  const int r0 = wave * 64 + (lane >> 3);
-  const uint32_t c0 = static_cast<uint32_t>((lane & 7) ^ ((r0 >> 1) & 7)) * 16u;
-  const uint32_t off_even = static_cast<uint32_t>(lane >> 3) * static_cast<uint32_t>(K * 2) + c0;
-  const uint32_t off_odd = static_cast<uint32_t>(lane >> 3) * static_cast<uint32_t>(K * 2) + (c0 ^ 64u);
-  const char* blk_a[8];
-  const char* blk_b[8];
-#pragma unroll
-  for (int q = 0; q < 8; ++q) {
-    const int64_t r = wave * 64 + q * 8;
-    blk_a[q] = reinterpret_cast<const char*>(A) + (m0 + min<int64_t>(r, M - 8 - m0)) * K * 2;
-    blk_b[q] = reinterpret_cast<const char*>(B) + (n0 + min<int64_t>(r, N - 8 - n0)) * K * 2;
-  }
+  // q and flips its bit 2 for odd q).  An address is a wave-uniform 64-bit base per operand tile plus a per-lane
+  // 32-bit offset per instruction (256 rows of K * 2 bytes: K < 2^21, checked on the host), which holds the row,
+  // the chunk and the K step being fetched.  A block of 8 rows past the end of an operand is replaced by the
+  // operand's last block (rows come in multiples of 16); it only feeds outputs that are never stored.
+  // One instruction per load inside the loop (a single wavefront per SIMD issues in order: what it spends on anything
+  // else, the matrix pipe waits): M0, the LDS destination, is written once per four loads; loads q % 4 = 1, 2, 3 reach
+  // the next KiB through the instruction's immediate offset, which moves the LDS and the global address alike, so
+  // the bases sit 3 KiB low and the offsets make up for what the immediate does not add.
+  //
+  // What depends on the lane is worked out once per tile, from a lane number asked for on the spot: values the
+  // compiler could keep from before the first tile would have to live through every output stage, which needs the
+  // registers itself, and end up in scratch memory, to be fetched back inside the K steps.
   const uint32_t lds0 = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(lds));
+  uint32_t lane_even = 0, lane_odd = 0;      // the lane's part of a load offset for even / odd q
+  uint32_t a_lo = 0, a_hi = 0, b_lo = 0, b_hi = 0;   // fragment addresses in stage 0: first / second 32 k of the step
+  auto lane_setup = [&]() {
+    const int lane = lane_id();
+    const int r0 = wave * 64 + (lane >> 3);
+    const uint32_t c0 = static_cast<uint32_t>((lane & 7) ^ ((r0 >> 1) & 7)) * 16u;
+    lane_even = static_cast<uint32_t>(lane >> 3) * static_cast<uint32_t>(K * 2) + c0;
+    lane_odd = static_cast<uint32_t>(lane >> 3) * static_cast<uint32_t>(K * 2) + (c0 ^ 64u);
+    const int arow = (wave >> 1) * 128 + (lane & 15), brow = (wave & 1) * 128 + (lane & 15), lq = lane >> 4;
+    a_lo = lds0 + swz(arow, lq);
+    a_hi = lds0 + swz(arow, 4 + lq);
+    b_lo = lds0 + kOperandBytes + swz(brow, lq);
+    b_hi = lds0 + kOperandBytes + swz(brow, 4 + lq);
+  };
+  lane_setup();
+  const char* base_a = nullptr;
+  const char* base_b = nullptr;
+  uint32_t voff[16];   // q 0..7 A, 8..15 B
+  // Point the loads at K step kt of tile (tm, tn).
+  auto aim = [&](int tm, int tn, int kt) {
+    const int64_t m_first = static_cast<int64_t>(tm) * TM, n_first = static_cast<int64_t>(tn) * TN;
+    base_a = reinterpret_cast<const char*>(A) + m_first * K * 2 - 3 * 1024;
+    base_b = reinterpret_cast<const char*>(B) + n_first * K * 2 - 3 * 1024;
+    const uint32_t last_a = static_cast<uint32_t>(M - 8 - m_first), last_b = static_cast<uint32_t>(N - 8 - n_first);
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      const uint32_t r = static_cast<uint32_t>(wave * 64 + q * 8);
+      const uint32_t fixed = static_cast<uint32_t>(3 - (q & 3)) * 1024u + static_cast<uint32_t>(kt) * kRowBytes;
+      voff[q] = ((q & 1) ? lane_odd : lane_even) + min(r, last_a) * static_cast<uint32_t>(K * 2) + fixed;
+      voff[8 + q] = ((q & 1) ? lane_odd : lane_even) + min(r, last_b) * static_cast<uint32_t>(K * 2) + fixed;
+    }
+  };
   const uint32_t fill0 = lds0 + wave * 8192;   // this wavefront's 8 KiB of each operand tile
-  // one of the 16 loads of K step kt into stage `stage`: q 0..7 A, 8..15 B
-  auto issue_one = [&](int q, int kt, int stage) {
-    const uint32_t dst = fill0 + stage * kStageBytes + (q < 8 ? 0 : kOperandBytes) + (q & 7) * 1024;
-    load_1k_to_lds((q & 1) ? off_odd : off_even, (q < 8 ? blk_a[q & 7] : blk_b[q & 7]) + static_cast<int64_t>(kt) * kRowBytes, dst);
-  };
-  // The loads inside the loop, one instruction each where the prologue's form takes three plus address arithmetic
-  // (a single wavefront per SIMD issues in order: what it spends on anything else, the matrix pipe waits):
-  //   - the K step enters through the per-lane offsets, advanced once per step (ve, vo below), so the sixteen 64-bit
-  //     row-block bases stay constant in scalar registers;
-  //   - M0 (the LDS destination) is written once per four loads; loads q % 4 = 1, 2, 3 reach the next KiB through
-  //     the instruction's immediate offset, which moves the LDS and the global address alike, hence bases that are
-  //     (q % 4) KiB too low.
-  const char* adj_a[8];
-  const char* adj_b[8];
-#pragma unroll
-  for (int q = 0; q < 8; ++q) {
-    adj_a[q] = blk_a[q] - (q & 3) * 1024;
-    adj_b[q] = blk_b[q] - (q & 3) * 1024;
-  }
-  uint32_t ve = 0, vo = 0;   // off_even / off_odd + the byte offset of the K step being fetched
-  auto issue_in_loop = [&](auto qc, int stage) {
+  // load q of the 16 that fill stage `stage`
+  auto issue = [&](auto qc, int stage) {
     constexpr int q = decltype(qc)::value;
-    const uint32_t voff = (q & 1) ? vo : ve;
-    const char* base = q < 8 ? adj_a[q & 7] : adj_b[q & 7];
+    const char* base = q < 8 ? base_a : base_b;
     if constexpr ((q & 3) == 0)
-      load_1k_to_lds(voff, base, fill0 + stage * kStageBytes + (q < 8 ? 0 : kOperandBytes) + (q & 4) * 1024);
+      load_1k_to_lds(voff[q], base, fill0 + stage * kStageBytes + (q < 8 ? 0 : kOperandBytes) + (q & 4) * 1024);
     else
-      load_1k_to_lds_next<(q & 3) * 1024>(voff, base);
+      load_1k_to_lds_next<(q & 3) * 1024>(voff[q], base);
   };
-  // fragment addresses in stage 0: first / second 32 k of the step
-  const uint32_t a_lo = lds0 + swz(arow, lq), a_hi = lds0 + swz(arow, 4 + lq);
-  const uint32_t b_lo = lds0 + kOperandBytes + swz(brow, lq), b_hi = lds0 + kOperandBytes + swz(brow, 4 + lq);
-
-  float4v acc[8][8];
-#pragma unroll
-  for (int i = 0; i < 8; ++i)
-#pragma unroll
-    for (int j = 0; j < 8; ++j)
-#pragma unroll
-      for (int r = 0; r < 4; ++r) acc[i][j][r] = 0.0f;
 
   const int KT = static_cast<int>(K / TK);
-  const int kt_begin = static_cast<int>(static_cast<int64_t>(KT) * split / k_splits);
-  const int kt_end = static_cast<int>(static_cast<int64_t>(KT) * (split + 1) / k_splits);   // > kt_begin: KT >= k_splits
-  static_for<0, 16>([&](auto q) { issue_one(decltype(q)::value, kt_begin, 0); });
-  static_for<0, 16>([&](auto q) { issue_one(decltype(q)::value, min(kt_begin + 1, kt_end - 1), 1); });
+  const int items = tile_count * k_splits;
+  int item = blockIdx.x;   // < items: the host launches at most that many workgroups
+  int tm = 0, tn = 0;
+  const int split = item % k_splits;   // k_splits > 1: one work item per workgroup
+  const int tile_local = locate(item / k_splits, tm, tn);
+  int kt_begin = static_cast<int>(static_cast<int64_t>(KT) * split / k_splits);
+  int kt_end = static_cast<int>(static_cast<int64_t>(KT) * (split + 1) / k_splits);   // > kt_begin: KT >= k_splits
+  // The K step the loads point at: they run two steps ahead of the MFMAs.
+  int fetch_kt = kt_begin;
+  aim(tm, tn, fetch_kt);
+  static_for<0, 16>([&](auto q) { issue(q, 0); });
+  if (fetch_kt + 1 < kt_end) {
+    ++fetch_kt;
+#pragma unroll
+    for (int q = 0; q < 16; ++q) voff[q] += kRowBytes;
+  }
+  static_for<0, 16>([&](auto q) { issue(q, 1); });
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __builtin_amdgcn_s_barrier();
+
   Frags f0, f1;
-  static_for<0, 16>([&](auto q) { read_frag<decltype(q)::value>(f0, a_lo, b_lo); });
-  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-
-  for (int kt = kt_begin; kt < kt_end; ++kt) {
-    const uint32_t cur = ((kt - kt_begin) & 1) * kStageBytes, nxt = cur ^ kStageBytes;
-    // Past the end the last K step is fetched again, into a buffer nobody reads any more: no branches in the loop.
-    const int kt2 = min(kt + 2, kt_end - 1);
-    ve = off_even + static_cast<uint32_t>(kt2) * kRowBytes;
-    vo = off_odd + static_cast<uint32_t>(kt2) * kRowBytes;
-    static_for<0, 64>([&](auto ic) {
-      constexpr int n = decltype(ic)::value;
-      mfma(acc[n >> 3][n & 7], f0.b[n & 7], f0.a[n >> 3]);
-      if constexpr ((n & 3) == 1) read_frag<(n >> 2)>(f1, a_hi + cur, b_hi + cur);
-    });
-    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
-    __builtin_amdgcn_s_barrier();
-    static_for<0, 64>([&](auto ic) {
-      constexpr int n = decltype(ic)::value;
-      mfma(acc[n >> 3][n & 7], f1.b[n & 7], f1.a[n >> 3]);
-      if constexpr ((n & 3) == 1) read_frag<(n >> 2)>(f0, a_lo + nxt, b_lo + nxt);
-      if constexpr ((n & 3) == 3) issue_in_loop(std::integral_constant<int, (n >> 2)>{}, (kt - kt_begin) & 1);
-    });
+  float4v acc[8][8];
+  uint32_t parity = 0;          // of the number of K steps done so far: which LDS stage holds the current one
+  bool stores_behind = false;   // the previous tile's kTileStores stores were issued after the loads now in flight
+  for (;;) {
+    // The tile's first fragments.  (After a tile of the same stream its last step has read them already; they are read
+    // again so that the output stage had their registers to work with.)
+    static_for<0, 16>([&](auto q) { read_frag<decltype(q)::value>(f0, a_lo + parity * kStageBytes, b_lo + parity * kStageBytes); });
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-  }
-  // The trailing global->LDS loads must have landed before LDS is reused or the wavefront ends; the MFMA results
-  // must have left the pipe before ordinary instructions read the accumulators (the compiler cannot see into the
-  // assembly statements to insert these wait states itself).
-  asm volatile("s_waitcnt vmcnt(0)\n\ts_nop 15\n\ts_nop 15" ::: "memory");
-  __syncthreads();
+    // The next tile of this workgroup, if any: its K steps follow this tile's without a break (k_splits == 1 then).
+    const int next_item = item + static_cast<int>(gridDim.x);
+    const bool has_next = next_item < items;
+    int next_tm = 0, next_tn = 0;
+    if (has_next) locate(next_item, next_tm, next_tn);
 
-  if (k_splits > 1) {
-    // Partial tile in fragment order: float4 number (i * 8 + j) * 256 + tid.
-    float4v* mine = reinterpret_cast<float4v*>(partials) +
-                    (static_cast<int64_t>(tile_local) * k_splits + split) * (TM * TN / 4) + tid;
-#pragma unroll
-    for (int i = 0; i < 8; ++i)
-#pragma unroll
-      for (int j = 0; j < 8; ++j) mine[(i * 8 + j) * kThreads] = acc[i][j];
-    // Publish: the barrier waits for every wavefront's stores to reach L2; then one thread makes
-    // them visible device-wide (one L2 write-back per workgroup instead of one per wavefront),
-    // draws the ticket and, if it is the last one, discards stale cached lines before anyone reads.
-    __syncthreads();
-    unsigned int* flag = reinterpret_cast<unsigned int*>(lds);   // LDS is free: the loop ended with a barrier
-    if (tid == 0) {
-      __threadfence();
-      const unsigned int ticket = atomicAdd(tickets + tile_local, 1u);
-      if (ticket == static_cast<unsigned int>(k_splits - 1)) __threadfence();
-      *flag = ticket;
+    // One K step; kFirst: the item's first (accumulators start from zero, and the stores of the tile before may still
+    // be in flight behind the loads this step waits for).
+    auto k_step = [&](auto first_tag) {
+      constexpr bool kFirst = decltype(first_tag)::value;
+      const uint32_t cur = parity * kStageBytes, nxt = cur ^ kStageBytes;
+      // The loads move on one step: within the tile, or to the next tile's step 0, or, with nothing to follow, not at
+      // all (the last step is fetched again, into a buffer nobody reads any more: no branches around the loads).
+      uint32_t advance = kRowBytes;
+      if (fetch_kt + 1 < kt_end) {
+        ++fetch_kt;
+      } else {
+        advance = 0;
+        if (has_next) {
+          fetch_kt = 0;
+          aim(next_tm, next_tn, 0);
+        }
+      }
+      static_for<0, 64>([&](auto ic) {
+        constexpr int n = decltype(ic)::value;
+        if constexpr (kFirst) mfma_first(acc[n >> 3][n & 7], f0.b[n & 7], f0.a[n >> 3]);
+        else mfma(acc[n >> 3][n & 7], f0.b[n & 7], f0.a[n >> 3]);
+        if constexpr ((n & 3) == 1) read_frag<(n >> 2)>(f1, a_hi + cur, b_hi + cur);
+        if constexpr ((n & 3) == 3) voff[n >> 2] += advance;
+      });
+      // Memory operations complete in issue order, so "at most kTileStores outstanding" means that the loads issued
+      // before those stores have landed.
+      if (kFirst && stores_behind) asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(kTileStores<kBf16Out>) : "memory");
+      else asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+      __builtin_amdgcn_s_barrier();
+      static_for<0, 64>([&](auto ic) {
+        constexpr int n = decltype(ic)::value;
+        mfma(acc[n >> 3][n & 7], f1.b[n & 7], f1.a[n >> 3]);
+        if constexpr ((n & 3) == 1) read_frag<(n >> 2)>(f0, a_lo + nxt, b_lo + nxt);
+        if constexpr ((n & 3) == 3) issue(std::integral_constant<int, (n >> 2)>{}, static_cast<int>(parity));
+      });
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+      parity ^= 1u;
+    };
+    k_step(std::true_type{});
+    for (int kt = kt_begin + 1; kt < kt_end; ++kt) k_step(std::false_type{});
+
+    // Everything below is computed here, per tile: were the compiler to move the output stage's loop-invariant
+    // address arithmetic in front of the stream, it would have to keep it in registers through the K steps, which
+    // have none to spare.
+    int wm = wave >> 1, wn = wave & 1;
+    asm volatile("" : "+s"(wm), "+s"(wn));
+    const int lane = lane_id(), tid = (wm * 2 + wn) * 64 + lane;
+    // Tensor-level decode scales on the finished sums (App. B.3, after Eq. 5).
+    const TensorScales out_scale{a_ts, b_ts, a_ts_per_row, b_ts_per_row};
+    const int64_t m0 = static_cast<int64_t>(tm) * TM, n0 = static_cast<int64_t>(tn) * TN;
+    const int Mt = static_cast<int>(M - m0 < TM ? M - m0 : TM);
+    const int Nt = static_cast<int>(N - n0 < TN ? N - n0 : TN);
+    // The MFMA results must have left the pipe before ordinary instructions read the accumulators (the compiler
+    // cannot see into the assembly statements to insert these wait states itself).  With nothing to follow, the
+    // trailing global->LDS loads must have landed before LDS is reused or the wavefront ends; otherwise the next
+    // tile's first K step is in LDS by now and its second on its way there.
+    if (has_next) {
+      asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+    } else {
+      asm volatile("s_waitcnt vmcnt(0)\n\ts_nop 15\n\ts_nop 15" ::: "memory");
+      __syncthreads();
     }
-    __syncthreads();
-    if (*flag != static_cast<unsigned int>(k_splits - 1)) return;
-    const float4v* all = reinterpret_cast<const float4v*>(partials) +
-                         static_cast<int64_t>(tile_local) * k_splits * (TM * TN / 4) + tid;
-    // acc = ((p0 + p1) + p2) + ...: every partial is fetched with 16 independent loads in flight.
-    for (int sp = 0; sp < k_splits; ++sp) {
-      const float4v* part = all + static_cast<int64_t>(sp) * (TM * TN / 4);
+
+    if (k_splits > 1) {   // has_next is false then
+      // Partial tile in fragment order: float4 number (i * 8 + j) * 256 + tid.
+      float4v* mine = reinterpret_cast<float4v*>(partials) +
+                      (static_cast<int64_t>(tile_local) * k_splits + split) * (TM * TN / 4) + tid;
 #pragma unroll
-      for (int h = 0; h < 4; ++h) {
-        float4v t[2][8];
+      for (int i = 0; i < 8; ++i)
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+        for (int j = 0; j < 8; ++j) mine[(i * 8 + j) * kThreads] = acc[i][j];
+      // Publish: the barrier waits for every wavefront's stores to reach L2; then one thread makes
+      // them visible device-wide (one L2 write-back per workgroup instead of one per wavefront),
+      // draws the ticket and, if it is the last one, discards stale cached lines before anyone reads.
+      __syncthreads();
+      unsigned int* flag = reinterpret_cast<unsigned int*>(lds);   // LDS is free: the loop ended with a barrier
+      if (tid == 0) {
+        __threadfence();
+        const unsigned int ticket = atomicAdd(tickets + tile_local, 1u);
+        if (ticket == static_cast<unsigned int>(k_splits - 1)) __threadfence();
+        *flag = ticket;
+      }
+      __syncthreads();
+      if (*flag != static_cast<unsigned int>(k_splits - 1)) return;
+      const float4v* all = reinterpret_cast<const float4v*>(partials) +
+                           static_cast<int64_t>(tile_local) * k_splits * (TM * TN / 4) + tid;
+      // acc = ((p0 + p1) + p2) + ...: every partial is fetched with 16 independent loads in flight.
+      for (int sp = 0; sp < k_splits; ++sp) {
+        const float4v* part = all + static_cast<int64_t>(sp) * (TM * TN / 4);
 #pragma unroll
-          for (int j = 0; j < 8; ++j) t[i][j] = part[((h * 2 + i) * 8 + j) * kThreads];
+        for (int h = 0; h < 4; ++h) {
+          float4v t[2][8];
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+          for (int i = 0; i < 2; ++i)
 #pragma unroll
-          for (int j = 0; j < 8; ++j) acc[h * 2 + i][j] = sp == 0 ? t[i][j] : acc[h * 2 + i][j] + t[i][j];
+            for (int j = 0; j < 8; ++j) t[i][j] = part[((h * 2 + i) * 8 + j) * kThreads];
+#pragma unroll
+          for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) acc[h * 2 + i][j] = sp == 0 ? t[i][j] : acc[h * 2 + i][j] + t[i][j];
+        }
       }
     }
+    store_wave_block<kBf16Out>(acc, out_scale, Dv, ldd, accumulate, m0 + wm * 128, n0 + wn * 128, Mt - wm * 128, Nt - wn * 128,
+                               lane);
+    if (!has_next) break;
+    stores_behind = Mt == TM && Nt == TN;   // every lane stored every block: the count is known
+    item = next_item;
+    tm = next_tm;
+    tn = next_tn;
+    kt_begin = 0;
+    kt_end = KT;
+    lane_setup();
+    aim(tm, tn, fetch_kt);
   }
-
-  // Tensor-level decode scales on the finished sums (App. B.3, after Eq. 5).
-  const TensorScales out_scale{a_ts, b_ts, a_ts_per_row, b_ts_per_row};
-  const int Mt = static_cast<int>(M - m0 < TM ? M - m0 : TM);
-  const int Nt = static_cast<int>(N - n0 < TN ? N - n0 : TN);
-  store_wave_block<kBf16Out>(acc, out_scale, Dv, ldd, accumulate, m0 + wm * 128, n0 + wn * 128, Mt - wm * 128, Nt - wn * 128,
-                             lane);
 }
 
 }  // namespace
@@ -419,7 +505,9 @@ bool gemm_two_pass_usable(const GemmArgs& g) {
 static hipError_t launch_f16(bool bf16_out, const _Float16* a16, const _Float16* b16, const GemmArgs& g, int tiles_m,
                              int tiles_n, int tile_begin, int tile_count, int k_splits, float* partials,
                              unsigned int* tickets, hipStream_t s) {
-  const unsigned wgs = static_cast<unsigned>(tile_count) * static_cast<unsigned>(k_splits);
+  // More whole tiles than CUs: one workgroup per CU, each running its tiles as one stream of K steps.
+  unsigned wgs = static_cast<unsigned>(tile_count) * static_cast<unsigned>(k_splits);
+  if (k_splits == 1 && g.K / TK >= 2 && wgs > static_cast<unsigned>(kCUs)) wgs = kCUs;
   if (bf16_out) NVFP4_LAUNCH_F16(true); else NVFP4_LAUNCH_F16(false);
   return hipGetLastError();
 }

@@ -264,6 +264,21 @@ def test_gemm_ragged_shapes_all_ops(mnk):
         assert np.linalg.norm(ref - exact) <= 0.3 * np.linalg.norm(exact)
 
 
+@pytest.mark.parametrize("K", [64, 128, 192])
+def test_gemm_with_more_tiles_than_compute_units(K):
+    """17 x 18 tiles of 256 x 256, the last row and column of them ragged: with a workspace the FP16 kernel is launched
+    with one workgroup per CU, 50 of which run two tiles as one stream of K steps (K = 128: the shortest tile that
+    allows it; K = 192: an odd number of steps, so the LDS stage parity differs from tile to tile; K = 64: one step,
+    launched with a workgroup per tile instead)."""
+    M, N = 4112, 4368
+    xb = synth.normal_with_outliers(M, K, 1.0, 900 + K, frac=0.01)
+    wb = synth.normal(K, N, 0.02, 901 + K)
+    qx, rx = check_quantize(xb, nv.LAYOUT_ROW)
+    qw, rw = check_quantize(wb, nv.LAYOUT_COL, nv.BLOCK_16x16)
+    y = gemm_both_routes(qx, qw, nv.OP_FPROP, oracle.gemm_f64(rx["row"], rw["col"]))
+    assert y.shape == (M, N)
+
+
 def test_gemm_output_with_leading_dimension():
     xb, wb = synth.normal(32, 64, 1.0, 61), synth.normal(64, 48, 0.02, 62)
     qx, rx = check_quantize(xb, nv.LAYOUT_ROW)
