@@ -123,8 +123,8 @@ typedef struct nvfp4_qtensor {
   uint64_t rht_seed;        /* seed of the sign diagonal, if rotated */
   int32_t row_has_rht;      /* 0, or 16: the row copy is rotated along its columns (NVFP4_LAYOUT_ROW_RHT) */
   int32_t scale_per_row;    /* 0: tensor_scale is float[2]; 1: float[2 * outer] per copy (NVFP4_LAYOUT_ROW_SCALES) */
-  void* row_fp16;           /* NULL, or the row copy decoded to FP16 by nvfp4_predecode: [rows, cols] */
-  void* col_fp16;           /* NULL, or the col copy decoded to FP16 by nvfp4_predecode: [cols, rows] */
+  void* row_fp16;           /* NULL, or the row copy decoded to FP16 by nvfp4_predecode (rows x cols elements) */
+  void* col_fp16;           /* NULL, or the col copy decoded to FP16 by nvfp4_predecode (cols x rows elements) */
 } nvfp4_qtensor;
 
 /*
@@ -247,8 +247,10 @@ int nvfp4_gemm(const nvfp4_qtensor* a, const nvfp4_qtensor* b, int op, void* d, 
  *   q           host descriptor of a quantized NVFP4 tensor (not MXFP4); on success its row_fp16 / col_fp16 field
  *               is set to fp16_out, and nvfp4_gemm reads that instead of decoding (its workspace then only has to
  *               hold the operands still to decode, the counters and the partial tiles)
- *   fp16_out    device, 16-byte aligned, outer * K * 2 bytes ([rows, cols] for the row copy, [cols, rows] for the col
- *               copy, K-contiguous); owned by the caller, must stay valid while the descriptor points to it
+ *   fp16_out    device, 16-byte aligned, outer * K * 2 bytes (outer x K = rows x cols for the row copy, cols x rows for
+ *               the col copy; K must be a multiple of 64, NVFP4_ERR_BAD_SHAPE otherwise).  The elements are stored in
+ *               the order the GEMM kernel loads them (8 rows x 64 k per KiB), not row by row: the buffer is for
+ *               nvfp4_gemm only.  Owned by the caller, must stay valid while the descriptor points to it
  *   fp16_bytes  its size; NVFP4_ERR_WORKSPACE if too small
  * nvfp4_quantize into the same descriptor clears both fields (the codes change), as does any call that rewrites it.
  */

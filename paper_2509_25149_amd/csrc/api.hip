@@ -330,8 +330,8 @@ int nvfp4_predecode(nvfp4_qtensor* q, int which_copy, void* fp16_out, size_t fp1
   int64_t K = 0;
   const int rc = pick_operand(q, which_copy == NVFP4_COPY_COL, &op, &K);
   if (rc != NVFP4_OK) return rc;
-  if (K <= 0 || K % 16 || op.outer <= 0) return NVFP4_ERR_BAD_SHAPE;
-  if (!aligned(op.codes, 4) || !aligned(op.scales, 1)) return NVFP4_ERR_INVALID_ARG;
+  if (K <= 0 || K % 64 || op.outer <= 0) return NVFP4_ERR_BAD_SHAPE;   // the decoded layout is made of 8-row x 64-k pieces
+  if (!aligned(op.codes, 16) || !aligned(op.scales, 4)) return NVFP4_ERR_INVALID_ARG;
   if (fp16_bytes < static_cast<size_t>(op.outer) * static_cast<size_t>(K) * 2) return NVFP4_ERR_WORKSPACE;
   if (launch_predecode(op, K, fp16_out, static_cast<hipStream_t>(stream)) != hipSuccess) return NVFP4_ERR_HIP;
   if (which_copy == NVFP4_COPY_COL) q->col_fp16 = fp16_out; else q->row_fp16 = fp16_out;

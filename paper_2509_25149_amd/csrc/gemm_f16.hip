@@ -50,41 +50,75 @@ __device__ __forceinline__ half2v scale_h2(uint32_t e4m3_byte) {
   return r;
 }
 
-// A thread decodes kDecodeUnroll x 8 elements (a dword of codes -> 16 bytes of FP16 each), the pieces 256 dwords
-// apart: consecutive lanes read consecutive dwords and write consecutive 16-byte pieces, so every load and store
-// instruction of a wavefront covers one contiguous span, and a thread has all its loads in flight before its first
-// store.  Both operands are decoded by one launch.
-constexpr int kDecodeUnroll = 4;
+// Layout of a decoded operand ([outer, K] elements, K a multiple of 64): the pieces the GEMM loads with one
+// instruction -- 8 rows x 64 k = 1 KiB -- are contiguous, and the K steps of an 8-row block follow each other:
+//   byte address of element (r, k) = (((r / 8) * (K / 64) + k / 64) * 8 + r % 8) * 128 + position * 16 + (k % 8) * 2,
+//   position = (k % 64) / 8 ^ ((r >> 1) & 7),
+// i.e. the 16-byte chunks of a row's 128 bytes already sit where the GEMM's LDS swizzle wants them, so a load
+// instruction reads 1 KiB of consecutive addresses, lane l its bytes 16 l .. 16 l + 15.  Against rows of K * 2 bytes
+// (8 separate 128-byte pieces per instruction, K * 2 bytes apart, a stride that puts the pieces of all 256 tile
+// rows into few cache channels) the GEMM's K step took 5-10 % less time on the three 12B shapes (1.41 -> 1.27,
+// 1.22 -> 1.20, 1.42 -> 1.32 us by timestamps inside the kernel, same process, same data, identical results).
+//
+// The decode pass: a workgroup takes an 8-row block x 1024 k (16 K steps).  It reads the block's codes and scales
+// row by row (512 and 64 contiguous bytes per row), passes them through LDS, and writes the 16 KiB of FP16 in output
+// order, a thread 16 bytes at a time, consecutive threads consecutive addresses -- so that both sides of the pass
+// move whole cache lines.  (With each thread fetching the 8 bytes of codes behind its own 32 bytes of output, reads
+// came in 64-byte pieces K / 2 bytes apart and the pass took half as long again.)  Both operands are decoded by
+// one launch: the 8-row blocks of B follow those of A in the grid.
+constexpr int kDecodeSteps = 16;                        // K steps per workgroup
+constexpr int kDecodeCodeRow = kDecodeSteps * 32 + 32;  // bytes per row of codes in LDS; the 32 keep 8 rows off each other's banks
+constexpr int kDecodeScaleRow = kDecodeSteps * 4 + 4;   // likewise for the scales
 __global__ __launch_bounds__(256) void decode_f16_kernel(const uint8_t* __restrict__ a_codes,
-                                                         const uint8_t* __restrict__ a_scales, int64_t a_n8,
+                                                         const uint8_t* __restrict__ a_scales, int a_blocks,
                                                          _Float16* __restrict__ a_out,
                                                          const uint8_t* __restrict__ b_codes,
-                                                         const uint8_t* __restrict__ b_scales, int64_t b_n8,
-                                                         _Float16* __restrict__ b_out,
+                                                         const uint8_t* __restrict__ b_scales, int b_blocks,
+                                                         _Float16* __restrict__ b_out, int64_t K,
                                                          unsigned int* __restrict__ tickets) {
+  __shared__ __attribute__((aligned(16))) uint8_t lds_codes[8 * kDecodeCodeRow];
+  __shared__ __attribute__((aligned(4))) uint8_t lds_scales[8 * kDecodeScaleRow];
   // The split-K tickets of the GEMM launches that follow start at zero (256 of them at most).
   if (blockIdx.x == 0 && tickets) tickets[threadIdx.x] = 0u;
-  const int64_t base = static_cast<int64_t>(blockIdx.x) * (256 * kDecodeUnroll) + threadIdx.x;
-  uint32_t c[kDecodeUnroll];
-  uint32_t sc[kDecodeUnroll];
-  uint4* dst[kDecodeUnroll];
-#pragma unroll
-  for (int u = 0; u < kDecodeUnroll; ++u) {
-    int64_t i = base + u * 256;
-    const bool in_a = i < a_n8;
-    if (!in_a) i -= a_n8;
-    dst[u] = nullptr;
-    c[u] = 0u;
-    sc[u] = 0u;
-    if (in_a || i < b_n8) {
-      c[u] = reinterpret_cast<const uint32_t*>(in_a ? a_codes : b_codes)[i];
-      sc[u] = (in_a ? a_scales : b_scales)[i >> 1];
-      dst[u] = reinterpret_cast<uint4*>(in_a ? a_out : b_out) + i;
+  // consecutive workgroups walk along K: they read consecutive pieces of the same 8 rows and write consecutive 16 KiB
+  const int k_groups = static_cast<int>((K / 64 + kDecodeSteps - 1) / kDecodeSteps);
+  int blk = static_cast<int>(blockIdx.x) / k_groups;
+  const int k_group = static_cast<int>(blockIdx.x) - blk * k_groups;
+  const bool in_a = blk < a_blocks;
+  if (!in_a) blk -= a_blocks;
+  if (!in_a && blk >= b_blocks) return;   // (the lone workgroup of a launch that only zeroes the tickets)
+  const uint8_t* codes = in_a ? a_codes : b_codes;
+  const uint8_t* scales = in_a ? a_scales : b_scales;
+  uint4* out = reinterpret_cast<uint4*>(in_a ? a_out : b_out);
+  const int t = static_cast<int>(threadIdx.x);
+  const int KT = static_cast<int>(K / 64), kt0 = k_group * kDecodeSteps;
+  {
+    // codes: thread -> row t / 32, 32 elements (16 bytes) at k = 64 kt0 + 32 (t % 32)
+    const int row = t >> 5, piece = t & 31;
+    const int64_t k = static_cast<int64_t>(kt0) * 64 + piece * 32;
+    if (k < K)
+      *reinterpret_cast<uint4*>(lds_codes + row * kDecodeCodeRow + piece * 16) =
+          *reinterpret_cast<const uint4*>(codes + ((static_cast<int64_t>(blk) * 8 + row) * K + k) / 2);
+    // scales: threads 0..127 -> row t / 16, the four scale bytes of K step kt0 + t % 16
+    if (t < 128) {
+      const int srow = t >> 4, j = t & 15;
+      if (kt0 + j < KT)
+        *reinterpret_cast<uint32_t*>(lds_scales + srow * kDecodeScaleRow + j * 4) =
+            *reinterpret_cast<const uint32_t*>(scales + (static_cast<int64_t>(blk) * 8 + srow) * (K / 16) + static_cast<int64_t>(kt0 + j) * 4);
     }
   }
+  __syncthreads();
 #pragma unroll
-  for (int u = 0; u < kDecodeUnroll; ++u)
-    if (dst[u]) *dst[u] = dec8(c[u], scale_h2(sc[u]));
+  for (int u = 0; u < kDecodeSteps / 4; ++u) {
+    // 16-byte piece number o of the workgroup's output: K step kt0 + o / 64, row (o / 8) % 8, position o % 8
+    const int o = u * 256 + t;
+    const int step = o >> 6, r8 = (o >> 3) & 7, pos = o & 7;
+    if (kt0 + step >= KT) break;
+    const int chunk = pos ^ ((blk * 4 + (r8 >> 1)) & 7);   // = pos ^ ((row >> 1) & 7), row = 8 blk + r8
+    const uint32_t c = *reinterpret_cast<const uint32_t*>(lds_codes + r8 * kDecodeCodeRow + step * 32 + chunk * 4);
+    const uint32_t s4 = *reinterpret_cast<const uint32_t*>(lds_scales + r8 * kDecodeScaleRow + step * 4);
+    out[(static_cast<int64_t>(blk) * KT + kt0 + step) * 64 + r8 * 8 + pos] = dec8(c, scale_h2((s4 >> ((chunk >> 1) * 8)) & 0xffu));
+  }
 }
 
 // ---------------------------------------------------------------- pass 2: FP16 GEMM
@@ -113,6 +147,7 @@ __global__ __launch_bounds__(256) void decode_f16_kernel(const uint8_t* __restri
 constexpr int TM = 256, TN = 256, TK = 64;
 constexpr int kThreads = 256;
 constexpr int kRowBytes = TK * 2;
+constexpr int kPieceBytes = 8 * kRowBytes;      // what one load instruction moves: 8 rows of a K step, 1 KiB, contiguous in the decoded operand
 constexpr int kOperandBytes = TM * kRowBytes;   // 32 KiB
 constexpr int kStageBytes = 2 * kOperandBytes;  // 64 KiB
 constexpr int kLdsBytes = 2 * kStageBytes;
@@ -231,12 +266,12 @@ __global__ __launch_bounds__(kThreads) void gemm_f16_kernel(const _Float16* __re
     return wg;   // the tile's number within the launch
   };
 
-  // Direct-load sources: instruction q of wavefront w fills rows w * 64 + 8 q .. + 7 of a tile (lane -> row lane / 8,
-  // position lane % 8, i.e. chunk (lane % 8) ^ ((row >> 1) & 7); adding 8 q to the row leaves that term alone for even
-  // q and flips its bit 2 for odd q).  An address is a wave-uniform 64-bit base per operand tile plus a per-lane
-  // 32-bit offset per instruction (256 rows of K * 2 bytes: K < 2^21, checked on the host), which holds the row,
-  // the chunk and the K step being fetched.  A block of 8 rows past the end of an operand is replaced by the
-  // operand's last block (rows come in multiples of 16); it only feeds outputs that are never stored.
+  // Direct-load sources: instruction q of wavefront w fills rows w * 64 + 8 q .. + 7 of a tile, which the decoded
+  // operand holds as 1 KiB of consecutive bytes per K step, in LDS order (lane l: bytes 16 l .. 16 l + 15).  An address
+  // is a wave-uniform 64-bit base per operand tile plus a per-lane 32-bit offset per instruction (256 rows of K * 2
+  // bytes: K < 2^21, checked on the host), which holds the 8-row block and the K step being fetched.  A block past
+  // the end of an operand is replaced by the operand's last block (rows come in multiples of 16); it only feeds
+  // outputs that are never stored.
   // One instruction per load inside the loop (a single wavefront per SIMD issues in order: what it spends on anything
   // else, the matrix pipe waits): M0, the LDS destination, is written once per four loads; loads q % 4 = 1, 2, 3 reach
   // the next KiB through the instruction's immediate offset, which moves the LDS and the global address alike, so
@@ -246,14 +281,11 @@ __global__ __launch_bounds__(kThreads) void gemm_f16_kernel(const _Float16* __re
   // compiler could keep from before the first tile would have to live through every output stage, which needs the
   // registers itself, and end up in scratch memory, to be fetched back inside the K steps.
   const uint32_t lds0 = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(lds));
-  uint32_t lane_even = 0, lane_odd = 0;      // the lane's part of a load offset for even / odd q
+  uint32_t lane_bytes = 0;                   // the lane's part of a load offset
   uint32_t a_lo = 0, a_hi = 0, b_lo = 0, b_hi = 0;   // fragment addresses in stage 0: first / second 32 k of the step
   auto lane_setup = [&]() {
     const int lane = lane_id();
-    const int r0 = wave * 64 + (lane >> 3);
-    const uint32_t c0 = static_cast<uint32_t>((lane & 7) ^ ((r0 >> 1) & 7)) * 16u;
-    lane_even = static_cast<uint32_t>(lane >> 3) * static_cast<uint32_t>(K * 2) + c0;
-    lane_odd = static_cast<uint32_t>(lane >> 3) * static_cast<uint32_t>(K * 2) + (c0 ^ 64u);
+    lane_bytes = static_cast<uint32_t>(lane) * 16u;
     const int arow = (wave >> 1) * 128 + (lane & 15), brow = (wave & 1) * 128 + (lane & 15), lq = lane >> 4;
     a_lo = lds0 + swz(arow, lq);
     a_hi = lds0 + swz(arow, 4 + lq);
@@ -269,13 +301,14 @@ __global__ __launch_bounds__(kThreads) void gemm_f16_kernel(const _Float16* __re
     const int64_t m_first = static_cast<int64_t>(tm) * TM, n_first = static_cast<int64_t>(tn) * TN;
     base_a = reinterpret_cast<const char*>(A) + m_first * K * 2 - 3 * 1024;
     base_b = reinterpret_cast<const char*>(B) + n_first * K * 2 - 3 * 1024;
-    const uint32_t last_a = static_cast<uint32_t>(M - 8 - m_first), last_b = static_cast<uint32_t>(N - 8 - n_first);
+    // 8-row blocks counted from the tile's first; a block's K steps are K / 64 KiB
+    const uint32_t last_a = static_cast<uint32_t>(M - 8 - m_first) >> 3, last_b = static_cast<uint32_t>(N - 8 - n_first) >> 3;
 #pragma unroll
     for (int q = 0; q < 8; ++q) {
-      const uint32_t r = static_cast<uint32_t>(wave * 64 + q * 8);
-      const uint32_t fixed = static_cast<uint32_t>(3 - (q & 3)) * 1024u + static_cast<uint32_t>(kt) * kRowBytes;
-      voff[q] = ((q & 1) ? lane_odd : lane_even) + min(r, last_a) * static_cast<uint32_t>(K * 2) + fixed;
-      voff[8 + q] = ((q & 1) ? lane_odd : lane_even) + min(r, last_b) * static_cast<uint32_t>(K * 2) + fixed;
+      const uint32_t blk = static_cast<uint32_t>(wave * 8 + q);
+      const uint32_t fixed = static_cast<uint32_t>(3 - (q & 3)) * 1024u + static_cast<uint32_t>(kt) * kPieceBytes;
+      voff[q] = lane_bytes + min(blk, last_a) * static_cast<uint32_t>(K * 16) + fixed;
+      voff[8 + q] = lane_bytes + min(blk, last_b) * static_cast<uint32_t>(K * 16) + fixed;
     }
   };
   const uint32_t fill0 = lds0 + wave * 8192;   // this wavefront's 8 KiB of each operand tile
@@ -304,7 +337,7 @@ __global__ __launch_bounds__(kThreads) void gemm_f16_kernel(const _Float16* __re
   if (fetch_kt + 1 < kt_end) {
     ++fetch_kt;
 #pragma unroll
-    for (int q = 0; q < 16; ++q) voff[q] += kRowBytes;
+    for (int q = 0; q < 16; ++q) voff[q] += kPieceBytes;
   }
   static_for<0, 16>([&](auto q) { issue(q, 1); });
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -332,7 +365,7 @@ __global__ __launch_bounds__(kThreads) void gemm_f16_kernel(const _Float16* __re
       const uint32_t cur = parity * kStageBytes, nxt = cur ^ kStageBytes;
       // The loads move on one step: within the tile, or to the next tile's step 0, or, with nothing to follow, not at
       // all (the last step is fetched again, into a buffer nobody reads any more: no branches around the loads).
-      uint32_t advance = kRowBytes;
+      uint32_t advance = kPieceBytes;
       if (fetch_kt + 1 < kt_end) {
         ++fetch_kt;
       } else {
@@ -488,8 +521,8 @@ bool gemm_two_pass_usable(const GemmArgs& g) {
          reinterpret_cast<uintptr_t>(g.a.fp16) % 16 == 0 && reinterpret_cast<uintptr_t>(g.b.fp16) % 16 == 0 &&
          g.K < (int64_t{1} << 21) &&   // the kernel's 32-bit byte offsets inside a 256-row tile
          reinterpret_cast<uintptr_t>(g.workspace) % 256 == 0 && reinterpret_cast<uintptr_t>(g.a.codes) % 16 == 0 &&
-         reinterpret_cast<uintptr_t>(g.b.codes) % 16 == 0 && reinterpret_cast<uintptr_t>(g.a.scales) % 2 == 0 &&
-         reinterpret_cast<uintptr_t>(g.b.scales) % 2 == 0;
+         reinterpret_cast<uintptr_t>(g.b.codes) % 16 == 0 && reinterpret_cast<uintptr_t>(g.a.scales) % 4 == 0 &&
+         reinterpret_cast<uintptr_t>(g.b.scales) % 4 == 0;
 }
 
 #define NVFP4_LAUNCH_F16(BF16)                                                                                    \
@@ -513,11 +546,21 @@ static hipError_t launch_f16(bool bf16_out, const _Float16* a16, const _Float16*
 }
 #undef NVFP4_LAUNCH_F16
 
+// Grid of the decode pass for `blocks` 8-row blocks: a workgroup per block and group of kDecodeSteps K steps; at least
+// one, which zeroes the tickets.  False if that is more than a grid can hold (operands beyond 2^44 elements).
+static bool decode_grid(int64_t blocks, int64_t K, dim3* grid) {
+  const int64_t n = blocks * ((K / TK + kDecodeSteps - 1) / kDecodeSteps);
+  if (n > 0x7fffffff) return false;
+  *grid = dim3(static_cast<unsigned>(n > 0 ? n : 1));
+  return true;
+}
+
 hipError_t launch_predecode(const Operand& op, int64_t K, void* fp16_out, hipStream_t s) {
-  const int64_t n8 = op.outer * K / 8;
-  hipLaunchKernelGGL(decode_f16_kernel, dim3(static_cast<unsigned>((n8 + 256 * kDecodeUnroll - 1) / (256 * kDecodeUnroll))), dim3(256), 0, s,
-                     op.codes, op.scales, n8, static_cast<_Float16*>(fp16_out), op.codes, op.scales, int64_t{0},
-                     static_cast<_Float16*>(fp16_out), static_cast<unsigned int*>(nullptr));
+  dim3 grid;
+  if (!decode_grid(op.outer / 8, K, &grid)) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(decode_f16_kernel, grid, dim3(256), 0, s, op.codes, op.scales,
+                     static_cast<int>(op.outer / 8), static_cast<_Float16*>(fp16_out), op.codes, op.scales, 0,
+                     static_cast<_Float16*>(fp16_out), K, static_cast<unsigned int*>(nullptr));
   return hipGetLastError();
 }
 
@@ -534,10 +577,10 @@ hipError_t launch_gemm_two_pass(const GemmArgs& g, hipStream_t s) {
   float* partials = reinterpret_cast<float*>(ws + operand_bytes(rows_a, rows_b, K) + kTicketBytes);
   // One launch decodes what is still to decode and zeroes the tickets (with both operands decoded beforehand it is one
   // workgroup that only does the latter).
-  const int64_t na = rows_a * K / 8, nb = rows_b * K / 8;   // a_n8 is a multiple of 256 only if M*K is a multiple of 2048; the kernel does not need it
-  const int64_t nwg = (na + nb + 256 * kDecodeUnroll - 1) / (256 * kDecodeUnroll);
-  hipLaunchKernelGGL(decode_f16_kernel, dim3(static_cast<unsigned>(nwg > 0 ? nwg : 1)), dim3(256), 0, s, g.a.codes,
-                     g.a.scales, na, a_ws, g.b.codes, g.b.scales, nb, b_ws, tickets);
+  dim3 grid;
+  if (!decode_grid((rows_a + rows_b) / 8, K, &grid)) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(decode_f16_kernel, grid, dim3(256), 0, s, g.a.codes, g.a.scales,
+                     static_cast<int>(rows_a / 8), a_ws, g.b.codes, g.b.scales, static_cast<int>(rows_b / 8), b_ws, K, tickets);
   const int tiles_m = static_cast<int>((M + TM - 1) / TM), tiles_n = static_cast<int>((N + TN - 1) / TN);
   const int tiles = tiles_m * tiles_n;
   // One 256x256 tile keeps one CU busy (its LDS fits one workgroup).  Whole rounds of kCUs tiles
