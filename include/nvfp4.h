@@ -233,6 +233,8 @@ int nvfp4_quantize_with_amax(const void* x, int64_t rows, int64_t cols, int64_t 
  * then runs an FP16 MFMA GEMM with no decode work in its loop; with NULL or
  * too little room it runs a fused kernel that decodes inside the GEMM loop
  * (slower, no scratch).  Both give the same result up to FP32 summation order.
+ * (With both operands decoded beforehand by nvfp4_predecode and no split last
+ * round of tiles the FP16 GEMM needs nothing of the workspace and runs without.)
  * The workspace contents are scratch: undefined afterwards, free for reuse once
  * the call's kernels have run.
  */
@@ -246,7 +248,7 @@ int nvfp4_gemm(const nvfp4_qtensor* a, const nvfp4_qtensor* b, int op, void* d, 
  * nvfp4_gemm call on its two-pass route decodes the operand again.
  *   q           host descriptor of a quantized NVFP4 tensor (not MXFP4); on success its row_fp16 / col_fp16 field
  *               is set to fp16_out, and nvfp4_gemm reads that instead of decoding (its workspace then only has to
- *               hold the operands still to decode, the counters and the partial tiles)
+ *               hold the operands still to decode and the partial tiles)
  *   fp16_out    device, 16-byte aligned, outer * K * 2 bytes (outer x K = rows x cols for the row copy, cols x rows for
  *               the col copy; K must be a multiple of 64, NVFP4_ERR_BAD_SHAPE otherwise).  The elements are stored in
  *               the order the GEMM kernel loads them (8 rows x 64 k per KiB), not row by row: the buffer is for
@@ -257,8 +259,8 @@ int nvfp4_gemm(const nvfp4_qtensor* a, const nvfp4_qtensor* b, int op, void* d, 
 int nvfp4_predecode(nvfp4_qtensor* q, int which_copy, void* fp16_out, size_t fp16_bytes, nvfp4_stream_t stream);
 
 /* Scratch bytes that let nvfp4_gemm take its faster two-pass route (host pointer out):
- * (M + N) * K * 2 for the FP16 operands, 1 KiB of counters, and up to 64 MiB of FP32 partial
- * tiles when the last round of 256x256 output tiles is partial and gets split along K.
+ * (M + N) * K * 2 for the FP16 operands and up to 64 MiB of FP32 partial tiles when the last
+ * round of 256x256 output tiles is partial and gets split along K.
  * Two calls that overlap in time on one GPU need a workspace each. */
 int nvfp4_gemm_workspace_bytes(int64_t m, int64_t n, int64_t k, size_t* workspace_bytes);
 

@@ -21,8 +21,7 @@ namespace nvfp4 {
 // timestamps inside the kernel; the Wgrad call 1.359 against 1.347 ms).  A wavefront's stores leave at about 1 KiB per
 // 150 cycles whatever else the chip does (the four wavefronts of a CU share one path to the L2: 128 KiB of bf16 per
 // tile take 2.3 us, another 2.6 us go to reading, scaling and converting the 256 sums), so what bounds
-// the output stage is what a wavefront has to issue, not memory bandwidth: hence no predicates and no address
-// arithmetic per store when the whole block exists.  Must be called by all 64 lanes.  (Reordering the bf16 block through LDS into 256-byte row pieces was tried
+// the output stage is what a wavefront has to issue, not memory bandwidth.  Must be called by all 64 lanes.  (Reordering the bf16 block through LDS into 256-byte row pieces was tried
 // with ordinary stores and measured no faster.)
 typedef uint32_t u32x4v __attribute__((ext_vector_type(4)));
 
@@ -48,9 +47,11 @@ __device__ __forceinline__ float4v scale4(const TensorScales& ts, float uniform,
 
 // kVec: an operand carries one scale per row; the lane's 8 rows (m = 16 i + l16) and 8 x 4 columns (n = 16 j + 4 lq + r)
 // then take their factors from the vectors, loaded once.  Otherwise the product a[0] * b[0] serves every output.
-// kFull: all 128 x 128 exist, so no store is predicated.  Either way a lane's addresses are one pointer (its row l16,
-// its first column) plus i * 16 rows plus a constant per j, which the stores carry as their immediate offsets.
-template <bool kBf16Out, bool kVec, bool kFull>
+// A lane's addresses are one pointer (its row l16, its first column) plus i * 16 rows plus a constant per j, which the
+// stores carry as their immediate offsets.  (A variant without the predicates for blocks that exist whole measured no
+// faster.)  A kernel should contain this once: where a second use of the sums sits in another branch, the compiler
+// reads all 256 out of the accumulation registers ahead of the branch, into registers it does not have.
+template <bool kBf16Out, bool kVec>
 __device__ __forceinline__ void store_wave_block_impl(float4v (&acc)[8][8], const TensorScales ts, void* __restrict__ Dv, int64_t ldd,
                                                       bool accumulate, int64_t row0, int64_t col0, int rows, int cols, int lane) {
   const int l16 = lane & 15, lq = lane >> 4;
@@ -80,7 +81,7 @@ __device__ __forceinline__ void store_wave_block_impl(float4v (&acc)[8][8], cons
   const int64_t lane_first = (row0 + l16) * ldd + col0 + nl;
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
-    const bool row_in = kFull || i * 16 + l16 < rows;
+    const bool row_in = i * 16 + l16 < rows;
     if (kBf16Out) {
       uint16_t* d_row = static_cast<uint16_t*>(Dv) + lane_first + i * 16 * ldd;
 #pragma unroll
@@ -94,13 +95,13 @@ __device__ __forceinline__ void store_wave_block_impl(float4v (&acc)[8][8], cons
         const auto s1 = __builtin_amdgcn_permlane16_swap(a1, b1, false, false);
         const u32x4v o = {s0[0], s1[0], s0[1], s1[1]};
         // columns come in multiples of 16, so the 8 columns are in or out together
-        if (row_in && (kFull || j * 16 + nl < cols)) *reinterpret_cast<u32x4v*>(d_row + j * 16) = o;
+        if (row_in && j * 16 + nl < cols) *reinterpret_cast<u32x4v*>(d_row + j * 16) = o;
       }
     } else {
       float* d_row = static_cast<float*>(Dv) + lane_first + i * 16 * ldd;
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
-        if (row_in && (kFull || j * 16 + nl < cols)) {  // columns come in multiples of 16, so the 4 columns are in or out together
+        if (row_in && j * 16 + nl < cols) {  // columns come in multiples of 16, so the 4 columns are in or out together
           float4v v = acc[i][j] * scale(i, j);
           float* d = d_row + j * 16;
           if (accumulate) v += *reinterpret_cast<const float4v*>(d);
@@ -111,17 +112,11 @@ __device__ __forceinline__ void store_wave_block_impl(float4v (&acc)[8][8], cons
   }
 }
 
+// The per-tensor form, for kernels that have no other.
 template <bool kBf16Out>
 __device__ __forceinline__ void store_wave_block(float4v (&acc)[8][8], const TensorScales ts, void* __restrict__ Dv, int64_t ldd,
                                                  bool accumulate, int64_t row0, int64_t col0, int rows, int cols, int lane) {
-  const bool full = rows >= 128 && cols >= 128;
-  if (ts.a_per_row || ts.b_per_row) {   // uniform over the launch
-    store_wave_block_impl<kBf16Out, true, false>(acc, ts, Dv, ldd, accumulate, row0, col0, rows, cols, lane);
-  } else if (full) {                    // uniform over the wavefront
-    store_wave_block_impl<kBf16Out, false, true>(acc, ts, Dv, ldd, accumulate, row0, col0, rows, cols, lane);
-  } else {
-    store_wave_block_impl<kBf16Out, false, false>(acc, ts, Dv, ldd, accumulate, row0, col0, rows, cols, lane);
-  }
+  store_wave_block_impl<kBf16Out, false>(acc, ts, Dv, ldd, accumulate, row0, col0, rows, cols, lane);
 }
 
 }  // namespace nvfp4

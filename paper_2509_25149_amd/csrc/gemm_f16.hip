@@ -74,19 +74,16 @@ __global__ __launch_bounds__(256) void decode_f16_kernel(const uint8_t* __restri
                                                          _Float16* __restrict__ a_out,
                                                          const uint8_t* __restrict__ b_codes,
                                                          const uint8_t* __restrict__ b_scales, int b_blocks,
-                                                         _Float16* __restrict__ b_out, int64_t K,
-                                                         unsigned int* __restrict__ tickets) {
+                                                         _Float16* __restrict__ b_out, int64_t K) {
   __shared__ __attribute__((aligned(16))) uint8_t lds_codes[8 * kDecodeCodeRow];
   __shared__ __attribute__((aligned(4))) uint8_t lds_scales[8 * kDecodeScaleRow];
-  // The split-K tickets of the GEMM launches that follow start at zero (256 of them at most).
-  if (blockIdx.x == 0 && tickets) tickets[threadIdx.x] = 0u;
   // consecutive workgroups walk along K: they read consecutive pieces of the same 8 rows and write consecutive 16 KiB
   const int k_groups = static_cast<int>((K / 64 + kDecodeSteps - 1) / kDecodeSteps);
   int blk = static_cast<int>(blockIdx.x) / k_groups;
   const int k_group = static_cast<int>(blockIdx.x) - blk * k_groups;
   const bool in_a = blk < a_blocks;
   if (!in_a) blk -= a_blocks;
-  if (!in_a && blk >= b_blocks) return;   // (the lone workgroup of a launch that only zeroes the tickets)
+  if (!in_a && blk >= b_blocks) return;
   const uint8_t* codes = in_a ? a_codes : b_codes;
   const uint8_t* scales = in_a ? a_scales : b_scales;
   uint4* out = reinterpret_cast<uint4*>(in_a ? a_out : b_out);
@@ -211,6 +208,17 @@ __device__ __forceinline__ int lane_id() {
   return lane;
 }
 
+// Tile number pid of the 256x256 tiling -> tile row and column: the tiles are walked in bands of 8 tile rows, column by
+// column within a band.
+__device__ __forceinline__ void tile_coordinates(int pid, int tiles_m, int tiles_n, int& tm, int& tn) {
+  constexpr int kBand = 8;
+  const int band = pid / (kBand * tiles_n);
+  const int band_rows = min(kBand, tiles_m - band * kBand);
+  const int in_band = pid - band * kBand * tiles_n;
+  tm = band * kBand + in_band % band_rows;
+  tn = in_band / band_rows;
+}
+
 // The first MFMA of an accumulator in a work item: C = 0, so the 256 accumulation registers are never cleared.
 __device__ __forceinline__ void mfma_first(float4v& acc, const half8v& b, const half8v& a) {
   asm volatile("v_mfma_f32_16x16x32_f16 %0, %1, %2, 0" : "=a"(acc) : "v"(b), "v"(a));
@@ -234,19 +242,21 @@ constexpr int kTileStores = kBf16Out ? 24 : 48;
 // otherwise.
 //
 // k_splits > 1 (one work item per workgroup) fills the chip during a last, partial round of tiles: a tile is shared by
-// k_splits workgroups, each summing one contiguous range of K steps.  Every one of
-// them stores its FP32 partial tile to `partials`, then takes a ticket from the tile's counter
-// (zeroed by the decode pass of the same call); the workgroup that draws the last ticket adds the
-// partials in split order - a fixed order, so the result does not depend on which workgroup
-// finishes last - and stores the tile.  Nobody waits for anybody, so the scheme cannot deadlock
-// whatever else shares the GPU.
-template <bool kBf16Out>
+// k_splits workgroups, each summing one contiguous range of K steps and storing its FP32 partial tile to
+// `partials`; splitk_sum_kernel, launched behind this one, adds the partials in split order and stores the tiles.
+// (The sum used to be done here, by whichever workgroup of a tile finished last, found by a ticket counter: by
+// timestamps inside the kernel, of the 127 us such a launch took on 64 tiles x 4 splits at K = 8192, the K steps
+// were 48, the partial stores 7, the device-wide fence and the ticket 10, and one workgroup fetching and adding the
+// 1 MiB that four XCDs had written 50 -- with 16 loads in flight per thread, and 90 with 64.)
+// kRowScales: an operand carries a tensor-level scale per row (uniform over a launch, and a different output stage).
+// kSplit: k_splits > 1; the output stage is the store of the partial tile (kBf16Out and kRowScales are false then).
+template <bool kBf16Out, bool kRowScales, bool kSplit>
 __global__ __launch_bounds__(kThreads) void gemm_f16_kernel(const _Float16* __restrict__ A, const _Float16* __restrict__ B,
                                                             int64_t M, int64_t N, int64_t K, const float* __restrict__ a_ts,
                                                             const float* __restrict__ b_ts, void* __restrict__ Dv,
                                                             int64_t ldd, bool accumulate, int tiles_m, int tiles_n,
                                                             int tile_begin, int tile_count, int k_splits, float* partials,
-                                                            unsigned int* tickets, bool a_ts_per_row, bool b_ts_per_row) {
+                                                            bool a_ts_per_row, bool b_ts_per_row) {
   extern __shared__ __attribute__((aligned(16))) char lds[];
 
   const int wave = __builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x) >> 6);
@@ -256,13 +266,7 @@ __global__ __launch_bounds__(kThreads) void gemm_f16_kernel(const _Float16* __re
   // of a later round continue the first round's, 8 | gridDim.x, so the low three bits stay the XCD.)
   auto locate = [&](int wg, int& tm, int& tn) -> int {
     if ((tile_count & 7) == 0) wg = (wg & 7) * (tile_count >> 3) + (wg >> 3);
-    const int pid = tile_begin + wg;
-    constexpr int kBand = 8;
-    const int band = pid / (kBand * tiles_n);
-    const int band_rows = min(kBand, tiles_m - band * kBand);
-    const int in_band = pid - band * kBand * tiles_n;
-    tm = band * kBand + in_band % band_rows;
-    tn = in_band / band_rows;
+    tile_coordinates(tile_begin + wg, tiles_m, tiles_n, tm, tn);
     return wg;   // the tile's number within the launch
   };
 
@@ -421,7 +425,7 @@ __global__ __launch_bounds__(kThreads) void gemm_f16_kernel(const _Float16* __re
       __syncthreads();
     }
 
-    if (k_splits > 1) {   // has_next is false then
+    if constexpr (kSplit) {   // has_next is false
       // Partial tile in fragment order: float4 number (i * 8 + j) * 256 + tid.
       float4v* mine = reinterpret_cast<float4v*>(partials) +
                       (static_cast<int64_t>(tile_local) * k_splits + split) * (TM * TN / 4) + tid;
@@ -429,40 +433,11 @@ __global__ __launch_bounds__(kThreads) void gemm_f16_kernel(const _Float16* __re
       for (int i = 0; i < 8; ++i)
 #pragma unroll
         for (int j = 0; j < 8; ++j) mine[(i * 8 + j) * kThreads] = acc[i][j];
-      // Publish: the barrier waits for every wavefront's stores to reach L2; then one thread makes
-      // them visible device-wide (one L2 write-back per workgroup instead of one per wavefront),
-      // draws the ticket and, if it is the last one, discards stale cached lines before anyone reads.
-      __syncthreads();
-      unsigned int* flag = reinterpret_cast<unsigned int*>(lds);   // LDS is free: the loop ended with a barrier
-      if (tid == 0) {
-        __threadfence();
-        const unsigned int ticket = atomicAdd(tickets + tile_local, 1u);
-        if (ticket == static_cast<unsigned int>(k_splits - 1)) __threadfence();
-        *flag = ticket;
-      }
-      __syncthreads();
-      if (*flag != static_cast<unsigned int>(k_splits - 1)) return;
-      const float4v* all = reinterpret_cast<const float4v*>(partials) +
-                           static_cast<int64_t>(tile_local) * k_splits * (TM * TN / 4) + tid;
-      // acc = ((p0 + p1) + p2) + ...: every partial is fetched with 16 independent loads in flight.
-      for (int sp = 0; sp < k_splits; ++sp) {
-        const float4v* part = all + static_cast<int64_t>(sp) * (TM * TN / 4);
-#pragma unroll
-        for (int h = 0; h < 4; ++h) {
-          float4v t[2][8];
-#pragma unroll
-          for (int i = 0; i < 2; ++i)
-#pragma unroll
-            for (int j = 0; j < 8; ++j) t[i][j] = part[((h * 2 + i) * 8 + j) * kThreads];
-#pragma unroll
-          for (int i = 0; i < 2; ++i)
-#pragma unroll
-            for (int j = 0; j < 8; ++j) acc[h * 2 + i][j] = sp == 0 ? t[i][j] : acc[h * 2 + i][j] + t[i][j];
-        }
-      }
+      return;
+    } else {
+      store_wave_block_impl<kBf16Out, kRowScales>(acc, out_scale, Dv, ldd, accumulate, m0 + wm * 128, n0 + wn * 128,
+                                                  Mt - wm * 128, Nt - wn * 128, lane);
     }
-    store_wave_block<kBf16Out>(acc, out_scale, Dv, ldd, accumulate, m0 + wm * 128, n0 + wn * 128, Mt - wm * 128, Nt - wn * 128,
-                               lane);
     if (!has_next) break;
     stores_behind = Mt == TM && Nt == TN;   // every lane stored every block: the count is known
     item = next_item;
@@ -475,11 +450,48 @@ __global__ __launch_bounds__(kThreads) void gemm_f16_kernel(const _Float16* __re
   }
 }
 
+// The sums over K of the tiles a split-K launch covered: one wavefront per tile and 128 x 128 block of it (the block
+// one wavefront of gemm_f16_kernel holds, in the same register layout, which is the order the partial tiles are
+// stored in), acc = ((p0 + p1) + p2) + ... in split order, then the same output stage.
+template <bool kBf16Out, bool kRowScales>
+__global__ __launch_bounds__(64) void splitk_sum_kernel(const float* __restrict__ partials, int k_splits, int64_t M, int64_t N,
+                                                        const float* __restrict__ a_ts, const float* __restrict__ b_ts,
+                                                        void* __restrict__ Dv, int64_t ldd, bool accumulate, int tiles_m,
+                                                        int tiles_n, int tile_begin, bool a_ts_per_row, bool b_ts_per_row) {
+  const int tile_local = static_cast<int>(blockIdx.x) >> 2, wave = static_cast<int>(blockIdx.x) & 3;
+  const int lane = static_cast<int>(threadIdx.x), wm = wave >> 1, wn = wave & 1;
+  int tm, tn;
+  tile_coordinates(tile_begin + tile_local, tiles_m, tiles_n, tm, tn);
+  const float4v* all = reinterpret_cast<const float4v*>(partials) +
+                       static_cast<int64_t>(tile_local) * k_splits * (TM * TN / 4) + wave * 64 + lane;
+  float4v acc[8][8];
+  for (int sp = 0; sp < k_splits; ++sp) {
+    const float4v* part = all + static_cast<int64_t>(sp) * (TM * TN / 4);
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {   // 32 loads in flight
+      float4v t[4][8];
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) t[i][j] = part[((h * 4 + i) * 8 + j) * kThreads];
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[h * 4 + i][j] = sp == 0 ? t[i][j] : acc[h * 4 + i][j] + t[i][j];
+    }
+  }
+  const TensorScales out_scale{a_ts, b_ts, a_ts_per_row, b_ts_per_row};
+  const int64_t m0 = static_cast<int64_t>(tm) * TM, n0 = static_cast<int64_t>(tn) * TN;
+  const int Mt = static_cast<int>(M - m0 < TM ? M - m0 : TM);
+  const int Nt = static_cast<int>(N - n0 < TN ? N - n0 : TN);
+  store_wave_block_impl<kBf16Out, kRowScales>(acc, out_scale, Dv, ldd, accumulate, m0 + wm * 128, n0 + wn * 128,
+                                              Mt - wm * 128, Nt - wn * 128, lane);
+}
+
 }  // namespace
 
-// Workspace: [A as FP16][B as FP16][256 tickets][split-K partial tiles], each part 256-byte aligned.
+// Workspace: [A as FP16][B as FP16][split-K partial tiles], each part 256-byte aligned.
 constexpr int kCUs = 256;
-constexpr size_t kTicketBytes = kCUs * sizeof(unsigned int);
 constexpr size_t kPartialTileBytes = static_cast<size_t>(TM) * TN * sizeof(float);
 
 // How the last, partial round of 256x256 tiles is run: `tail` tiles (0 = there is none to treat
@@ -507,51 +519,72 @@ static size_t operand_bytes(int64_t rows_a, int64_t rows_b, int64_t K) {
 
 size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t K) {
   const TailPlan p = plan_tail(M, N, K);
-  return operand_bytes(M, N, K) + kTicketBytes + static_cast<size_t>(p.tail) * p.splits * kPartialTileBytes;
+  return operand_bytes(M, N, K) + static_cast<size_t>(p.tail) * p.splits * kPartialTileBytes;
 }
 
 static size_t workspace_need(const GemmArgs& g) {
   const TailPlan p = plan_tail(g.a.outer, g.b.outer, g.K);
-  return operand_bytes(g.a.fp16 ? 0 : g.a.outer, g.b.fp16 ? 0 : g.b.outer, g.K) + kTicketBytes +
+  return operand_bytes(g.a.fp16 ? 0 : g.a.outer, g.b.fp16 ? 0 : g.b.outer, g.K) +
          static_cast<size_t>(p.tail) * p.splits * kPartialTileBytes;
 }
 
 bool gemm_two_pass_usable(const GemmArgs& g) {
-  return g.workspace && g.workspace_bytes >= workspace_need(g) && (g.K % TK) == 0 &&
+  // (With both operands decoded beforehand and no partial last round of tiles nothing is needed of the workspace.)
+  const size_t need = workspace_need(g);
+  const bool room = need == 0 || (g.workspace && g.workspace_bytes >= need && reinterpret_cast<uintptr_t>(g.workspace) % 256 == 0);
+  return room && (g.K % TK) == 0 &&
          reinterpret_cast<uintptr_t>(g.a.fp16) % 16 == 0 && reinterpret_cast<uintptr_t>(g.b.fp16) % 16 == 0 &&
          g.K < (int64_t{1} << 21) &&   // the kernel's 32-bit byte offsets inside a 256-row tile
-         reinterpret_cast<uintptr_t>(g.workspace) % 256 == 0 && reinterpret_cast<uintptr_t>(g.a.codes) % 16 == 0 &&
+         reinterpret_cast<uintptr_t>(g.a.codes) % 16 == 0 &&
          reinterpret_cast<uintptr_t>(g.b.codes) % 16 == 0 && reinterpret_cast<uintptr_t>(g.a.scales) % 4 == 0 &&
          reinterpret_cast<uintptr_t>(g.b.scales) % 4 == 0;
 }
 
-#define NVFP4_LAUNCH_F16(BF16)                                                                                    \
+#define NVFP4_LAUNCH_F16(BF16, ROWSCALES, SPLIT)                                                                  \
   do {                                                                                                            \
     static PerDeviceOnce once;                                                                                    \
-    const hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(&gemm_f16_kernel<BF16>), kLdsBytes, once); \
+    const hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(&gemm_f16_kernel<BF16, ROWSCALES, SPLIT>), kLdsBytes, once); \
     if (e != hipSuccess) return e;                                                                                \
-    hipLaunchKernelGGL((gemm_f16_kernel<BF16>), dim3(wgs), dim3(kThreads), kLdsBytes, s, a16, b16,                   \
+    hipLaunchKernelGGL((gemm_f16_kernel<BF16, ROWSCALES, SPLIT>), dim3(wgs), dim3(kThreads), kLdsBytes, s, a16, b16, \
                        g.a.outer, g.b.outer, g.K, g.a.ts, g.b.ts, g.d, g.ldd, g.accumulate, tiles_m, tiles_n,     \
-                       tile_begin, tile_count, k_splits, partials, tickets, g.a.ts_per_row != 0, g.b.ts_per_row != 0);    \
+                       tile_begin, tile_count, k_splits, partials, g.a.ts_per_row != 0, g.b.ts_per_row != 0);      \
   } while (0)
 
+// Tiles [tile_begin, tile_begin + tile_count); k_splits > 1: each shared by that many workgroups, summed by a second launch.
 static hipError_t launch_f16(bool bf16_out, const _Float16* a16, const _Float16* b16, const GemmArgs& g, int tiles_m,
-                             int tiles_n, int tile_begin, int tile_count, int k_splits, float* partials,
-                             unsigned int* tickets, hipStream_t s) {
+                             int tiles_n, int tile_begin, int tile_count, int k_splits, float* partials, hipStream_t s) {
   // More whole tiles than CUs: one workgroup per CU, each running its tiles as one stream of K steps.
   unsigned wgs = static_cast<unsigned>(tile_count) * static_cast<unsigned>(k_splits);
   if (k_splits == 1 && g.K / TK >= 2 && wgs > static_cast<unsigned>(kCUs)) wgs = kCUs;
-  if (bf16_out) NVFP4_LAUNCH_F16(true); else NVFP4_LAUNCH_F16(false);
+  const bool row_scales = g.a.ts_per_row != 0 || g.b.ts_per_row != 0;
+  if (k_splits > 1) {
+    NVFP4_LAUNCH_F16(false, false, true);
+    const dim3 grid(static_cast<unsigned>(tile_count) * 4);
+#define NVFP4_LAUNCH_SUM(BF16, ROWSCALES)                                                                              \
+  hipLaunchKernelGGL((splitk_sum_kernel<BF16, ROWSCALES>), grid, dim3(64), 0, s, partials, k_splits, g.a.outer, g.b.outer, \
+                     g.a.ts, g.b.ts, g.d, g.ldd, g.accumulate, tiles_m, tiles_n, tile_begin, g.a.ts_per_row != 0,      \
+                     g.b.ts_per_row != 0)
+    if (bf16_out) {
+      if (row_scales) NVFP4_LAUNCH_SUM(true, true); else NVFP4_LAUNCH_SUM(true, false);
+    } else {
+      if (row_scales) NVFP4_LAUNCH_SUM(false, true); else NVFP4_LAUNCH_SUM(false, false);
+    }
+#undef NVFP4_LAUNCH_SUM
+  } else if (row_scales) {
+    if (bf16_out) NVFP4_LAUNCH_F16(true, true, false); else NVFP4_LAUNCH_F16(false, true, false);
+  } else {
+    if (bf16_out) NVFP4_LAUNCH_F16(true, false, false); else NVFP4_LAUNCH_F16(false, false, false);
+  }
   return hipGetLastError();
 }
 #undef NVFP4_LAUNCH_F16
 
-// Grid of the decode pass for `blocks` 8-row blocks: a workgroup per block and group of kDecodeSteps K steps; at least
-// one, which zeroes the tickets.  False if that is more than a grid can hold (operands beyond 2^44 elements).
+// Grid of the decode pass for `blocks` 8-row blocks: a workgroup per block and group of kDecodeSteps K steps.  False
+// if that is more than a grid can hold (operands beyond 2^44 elements).
 static bool decode_grid(int64_t blocks, int64_t K, dim3* grid) {
   const int64_t n = blocks * ((K / TK + kDecodeSteps - 1) / kDecodeSteps);
   if (n > 0x7fffffff) return false;
-  *grid = dim3(static_cast<unsigned>(n > 0 ? n : 1));
+  *grid = dim3(static_cast<unsigned>(n));
   return true;
 }
 
@@ -560,27 +593,27 @@ hipError_t launch_predecode(const Operand& op, int64_t K, void* fp16_out, hipStr
   if (!decode_grid(op.outer / 8, K, &grid)) return hipErrorInvalidValue;
   hipLaunchKernelGGL(decode_f16_kernel, grid, dim3(256), 0, s, op.codes, op.scales,
                      static_cast<int>(op.outer / 8), static_cast<_Float16*>(fp16_out), op.codes, op.scales, 0,
-                     static_cast<_Float16*>(fp16_out), K, static_cast<unsigned int*>(nullptr));
+                     static_cast<_Float16*>(fp16_out), K);
   return hipGetLastError();
 }
 
 hipError_t launch_gemm_two_pass(const GemmArgs& g, hipStream_t s) {
   const int64_t M = g.a.outer, N = g.b.outer, K = g.K;
-  // Workspace: [A as FP16 unless decoded beforehand][B likewise][tickets][partial tiles]
+  // Workspace: [A as FP16 unless decoded beforehand][B likewise][partial tiles]
   char* ws = static_cast<char*>(g.workspace);
   const int64_t rows_a = g.a.fp16 ? 0 : M, rows_b = g.b.fp16 ? 0 : N;
   _Float16* a_ws = reinterpret_cast<_Float16*>(ws);
   _Float16* b_ws = a_ws + rows_a * K;
   const _Float16* a16 = g.a.fp16 ? static_cast<const _Float16*>(g.a.fp16) : a_ws;
   const _Float16* b16 = g.b.fp16 ? static_cast<const _Float16*>(g.b.fp16) : b_ws;
-  unsigned int* tickets = reinterpret_cast<unsigned int*>(ws + operand_bytes(rows_a, rows_b, K));
-  float* partials = reinterpret_cast<float*>(ws + operand_bytes(rows_a, rows_b, K) + kTicketBytes);
-  // One launch decodes what is still to decode and zeroes the tickets (with both operands decoded beforehand it is one
-  // workgroup that only does the latter).
-  dim3 grid;
-  if (!decode_grid((rows_a + rows_b) / 8, K, &grid)) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(decode_f16_kernel, grid, dim3(256), 0, s, g.a.codes, g.a.scales,
-                     static_cast<int>(rows_a / 8), a_ws, g.b.codes, g.b.scales, static_cast<int>(rows_b / 8), b_ws, K, tickets);
+  float* partials = reinterpret_cast<float*>(ws + operand_bytes(rows_a, rows_b, K));
+  // One launch decodes what is still to decode.
+  if (rows_a + rows_b > 0) {
+    dim3 grid;
+    if (!decode_grid((rows_a + rows_b) / 8, K, &grid)) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(decode_f16_kernel, grid, dim3(256), 0, s, g.a.codes, g.a.scales, static_cast<int>(rows_a / 8), a_ws,
+                       g.b.codes, g.b.scales, static_cast<int>(rows_b / 8), b_ws, K);
+  }
   const int tiles_m = static_cast<int>((M + TM - 1) / TM), tiles_n = static_cast<int>((N + TN - 1) / TN);
   const int tiles = tiles_m * tiles_n;
   // One 256x256 tile keeps one CU busy (its LDS fits one workgroup).  Whole rounds of kCUs tiles
@@ -588,9 +621,9 @@ hipError_t launch_gemm_two_pass(const GemmArgs& g, hipStream_t s) {
   const TailPlan p = plan_tail(M, N, K);
   const int full = tiles - p.tail;
   hipError_t e = hipSuccess;
-  if (full > 0) e = launch_f16(g.out_bf16, a16, b16, g, tiles_m, tiles_n, 0, full, 1, nullptr, nullptr, s);
+  if (full > 0) e = launch_f16(g.out_bf16, a16, b16, g, tiles_m, tiles_n, 0, full, 1, nullptr, s);
   if (e == hipSuccess && p.tail > 0)
-    e = launch_f16(g.out_bf16, a16, b16, g, tiles_m, tiles_n, full, p.tail, p.splits, partials, tickets, s);
+    e = launch_f16(g.out_bf16, a16, b16, g, tiles_m, tiles_n, full, p.tail, p.splits, partials, s);
   return e;
 }
 

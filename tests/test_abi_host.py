@@ -151,11 +151,11 @@ def test_gemm_and_dequantize_reject_bad_arguments(lib):
 
 
 def test_gemm_workspace_query(lib):
-    # FP16 copies of both operands + 256 split-K tickets (+ FP32 partial tiles when the last round of 256x256
-    # tiles is partial: 640 tiles -> 128 tiles x 2 splits, 1600 tiles -> 64 tiles x 4 splits)
-    assert nv.gemm_workspace_bytes(8192, 20480, 5120) == (8192 + 20480) * 5120 * 2 + 1024
-    assert nv.gemm_workspace_bytes(8192, 5120, 20480) == (8192 + 5120) * 20480 * 2 + 1024 + 256 * 256 * 256 * 4
-    assert nv.gemm_workspace_bytes(20480, 5120, 8192) == (20480 + 5120) * 8192 * 2 + 1024 + 256 * 256 * 256 * 4
+    # FP16 copies of both operands (+ FP32 partial tiles when the last round of 256x256 tiles is partial:
+    # 640 tiles -> 128 tiles x 2 splits, 1600 tiles -> 64 tiles x 4 splits)
+    assert nv.gemm_workspace_bytes(8192, 20480, 5120) == (8192 + 20480) * 5120 * 2
+    assert nv.gemm_workspace_bytes(8192, 5120, 20480) == (8192 + 5120) * 20480 * 2 + 256 * 256 * 256 * 4
+    assert nv.gemm_workspace_bytes(20480, 5120, 8192) == (20480 + 5120) * 8192 * 2 + 256 * 256 * 256 * 4
     w = ctypes.c_size_t()
     assert lib.nvfp4_gemm_workspace_bytes(8, 16, 16, ctypes.addressof(w)) == -2
     assert lib.nvfp4_gemm_workspace_bytes(16, 16, 16, None) == -1
@@ -253,9 +253,8 @@ def test_separate_passes_reject_bad_arguments(lib):
 def test_no_kernel_keeps_arrays_in_scratch_memory():
     """The build records what the compiler reports per kernel.  A patch or fragment array that ends up in scratch
     (private) memory, or register spills reloaded inside a loop, are silent 2-3x slowdowns (both happened here), so:
-    no dynamic stack, at most a few spilled values per kernel (the 512-register GEMM kernels park a few across their
-    loop or, the FP16 one, inside the sum over split-K partial tiles: never inside the K steps, where a reload would
-    also wait for every store of the tile before), none at all in the streaming kernels."""
+    no dynamic stack, at most a few spilled values per kernel, none at all in the streaming kernels and in the FP16
+    GEMM (whose K steps run behind the stores of the tile before: a reload there would wait for all of them)."""
     import json
     from paper_2509_25149_amd import build
     if not os.path.exists(build.RESOURCES):
@@ -264,14 +263,14 @@ def test_no_kernel_keeps_arrays_in_scratch_memory():
     assert len(res) >= 60
     for name, r in res.items():
         assert r["Dynamic Stack"] == "False", name
-        assert r["ScratchSize"] <= 64, (name, r["ScratchSize"])
+        assert r["ScratchSize"] <= 32, (name, r["ScratchSize"])
         if any(k in name for k in ("quantize_mx_kernel", "cast_kernel", "amax_kernel", "cast_wide", "amax_wide", "decode_f16",
-                                   "dequantize", "rowscale_")):
+                                   "dequantize", "rowscale_", "gemm_f16_kernel")):
             assert r["ScratchSize"] == 0 and r["VGPRs Spill"] == 0, (name, r)
+        if "splitk_sum" in name:
+            assert r["ScratchSize"] == 0, (name, r)   # (values parked in unused accumulation registers are no memory traffic)
         if "gemm_mx_kernel" in name:
             assert r["ScratchSize"] <= 16 and r["VGPRs Spill"] <= 3, (name, r)     # parked across the loop, not inside it
-        if "gemm_f16_kernel" in name:
-            assert r["ScratchSize"] <= 48 and r["VGPRs Spill"] <= 16, (name, r)
 
 
 def test_quantize_static_rejects_before_touching_the_gpu(lib):

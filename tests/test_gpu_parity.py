@@ -340,7 +340,7 @@ def test_linear_layer_calls_equal_the_call_sequence():
 def test_layer_step_replays_from_a_hip_graph():
     """A whole layer step (quantize + three GEMMs through the per-layer entry points, caller-owned buffers only) is
     captured into a HIP graph and replayed with eager work in between; every replay must reproduce the eager
-    result bit for bit.  Shapes with a split-K last round (tickets are zeroed by a kernel, not by a memset)."""
+    result bit for bit.  Shapes with a split-K last round."""
     tokens, d_in, d_out = 4352, 1024, 4096          # Fprop: 17 x 16 = 272 tiles -> the last 16 are split along K
     wb = synth.normal(d_in, d_out, 0.02, 951)
     xb = synth.normal_with_outliers(tokens, d_in, 1.0, 952)
@@ -461,14 +461,14 @@ def test_predecoded_operands_give_the_same_bits():
     row_major = by_chunk.permute(0, 2, 1, 3, 4).reshape(d_out, d_in)
     deq = nv.nvfp4_dequantize(qw, nv.COPY_COL)
     assert torch.allclose(row_major.float() * qw.col_ts[0], deq, rtol=1e-6, atol=0)
-    # less scratch is enough now: only X (or dY), the counters and the partial tiles
+    # less scratch is enough now: only X (or dY) and the partial tiles
     small = torch.empty(nv.gemm_workspace_bytes(tokens, d_out, d_in) - d_out * d_in * 2, dtype=torch.uint8, device="cuda")
     y1 = nv.nvfp4_gemm(qx, qw, nv.OP_FPROP, nv.OUT_F32, workspace=small)
     assert torch.equal(y1, y0)
     small2 = torch.empty(nv.gemm_workspace_bytes(tokens, d_in, d_out) - d_in * d_out * 2, dtype=torch.uint8, device="cuda")
     dx1 = nv.nvfp4_gemm(qdy, qw, nv.OP_DGRAD, nv.OUT_F32, workspace=small2)
     assert torch.equal(dx1, dx0)
-    # both operands decoded beforehand (Wgrad): only counters and partial tiles remain in the workspace
+    # both operands decoded beforehand (Wgrad): only partial tiles remain in the workspace, here none: no workspace at all
     dw0 = nv.nvfp4_gemm(qx, qdy, nv.OP_WGRAD, nv.OUT_F32, workspace=gemm_ws(d_in, d_out, tokens))
     nv.nvfp4_predecode(qx, nv.COPY_COL)
     nv.nvfp4_predecode(qdy, nv.COPY_COL)
