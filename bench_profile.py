@@ -55,9 +55,12 @@ def find_db(directory: str):
 
 def short_name(n: str) -> str:
     """A readable kernel name: template arguments kept, parameter list and namespaces of no interest dropped."""
-    m = re.search(r"gemm_f16_kernelILb(\d)E", n)
+    m = re.search(r"gemm_f16_kernelILb(\d)ELb(\d)ELb(\d)E", n)
+    if m:      # template arguments: bf16 output, per-row tensor scales, split-K partial tiles as output
+        return "nvfp4::gemm_f16_kernel<%s>" % ", ".join("true" if g == "1" else "false" for g in m.groups())
+    m = re.search(r"splitk_sum_kernelILb(\d)ELb(\d)E", n)
     if m:
-        return "nvfp4::gemm_f16_kernel<%s>" % ("true" if m.group(1) == "1" else "false")
+        return "nvfp4::splitk_sum_kernel<%s>" % ", ".join("true" if g == "1" else "false" for g in m.groups())
     if "decode_f16_kernel" in n:
         return "nvfp4::decode_f16_kernel"
     n = re.sub(r"\(.*", "", n.replace("void ", "").replace("(anonymous namespace)::", ""))
@@ -164,7 +167,8 @@ def main() -> int:
             fh.write("rocprofv3 kernel-trace summary: " + head)
             fh.write("Command:\n  " + COMMANDS["trace"] + "\n")
             fh.write("5 timed steps + 1 warm-up step + the side blocks are all in the counts.  One nvfp4_gemm call = decode_f16_kernel +\n"
-                     "gemm_f16_kernel (+ a second, split-K gemm_f16_kernel launch for the last partial round of tiles: Dgrad and Wgrad).\n"
+                     "gemm_f16_kernel<bf16 output, per-row scales, false> (+ for the last partial round of tiles, Dgrad and Wgrad:\n"
+                     "gemm_f16_kernel<false, false, true>, which stores split-K partial tiles, and splitk_sum_kernel, which adds them).\n"
                      "Durations in microseconds; pct = share of all GPU kernel time in the process (input generation included).\n\n")
             fh.write(f"{'calls':>6} {'total_us':>12} {'avg_us':>10} {'min_us':>10} {'max_us':>10} {'pct':>6}  kernel\n")
             for n, k, s, a, mi, ma, pct in rows:
@@ -193,7 +197,7 @@ def main() -> int:
             def total(kernels, table, scale):
                 return sum(sum(table.get(k, [])) for k in kernels) * 1024.0 * scale
 
-            gemm_k = [k for k in fv if "gemm_f16_kernel" in k or "decode_f16_kernel" in k]
+            gemm_k = [k for k in fv if "gemm_f16_kernel" in k or "decode_f16_kernel" in k or "splitk_sum_kernel" in k]
             quant_k = [k for k in fv if ("cast_kernel" in k or "amax_kernel" in k or "amax_finalize" in k)]
             steps = 3                                           # --steps 2 --warmup 1
             g_calls = 3 * steps
@@ -233,7 +237,7 @@ def main() -> int:
                     if kern in mops and mops[kern][1] > 0:
                         fh.write(f"; MOPS_F16 x 512 = {mops[kern][1] * 512:.4e} flop per dispatch (avg)")
                     fh.write("\n")
-                    if "gemm_f16_kernel<true>" in kern:
+                    if "gemm_f16_kernel<true, false, false>" in kern:
                         measured["gemm_f16_kernel_mfma_busy_frac"] = frac
                     if "gemm_mx_kernel_k512" in kern:
                         measured.setdefault("gemm_mx_kernel_mfma_busy_frac", frac)

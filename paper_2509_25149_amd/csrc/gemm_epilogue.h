@@ -45,48 +45,58 @@ __device__ __forceinline__ float4v scale4(const TensorScales& ts, float uniform,
   return s;
 }
 
-// kVec: an operand carries one scale per row; the lane's 8 rows (m = 16 i + l16) and 8 x 4 columns (n = 16 j + 4 lq + r)
-// then take their factors from the vectors, loaded once.  Otherwise the product a[0] * b[0] serves every output.
+// What a lane needs to know to store its part of a 128 x 128 block: kVec: an operand carries one scale per row; the
+// lane's 8 x 4 columns (n = 16 j + 4 lq + r) then take their factors from sb, loaded once, and its 8 rows
+// (m = 16 i + l16) one factor each.  Otherwise the product a[0] * b[0] serves every output.
 // A lane's addresses are one pointer (its row l16, its first column) plus i * 16 rows plus a constant per j, which the
-// stores carry as their immediate offsets.  (A variant without the predicates for blocks that exist whole measured no
-// faster.)  A kernel should contain this once: where a second use of the sums sits in another branch, the compiler
-// reads all 256 out of the accumulation registers ahead of the branch, into registers it does not have.
+// stores carry as their immediate offsets.
 template <bool kBf16Out, bool kVec>
-__device__ __forceinline__ void store_wave_block_impl(float4v (&acc)[8][8], const TensorScales ts, void* __restrict__ Dv, int64_t ldd,
-                                                      bool accumulate, int64_t row0, int64_t col0, int rows, int cols, int lane) {
-  const int l16 = lane & 15, lq = lane >> 4;
-  const float out_scale = ts.a[0] * ts.b[0];
-  float sa[kVec ? 8 : 1];
+struct WaveBlockStore {
+  void* d;
+  int64_t ldd, lane_first;
+  int l16, nl, rows, cols;
+  bool accumulate;
+  float out_scale;
   float4v sb[kVec ? 8 : 1];
-  if (kVec) {
+
+  __device__ __forceinline__ WaveBlockStore(const TensorScales ts, void* Dv, int64_t ldd_, bool accumulate_, int64_t row0, int64_t col0,
+                                            int rows_, int cols_, int lane)
+      : d(Dv), ldd(ldd_), l16(lane & 15), rows(rows_), cols(cols_), accumulate(accumulate_), out_scale(ts.a[0] * ts.b[0]) {
+    const int lq = lane >> 4;
+    // bf16: after the exchange a lane of an even column group holds 8 consecutive columns of block j, a lane of an odd
+    // group 8 of block j + 1: column 16 j + nl, nl = 0, 16, 8, 24 for lq = 0 .. 3.
+    nl = kBf16Out ? (lq & 1) * 16 + (lq >> 1) * 8 : lq * 4;
+    lane_first = (row0 + l16) * ldd + col0 + nl;
+    if (kVec) {
 #pragma unroll
-    for (int i = 0; i < 8; ++i) sa[kVec ? i : 0] = ts.a[ts.a_per_row && i * 16 + l16 < rows ? row0 + i * 16 + l16 : 0];
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      if (ts.b_per_row && j * 16 + lq * 4 < cols) {
-        sb[kVec ? j : 0] = *reinterpret_cast<const float4v*>(ts.b + col0 + j * 16 + lq * 4);
-      } else {
-        const float b0 = ts.b[0];
-        sb[kVec ? j : 0] = float4v{b0, b0, b0, b0};
+      for (int j = 0; j < 8; ++j) {
+        if (ts.b_per_row && j * 16 + lq * 4 < cols) {
+          sb[kVec ? j : 0] = *reinterpret_cast<const float4v*>(ts.b + col0 + j * 16 + lq * 4);
+        } else {
+          const float b0 = ts.b[0];
+          sb[kVec ? j : 0] = float4v{b0, b0, b0, b0};
+        }
       }
     }
   }
-  auto scale = [&](int i, int j) -> float4v {
-    if (kVec) return sb[kVec ? j : 0] * sa[kVec ? i : 0];
-    return float4v{out_scale, out_scale, out_scale, out_scale};
-  };
-  // bf16: after the exchange a lane of an even column group holds 8 consecutive columns of block j, a lane of an odd
-  // group 8 of block j + 1: column 16 j + nl, nl = 0, 16, 8, 24 for lq = 0 .. 3.
-  const int nl = kBf16Out ? (lq & 1) * 16 + (lq >> 1) * 8 : lq * 4;
-  const int64_t lane_first = (row0 + l16) * ldd + col0 + nl;
-#pragma unroll
-  for (int i = 0; i < 8; ++i) {
+
+  // the factor of the lane's row in 16-row block i (kVec only)
+  __device__ __forceinline__ float row_scale(const TensorScales ts, int64_t row0, int i) const {
+    return ts.a[ts.a_per_row && i * 16 + l16 < rows ? row0 + i * 16 + l16 : 0];
+  }
+
+  // The lane's 8 x 4 sums of 16-row block i: row m = 16 i + l16, columns 16 j + 4 lq + r.
+  __device__ __forceinline__ void store_rows(const float4v (&sums)[8], int i, float sa) const {
+    auto scale = [&](int j) -> float4v {
+      if (kVec) return sb[kVec ? j : 0] * sa;
+      return float4v{out_scale, out_scale, out_scale, out_scale};
+    };
     const bool row_in = i * 16 + l16 < rows;
     if (kBf16Out) {
-      uint16_t* d_row = static_cast<uint16_t*>(Dv) + lane_first + i * 16 * ldd;
+      uint16_t* d_row = static_cast<uint16_t*>(d) + lane_first + i * 16 * ldd;
 #pragma unroll
       for (int j = 0; j < 8; j += 2) {
-        const float4v va = acc[i][j] * scale(i, j), vb = acc[i][j + 1] * scale(i, j + 1);
+        const float4v va = sums[j] * scale(j), vb = sums[j + 1] * scale(j + 1);
         const uint32_t a0 = f32x2_to_bf16(va[0], va[1]), a1 = f32x2_to_bf16(va[2], va[3]);
         const uint32_t b0 = f32x2_to_bf16(vb[0], vb[1]), b1 = f32x2_to_bf16(vb[2], vb[3]);
         // first result: lanes of odd groups now hold the second block's dword of the group below; second result: lanes of
@@ -98,18 +108,34 @@ __device__ __forceinline__ void store_wave_block_impl(float4v (&acc)[8][8], cons
         if (row_in && j * 16 + nl < cols) *reinterpret_cast<u32x4v*>(d_row + j * 16) = o;
       }
     } else {
-      float* d_row = static_cast<float*>(Dv) + lane_first + i * 16 * ldd;
+      float* d_row = static_cast<float*>(d) + lane_first + i * 16 * ldd;
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
         if (row_in && j * 16 + nl < cols) {  // columns come in multiples of 16, so the 4 columns are in or out together
-          float4v v = acc[i][j] * scale(i, j);
-          float* d = d_row + j * 16;
-          if (accumulate) v += *reinterpret_cast<const float4v*>(d);
-          *reinterpret_cast<float4v*>(d) = v;
+          float4v v = sums[j] * scale(j);
+          float* p = d_row + j * 16;
+          if (accumulate) v += *reinterpret_cast<const float4v*>(p);
+          *reinterpret_cast<float4v*>(p) = v;
         }
       }
     }
   }
+};
+
+// A wavefront's whole 128 x 128 block.  (A variant without the predicates for blocks that exist whole measured no
+// faster.)  A kernel should contain this once: where a second use of the sums sits in another branch, the compiler
+// reads all 256 out of the accumulation registers ahead of the branch, into registers it does not have.
+template <bool kBf16Out, bool kVec>
+__device__ __forceinline__ void store_wave_block_impl(float4v (&acc)[8][8], const TensorScales ts, void* __restrict__ Dv, int64_t ldd,
+                                                      bool accumulate, int64_t row0, int64_t col0, int rows, int cols, int lane) {
+  const WaveBlockStore<kBf16Out, kVec> out(ts, Dv, ldd, accumulate, row0, col0, rows, cols, lane);
+  float sa[kVec ? 8 : 1] = {};
+  if (kVec) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) sa[kVec ? i : 0] = out.row_scale(ts, row0, i);
+  }
+#pragma unroll
+  for (int i = 0; i < 8; ++i) out.store_rows(acc[i], i, sa[kVec ? i : 0]);
 }
 
 // The per-tensor form, for kernels that have no other.

@@ -450,42 +450,42 @@ __global__ __launch_bounds__(kThreads) void gemm_f16_kernel(const _Float16* __re
   }
 }
 
-// The sums over K of the tiles a split-K launch covered: one wavefront per tile and 128 x 128 block of it (the block
-// one wavefront of gemm_f16_kernel holds, in the same register layout, which is the order the partial tiles are
-// stored in), acc = ((p0 + p1) + p2) + ... in split order, then the same output stage.
+// The sums over K of the tiles a split-K launch covered: one wavefront per tile, 128 x 128 block of it (the block one
+// wavefront of gemm_f16_kernel holds, in the same register layout, which is the order the partial tiles are stored
+// in) and 16 rows of that, sum = ((p0 + p1) + p2) + ... in split order, then the same output stage.  Many small
+// workgroups: the partial tiles were written by other XCDs and every load of them is a long trip, so what counts is
+// how many are in flight over the chip (with a wavefront per 128 x 128 block the sum of 64 tiles x 4 splits took 57 us).
 template <bool kBf16Out, bool kRowScales>
 __global__ __launch_bounds__(64) void splitk_sum_kernel(const float* __restrict__ partials, int k_splits, int64_t M, int64_t N,
                                                         const float* __restrict__ a_ts, const float* __restrict__ b_ts,
                                                         void* __restrict__ Dv, int64_t ldd, bool accumulate, int tiles_m,
                                                         int tiles_n, int tile_begin, bool a_ts_per_row, bool b_ts_per_row) {
-  const int tile_local = static_cast<int>(blockIdx.x) >> 2, wave = static_cast<int>(blockIdx.x) & 3;
+  const int tile_local = static_cast<int>(blockIdx.x) >> 5, wave = (static_cast<int>(blockIdx.x) >> 3) & 3;
+  const int i = static_cast<int>(blockIdx.x) & 7;
   const int lane = static_cast<int>(threadIdx.x), wm = wave >> 1, wn = wave & 1;
   int tm, tn;
   tile_coordinates(tile_begin + tile_local, tiles_m, tiles_n, tm, tn);
+  // float4 number (i * 8 + j) * 256 + 64 wave + lane of a partial tile
   const float4v* all = reinterpret_cast<const float4v*>(partials) +
-                       static_cast<int64_t>(tile_local) * k_splits * (TM * TN / 4) + wave * 64 + lane;
-  float4v acc[8][8];
-  for (int sp = 0; sp < k_splits; ++sp) {
+                       static_cast<int64_t>(tile_local) * k_splits * (TM * TN / 4) + i * 8 * kThreads + wave * 64 + lane;
+  float4v sums[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) sums[j] = all[j * kThreads];
+  for (int sp = 1; sp < k_splits; ++sp) {
     const float4v* part = all + static_cast<int64_t>(sp) * (TM * TN / 4);
+    float4v t[8];
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {   // 32 loads in flight
-      float4v t[4][8];
+    for (int j = 0; j < 8; ++j) t[j] = part[j * kThreads];
 #pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 8; ++j) t[i][j] = part[((h * 4 + i) * 8 + j) * kThreads];
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 8; ++j) acc[h * 4 + i][j] = sp == 0 ? t[i][j] : acc[h * 4 + i][j] + t[i][j];
-    }
+    for (int j = 0; j < 8; ++j) sums[j] = sums[j] + t[j];
   }
-  const TensorScales out_scale{a_ts, b_ts, a_ts_per_row, b_ts_per_row};
+  const TensorScales ts{a_ts, b_ts, a_ts_per_row, b_ts_per_row};
   const int64_t m0 = static_cast<int64_t>(tm) * TM, n0 = static_cast<int64_t>(tn) * TN;
   const int Mt = static_cast<int>(M - m0 < TM ? M - m0 : TM);
   const int Nt = static_cast<int>(N - n0 < TN ? N - n0 : TN);
-  store_wave_block_impl<kBf16Out, kRowScales>(acc, out_scale, Dv, ldd, accumulate, m0 + wm * 128, n0 + wn * 128,
-                                              Mt - wm * 128, Nt - wn * 128, lane);
+  const WaveBlockStore<kBf16Out, kRowScales> out(ts, Dv, ldd, accumulate, m0 + wm * 128, n0 + wn * 128, Mt - wm * 128,
+                                                 Nt - wn * 128, lane);
+  out.store_rows(sums, i, kRowScales ? out.row_scale(ts, m0 + wm * 128, i) : 0.0f);
 }
 
 }  // namespace
@@ -559,7 +559,7 @@ static hipError_t launch_f16(bool bf16_out, const _Float16* a16, const _Float16*
   const bool row_scales = g.a.ts_per_row != 0 || g.b.ts_per_row != 0;
   if (k_splits > 1) {
     NVFP4_LAUNCH_F16(false, false, true);
-    const dim3 grid(static_cast<unsigned>(tile_count) * 4);
+    const dim3 grid(static_cast<unsigned>(tile_count) * 32);   // tile, 128 x 128 block, 16 rows
 #define NVFP4_LAUNCH_SUM(BF16, ROWSCALES)                                                                              \
   hipLaunchKernelGGL((splitk_sum_kernel<BF16, ROWSCALES>), grid, dim3(64), 0, s, partials, k_splits, g.a.outer, g.b.outer, \
                      g.a.ts, g.b.ts, g.d, g.ldd, g.accumulate, tiles_m, tiles_n, tile_begin, g.a.ts_per_row != 0,      \
