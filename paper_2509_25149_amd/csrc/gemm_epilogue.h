@@ -1,4 +1,5 @@
-// Output stage shared by the 4-wavefront GEMM kernels for gfx950: one wavefront's 128 x 128 block of FP32 sums,
+// What the 4-wavefront GEMM kernels for gfx950 share besides their loops: the walk over the 256 x 256 tiles, and the
+// output stage: one wavefront's 128 x 128 block of FP32 sums,
 // held as 8 x 8 results of 16x16 MFMAs (acc[i][j][r] = D[m = 16 i + (lane & 15)][n = 16 j + 4 (lane >> 4) + r]),
 // times the tensor-level decode scales (App. B.3, after Eq. 5), to FP32 (optionally added into D) or bf16.
 // Device code only.
@@ -24,6 +25,26 @@ namespace nvfp4 {
 // the output stage is what a wavefront has to issue, not memory bandwidth.  Must be called by all 64 lanes.  (Reordering the bf16 block through LDS into 256-byte row pieces was tried
 // with ordinary stores and measured no faster.)
 typedef uint32_t u32x4v __attribute__((ext_vector_type(4)));
+
+// The lane's number within its wavefront, asked of the hardware at the place of the call: the compiler can neither
+// move the question nor keep an earlier answer in a register.
+__device__ __forceinline__ int lane_id() {
+  int lane;
+  asm volatile("v_mbcnt_lo_u32_b32 %0, -1, 0\n\tv_mbcnt_hi_u32_b32 %0, -1, %0" : "=v"(lane));
+  return lane;
+}
+
+// Tile number pid of the 256x256 tiling -> tile row and column: the tiles are walked in bands of 8 tile rows, column by
+// column within a band.
+__device__ __forceinline__ void tile_coordinates(int pid, int tiles_m, int tiles_n, int& tm, int& tn) {
+  constexpr int kBand = 8;
+  const int band = pid / (kBand * tiles_n);
+  const int band_rows = min(kBand, tiles_m - band * kBand);
+  const int in_band = pid - band * kBand * tiles_n;
+  tm = band * kBand + in_band % band_rows;
+  tn = in_band / band_rows;
+}
+
 
 // The two operands' tensor-level decode scales.  Per tensor: a[0] * b[0] for every output.  With a scale per row of an
 // operand (App. B.1, last sentence) output (m, n) takes a[m] * b[n]: still constant along k, so still outside the sum.

@@ -200,25 +200,6 @@ __device__ __forceinline__ void load_1k_to_lds_next(uint32_t lane_offset, const 
   asm volatile("global_load_lds_dwordx4 %0, %1 offset:%2" ::"v"(lane_offset), "s"(base_minus_off), "n"(kOff) : "memory");
 }
 
-// The lane's number within its wavefront, asked of the hardware at the place of the call: the compiler can neither
-// move the question nor keep an earlier answer in a register.
-__device__ __forceinline__ int lane_id() {
-  int lane;
-  asm volatile("v_mbcnt_lo_u32_b32 %0, -1, 0\n\tv_mbcnt_hi_u32_b32 %0, -1, %0" : "=v"(lane));
-  return lane;
-}
-
-// Tile number pid of the 256x256 tiling -> tile row and column: the tiles are walked in bands of 8 tile rows, column by
-// column within a band.
-__device__ __forceinline__ void tile_coordinates(int pid, int tiles_m, int tiles_n, int& tm, int& tn) {
-  constexpr int kBand = 8;
-  const int band = pid / (kBand * tiles_n);
-  const int band_rows = min(kBand, tiles_m - band * kBand);
-  const int in_band = pid - band * kBand * tiles_n;
-  tm = band * kBand + in_band % band_rows;
-  tn = in_band / band_rows;
-}
-
 // The first MFMA of an accumulator in a work item: C = 0, so the 256 accumulation registers are never cleared.
 __device__ __forceinline__ void mfma_first(float4v& acc, const half8v& b, const half8v& a) {
   asm volatile("v_mfma_f32_16x16x32_f16 %0, %1, %2, 0" : "=a"(acc) : "v"(b), "v"(a));

@@ -291,123 +291,216 @@ __device__ __forceinline__ void read_frag_wide(Frags& f, RawScales& r, uint32_t 
   else lds_read_2x4_st64<(q - 20) * 2, (q - 20) * 2 + 1>(r.b[q - 20], b_scales);
 }
 
+// The first instruction on an accumulator in a tile: C = 0, so the 256 accumulation registers are never cleared.
+template <int kSelB, int kSelA>
+__device__ __forceinline__ void mfma_first(float4v& acc, const int4v& b, const int4v& a, int sb, int sa) {
+  asm volatile("v_mfma_scale_f32_16x16x128_f8f6f4 %0, %1, %2, 0, %3, %4 op_sel:[%5,%6,0] op_sel_hi:[%7,%8,0] cbsz:4 blgp:4"
+               : "=a"(acc)
+               : "v"(b), "v"(a), "v"(sb), "v"(sa), "n"(kSelB & 1), "n"(kSelA & 1), "n"(kSelB >> 1), "n"(kSelA >> 1));
+}
+
+// A wavefront's output stage issues 32 (bf16) or 64 (FP32) stores for a full tile; three quarters of them may still be
+// outstanding when the loads issued before it are needed (memory operations complete in issue order).
+template <bool kBf16Out>
+constexpr int kTileStoresMx = kBf16Out ? 24 : 48;
+
+// With more tiles than CUs the host launches one workgroup per CU, which takes tiles blockIdx.x, blockIdx.x +
+// gridDim.x, ... and runs them as ONE stream of stages, as the FP16 kernel of the NVFP4 route does: the loads issued
+// during a tile's last two stages fetch the next tile's first two (and its first scale chunk), so the pipeline
+// neither drains nor refills at a tile boundary.  K is a multiple of 512, so every tile is an even number of stages
+// and a whole number of scale chunks: the stage buffers and the scale ring simply keep turning (`gst` below counts
+// stages over all tiles).  The output stage's stores are not waited for.
 template <bool kBf16Out>
 __global__ __launch_bounds__(kThreads) void gemm_mx_kernel_k512(Operand A, Operand B, int64_t K, void* __restrict__ Dv,
                                                                 int64_t ldd, bool accumulate, int tiles_m, int tiles_n) {
   extern __shared__ __attribute__((aligned(16))) char lds[];
 
   const int num_tiles = tiles_m * tiles_n;
-  int pid = blockIdx.x;
-  if ((num_tiles & 7) == 0) pid = (pid & 7) * (num_tiles >> 3) + (pid >> 3);
-  constexpr int kBand = 8;
-  const int band = pid / (kBand * tiles_n);
-  const int band_rows = min(kBand, tiles_m - band * kBand);
-  const int in_band = pid - band * kBand * tiles_n;
-  const int tm = band * kBand + in_band % band_rows, tn = in_band / band_rows;
-  const int64_t m0 = static_cast<int64_t>(tm) * TM, n0 = static_cast<int64_t>(tn) * TN;
-
-  const int tid = threadIdx.x, lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wm = wave >> 1, wn = wave & 1, l16 = lane & 15, kb = lane >> 4;
-  const int arow = wm * 128 + l16, brow = wn * 128 + l16;
+  const int wave = __builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x) >> 6);
   const int64_t code_ld = K / 2, scale_ld = K / 32;
+  // Work item -> tile: consecutive workgroup ids go to different XCDs (round robin over 8, one L2 each); every XCD
+  // gets a contiguous range of tiles, walked in bands of 8 tile rows.
+  auto locate = [&](int item, int& tm, int& tn) {
+    if ((num_tiles & 7) == 0) item = (item & 7) * (num_tiles >> 3) + (item >> 3);
+    tile_coordinates(item, tiles_m, tiles_n, tm, tn);
+  };
 
-  // Code loads: instruction q (0..7) of wavefront w fills tile rows w * 64 + 8 q .. + 7 (lane -> row lane / 8,
-  // position lane % 8, i.e. chunk (lane % 8) ^ ((row >> 1) & 7); 8 q leaves that term alone for even q and flips
-  // its bit 2 for odd q).  Wave-uniform 64-bit base per 8-row block + one per-lane 32-bit offset for even and one
-  // for odd q (K < 2^24, checked on the host).  A block past the end of an operand is replaced by the operand's
-  // last block (rows come in multiples of 32); it only feeds outputs that are never stored.
-  const int r0 = wave * 64 + (lane >> 3);
-  const uint32_t c0 = static_cast<uint32_t>((lane & 7) ^ ((r0 >> 1) & 7)) * 16u;
-  const uint32_t off_even = static_cast<uint32_t>(lane >> 3) * static_cast<uint32_t>(code_ld) + c0;
-  const uint32_t off_odd = static_cast<uint32_t>(lane >> 3) * static_cast<uint32_t>(code_ld) + (c0 ^ 64u);
-  const uint8_t* blk_a[8];
-  const uint8_t* blk_b[8];
-#pragma unroll
-  for (int q = 0; q < 8; ++q) {
-    const int64_t r = wave * 64 + q * 8;
-    blk_a[q] = A.codes + (m0 + min<int64_t>(r, A.outer - 8 - m0)) * code_ld;
-    blk_b[q] = B.codes + (n0 + min<int64_t>(r, B.outer - 8 - n0)) * code_ld;
-  }
-  // Scale loads: one instruction = 64 tile rows x 16 bytes (four K steps), rows clamped per lane.
-  const uint32_t off_sa = static_cast<uint32_t>(min<int64_t>(wave * 64 + lane, A.outer - 1 - m0)) * static_cast<uint32_t>(scale_ld);
-  const uint32_t off_sb = static_cast<uint32_t>(min<int64_t>(wave * 64 + lane, B.outer - 1 - n0)) * static_cast<uint32_t>(scale_ld);
-  const uint8_t* tile_sa = A.scales + m0 * scale_ld;
-  const uint8_t* tile_sb = B.scales + n0 * scale_ld;
   const uint32_t lds0 = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(lds));
   const uint32_t scales0 = lds0 + 2 * kWideStageBytes;
-  // load number q (0..15) of stage `st` (K steps 2 st, 2 st + 1) into stage buffer `buf`: 0..7 A, 8..15 B
-  auto issue_codes = [&](int q, int st, int buf) {
+  // What depends on the lane is worked out once per tile, from a lane number asked for on the spot (values kept from
+  // before the first tile would have to live through every output stage and end up in scratch memory).
+  // Code loads: instruction q (0..7) of wavefront w fills tile rows w * 64 + 8 q .. + 7 (lane -> row lane / 8,
+  // position lane % 8, i.e. chunk (lane % 8) ^ ((row >> 1) & 7); 8 q leaves that term alone for even q and flips
+  // its bit 2 for odd q).  Scale loads: one instruction = 64 tile rows x 16 bytes (four K steps).
+  uint32_t lane_even = 0, lane_odd = 0, lane_srow = 0;
+  uint32_t a_lo = 0, a_hi = 0, b_lo = 0, b_hi = 0, a_scales = 0, b_scales = 0;   // fragment addresses: stage buffer 0 / scale slot 0, step 0
+  int sel01 = 0;
+  auto lane_setup = [&]() {
+    const int lane = lane_id();
+    const int r0 = wave * 64 + (lane >> 3);
+    const uint32_t c0 = static_cast<uint32_t>((lane & 7) ^ ((r0 >> 1) & 7)) * 16u;
+    lane_even = static_cast<uint32_t>(lane >> 3) * static_cast<uint32_t>(code_ld) + c0;
+    lane_odd = static_cast<uint32_t>(lane >> 3) * static_cast<uint32_t>(code_ld) + (c0 ^ 64u);
+    lane_srow = static_cast<uint32_t>(wave * 64 + lane);
+    const int l16 = lane & 15, kb = lane >> 4;
+    const int arow = (wave >> 1) * 128 + l16, brow = (wave & 1) * 128 + l16;
+    a_lo = lds0 + swz128(arow, kb);
+    a_hi = lds0 + swz128(arow, 4 + kb);
+    b_lo = lds0 + kWideOperandBytes + swz128(brow, kb);
+    b_hi = lds0 + kWideOperandBytes + swz128(brow, 4 + kb);
+    a_scales = scales0 + arow * 16;
+    b_scales = scales0 + kWideScaleOperandBytes + brow * 16;
+    sel01 = kb | ((4 + kb) << 8);
+  };
+  lane_setup();
+  // Load addresses: a wave-uniform 64-bit base per operand tile (codes, scales) plus per-lane 32-bit offsets, which
+  // hold the row, the chunk and the stage / scale chunk being fetched (256 rows of K / 2 bytes: K < 2^24, checked on
+  // the host).  An 8-row block past the end of an operand is replaced by the operand's last block (rows come in
+  // multiples of 32); it only feeds outputs that are never stored.  Scale rows are clamped per lane.
+  const uint8_t* base_a = nullptr;
+  const uint8_t* base_b = nullptr;
+  const uint8_t* base_sa = nullptr;
+  const uint8_t* base_sb = nullptr;
+  uint32_t voff[16];   // q 0..7 A, 8..15 B
+  uint32_t vsa = 0, vsb = 0;
+  // Point the loads at stage `stage` and scale chunk `chunk` of tile (tm, tn).
+  auto aim = [&](int tm, int tn, int stage, int chunk) {
+    const int64_t m_first = static_cast<int64_t>(tm) * TM, n_first = static_cast<int64_t>(tn) * TN;
+    base_a = A.codes + m_first * code_ld;
+    base_b = B.codes + n_first * code_ld;
+    base_sa = A.scales + m_first * scale_ld;
+    base_sb = B.scales + n_first * scale_ld;
+    const uint32_t last_a = static_cast<uint32_t>(A.outer - 8 - m_first), last_b = static_cast<uint32_t>(B.outer - 8 - n_first);
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      const uint32_t r = static_cast<uint32_t>(wave * 64 + q * 8);
+      const uint32_t fixed = static_cast<uint32_t>(stage) * kWideRowBytes;
+      voff[q] = ((q & 1) ? lane_odd : lane_even) + min(r, last_a) * static_cast<uint32_t>(code_ld) + fixed;
+      voff[8 + q] = ((q & 1) ? lane_odd : lane_even) + min(r, last_b) * static_cast<uint32_t>(code_ld) + fixed;
+    }
+    vsa = min(lane_srow, last_a + 7) * static_cast<uint32_t>(scale_ld) + static_cast<uint32_t>(chunk) * 16u;
+    vsb = min(lane_srow, last_b + 7) * static_cast<uint32_t>(scale_ld) + static_cast<uint32_t>(chunk) * 16u;
+  };
+  // load number q (0..15) of a stage into stage buffer `buf`: 0..7 A, 8..15 B
+  auto issue_codes = [&](auto qc, int buf) {
+    constexpr int q = decltype(qc)::value;
     const uint32_t dst = lds0 + buf * kWideStageBytes + (q < 8 ? 0 : kWideOperandBytes) + wave * 8192 + (q & 7) * 1024;
-    load16_to_lds((q & 1) ? off_odd : off_even, (q < 8 ? blk_a[q & 7] : blk_b[q & 7]) + static_cast<int64_t>(st) * kWideRowBytes, dst);
+    load16_to_lds(voff[q], q < 8 ? base_a : base_b, dst);
   };
-  // the two loads of scale chunk `ch` (K steps 4 ch .. 4 ch + 3) into ring slot `slot`
-  auto issue_scales = [&](int ch, int slot) {
+  // the two loads of a scale chunk (four K steps) into ring slot `slot`
+  auto issue_scales = [&](int slot) {
     const uint32_t dst = scales0 + slot * kWideScaleSlotBytes + wave * 1024;
-    load16_to_lds(off_sa, tile_sa + static_cast<int64_t>(ch) * 16, dst);
-    load16_to_lds(off_sb, tile_sb + static_cast<int64_t>(ch) * 16, dst + kWideScaleOperandBytes);
+    load16_to_lds(vsa, base_sa, dst);
+    load16_to_lds(vsb, base_sb, dst + kWideScaleOperandBytes);
   };
-  // fragment addresses in stage buffer 0 / scale slot 0, step 0
-  const uint32_t a_lo = lds0 + swz128(arow, kb), a_hi = lds0 + swz128(arow, 4 + kb);
-  const uint32_t b_lo = lds0 + kWideOperandBytes + swz128(brow, kb), b_hi = lds0 + kWideOperandBytes + swz128(brow, 4 + kb);
-  const uint32_t a_scales = scales0 + arow * 16, b_scales = scales0 + kWideScaleOperandBytes + brow * 16;
-  const int sel01 = kb | ((4 + kb) << 8);
-
-  float4v acc[8][8];
-#pragma unroll
-  for (int i = 0; i < 8; ++i)
-#pragma unroll
-    for (int j = 0; j < 8; ++j)
-#pragma unroll
-      for (int r = 0; r < 4; ++r) acc[i][j][r] = 0.0f;
 
   const int stages = static_cast<int>(K / 256), chunks = static_cast<int>(K / 512);   // stages = 2 chunks >= 2
-  static_for<0, 16>([&](auto q) { issue_codes(decltype(q)::value, 0, 0); });
-  static_for<0, 16>([&](auto q) { issue_codes(decltype(q)::value, 1, 1); });
-  issue_scales(0, 0);
+  int item = blockIdx.x;   // < num_tiles: the host launches at most that many workgroups
+  int tm = 0, tn = 0;
+  locate(item, tm, tn);
+  aim(tm, tn, 0, 0);
+  static_for<0, 16>([&](auto q) { issue_codes(q, 0); });
+#pragma unroll
+  for (int q = 0; q < 16; ++q) voff[q] += kWideRowBytes;
+  static_for<0, 16>([&](auto q) { issue_codes(q, 1); });
+  issue_scales(0);
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __builtin_amdgcn_s_barrier();
+
   Frags f0, f1;
   RawScales raw;
-  static_for<0, kFragReads>([&](auto q) { read_frag_wide<decltype(q)::value>(f0, raw, a_lo, b_lo, a_scales, b_scales); });
-  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-  pack_scales(f0, raw, sel01);
+  float4v acc[8][8];
+  uint32_t gst = 0;             // stages done so far, over all tiles (even at every tile's start)
+  bool stores_behind = false;   // the previous tile's stores were issued after the loads now in flight
+  for (;;) {
+    // The tile's first fragments.  (After a tile of the same stream its last stage has read them already; they are
+    // read again so that the output stage had their registers to work with.)
+    {
+      const uint32_t cur = (gst & 1) * kWideStageBytes, sc = ((gst >> 1) & 1) * kWideScaleSlotBytes;
+      static_for<0, kFragReads>([&](auto q) { read_frag_wide<decltype(q)::value>(f0, raw, a_lo + cur, b_lo + cur, a_scales + sc, b_scales + sc); });
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+      pack_scales(f0, raw, sel01);
+    }
+    const int next_item = item + static_cast<int>(gridDim.x);
+    const bool has_next = next_item < num_tiles;
+    int next_tm = 0, next_tn = 0;
+    if (has_next) locate(next_item, next_tm, next_tn);
 
-  for (int st = 0; st < stages; ++st) {
-    const uint32_t cur = (st & 1) * kWideStageBytes, nxt = cur ^ kWideStageBytes;
-    // scale addresses: this stage's second step; the next stage's first step (ring slot of its chunk)
-    const uint32_t sc1 = ((st >> 1) & 1) * kWideScaleSlotBytes + (st & 1) * 8 + 4;
-    const uint32_t sc2 = (((st + 1) >> 1) & 1) * kWideScaleSlotBytes + ((st + 1) & 1) * 8;
-    const int st2 = min(st + 2, stages - 1);   // past the end: the last stage again, into a buffer nobody reads any more
-    static_for<0, 64>([&](auto ic) {
-      constexpr int n = decltype(ic)::value;
-      mfma<(n & 3), ((n >> 3) & 3)>(acc[n >> 3][n & 7], f0.b[n & 7], f0.a[n >> 3], f0.pb[(n & 7) >> 2], f0.pa[n >> 5]);
-      if constexpr ((n & 1) == 1 && (n >> 1) < kFragReads)
-        read_frag_wide<(n >> 1)>(f1, raw, a_hi + cur, b_hi + cur, a_scales + sc1, b_scales + sc1);
-    });
-    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
-    __builtin_amdgcn_s_barrier();
-    pack_scales(f1, raw, sel01);
-    static_for<0, 64>([&](auto ic) {
-      constexpr int n = decltype(ic)::value;
-      mfma<(n & 3), ((n >> 3) & 3)>(acc[n >> 3][n & 7], f1.b[n & 7], f1.a[n >> 3], f1.pb[(n & 7) >> 2], f1.pa[n >> 5]);
-      if constexpr ((n & 1) == 0 && (n >> 1) < kFragReads)
-        read_frag_wide<(n >> 1)>(f0, raw, a_lo + nxt, b_lo + nxt, a_scales + sc2, b_scales + sc2);
-      if constexpr ((n & 3) == 3) issue_codes(n >> 2, st2, st & 1);
-    });
-    // even stages also fetch the scales of the chunk after the next stage's, into the slot its predecessor left
-    // at this stage's barrier
-    if ((st & 1) == 0) issue_scales(min((st >> 1) + 1, chunks - 1), ((st >> 1) + 1) & 1);
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    pack_scales(f0, raw, sel01);
+    // One stage = two K steps; kFirst: the tile's first.  The loads run two stages ahead of the MFMAs, the scale
+    // loads (every other stage) one chunk ahead of the stage that reads it.
+    auto stage_step = [&](auto first_tag, int st) {
+      constexpr bool kFirst = decltype(first_tag)::value;
+      const uint32_t cur = (gst & 1) * kWideStageBytes, nxt = cur ^ kWideStageBytes;
+      // scale addresses: this stage's second step; the next stage's first step (ring slot of its chunk)
+      const uint32_t sc1 = ((gst >> 1) & 1) * kWideScaleSlotBytes + (gst & 1) * 8 + 4;
+      const uint32_t sc2 = (((gst + 1) >> 1) & 1) * kWideScaleSlotBytes + ((gst + 1) & 1) * 8;
+      // Where the loads go next: on within the tile, or to the next tile's first stage and chunk, or, with nothing
+      // to follow, nowhere (the last stage and chunk are fetched again into buffers nobody reads any more).
+      uint32_t code_advance = kWideRowBytes;
+      if ((st & 1) == 0 && (st >> 1) + 1 < chunks) {
+        vsa += 16u;
+        vsb += 16u;
+      }
+      if (st + 2 == stages) {
+        code_advance = 0;
+        if (has_next) aim(next_tm, next_tn, 0, 0);
+      } else if (st + 2 > stages && !has_next) {
+        code_advance = 0;
+      }
+      static_for<0, 64>([&](auto ic) {
+        constexpr int n = decltype(ic)::value;
+        if constexpr (kFirst)
+          mfma_first<(n & 3), ((n >> 3) & 3)>(acc[n >> 3][n & 7], f0.b[n & 7], f0.a[n >> 3], f0.pb[(n & 7) >> 2], f0.pa[n >> 5]);
+        else
+          mfma<(n & 3), ((n >> 3) & 3)>(acc[n >> 3][n & 7], f0.b[n & 7], f0.a[n >> 3], f0.pb[(n & 7) >> 2], f0.pa[n >> 5]);
+        if constexpr ((n & 1) == 1 && (n >> 1) < kFragReads)
+          read_frag_wide<(n >> 1)>(f1, raw, a_hi + cur, b_hi + cur, a_scales + sc1, b_scales + sc1);
+        if constexpr ((n & 3) == 2) voff[n >> 2] += code_advance;
+      });
+      if (kFirst && stores_behind) asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(kTileStoresMx<kBf16Out>) : "memory");
+      else asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+      __builtin_amdgcn_s_barrier();
+      pack_scales(f1, raw, sel01);
+      static_for<0, 64>([&](auto ic) {
+        constexpr int n = decltype(ic)::value;
+        mfma<(n & 3), ((n >> 3) & 3)>(acc[n >> 3][n & 7], f1.b[n & 7], f1.a[n >> 3], f1.pb[(n & 7) >> 2], f1.pa[n >> 5]);
+        if constexpr ((n & 1) == 0 && (n >> 1) < kFragReads)
+          read_frag_wide<(n >> 1)>(f0, raw, a_lo + nxt, b_lo + nxt, a_scales + sc2, b_scales + sc2);
+        if constexpr ((n & 3) == 3) issue_codes(std::integral_constant<int, (n >> 2)>{}, static_cast<int>(gst & 1));
+      });
+      // even stages also fetch the scales of the chunk after the next stage's, into the slot its predecessor left
+      // at this stage's barrier
+      if ((gst & 1) == 0) issue_scales(static_cast<int>(((gst >> 1) + 1) & 1));
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+      pack_scales(f0, raw, sel01);
+      ++gst;
+    };
+    stage_step(std::true_type{}, 0);
+    for (int st = 1; st < stages; ++st) stage_step(std::false_type{}, st);
+
+    // Everything below is computed here, per tile (see lane_setup).
+    int wm = wave >> 1, wn = wave & 1;
+    asm volatile("" : "+s"(wm), "+s"(wn));
+    const int lane = lane_id();
+    const TensorScales out_scale{A.ts, B.ts, false, false};    // both are 1 for MXFP4 (no tensor-level scale)
+    const int64_t m0 = static_cast<int64_t>(tm) * TM, n0 = static_cast<int64_t>(tn) * TN;
+    const int Mt = static_cast<int>(A.outer - m0 < TM ? A.outer - m0 : TM);
+    const int Nt = static_cast<int>(B.outer - n0 < TN ? B.outer - n0 : TN);
+    // The MFMA results must have left the pipe before ordinary instructions read the accumulators (the compiler
+    // cannot see into the assembly statements to insert these wait states itself).  With nothing to follow, the
+    // trailing global->LDS loads must have landed before the wavefront ends.
+    if (has_next) asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(0)\n\ts_nop 15\n\ts_nop 15" ::: "memory");
+    store_wave_block<kBf16Out>(acc, out_scale, Dv, ldd, accumulate, m0 + wm * 128, n0 + wn * 128, Mt - wm * 128, Nt - wn * 128,
+                               lane);
+    if (!has_next) break;
+    stores_behind = Mt == TM && Nt == TN;   // every lane stored every block: the count is known
+    item = next_item;
+    tm = next_tm;
+    tn = next_tn;
+    lane_setup();
+    aim(tm, tn, 1, 0);   // where the loads stand: the tile's second stage and first scale chunk are the last fetched
   }
-  asm volatile("s_waitcnt vmcnt(0)\n\ts_nop 15\n\ts_nop 15" ::: "memory");
-
-  const TensorScales out_scale{A.ts, B.ts, false, false};    // both are 1 for MXFP4 (no tensor-level scale)
-  const int Mt = static_cast<int>(A.outer - m0 < TM ? A.outer - m0 : TM);
-  const int Nt = static_cast<int>(B.outer - n0 < TN ? B.outer - n0 : TN);
-  store_wave_block<kBf16Out>(acc, out_scale, Dv, ldd, accumulate, m0 + wm * 128, n0 + wn * 128, Mt - wm * 128, Nt - wn * 128,
-                             lane);
 }
 
 }  // namespace
@@ -424,13 +517,15 @@ static hipError_t launch_mx(Kernel kernel, PerDeviceOnce& once, int lds_bytes, c
 hipError_t launch_gemm_mx(const GemmArgs& g, hipStream_t s) {
   if (g.K >= (int64_t{1} << 24)) return hipErrorInvalidValue;   // the kernels' 32-bit byte offsets inside a block of rows
   const int tiles_m = static_cast<int>((g.a.outer + TM - 1) / TM), tiles_n = static_cast<int>((g.b.outer + TN - 1) / TN);
-  const dim3 grid(static_cast<unsigned>(tiles_m) * static_cast<unsigned>(tiles_n));
+  const unsigned tiles = static_cast<unsigned>(tiles_m) * static_cast<unsigned>(tiles_n);
+  const dim3 grid(tiles);
+  const dim3 grid_cus(tiles < 256u ? tiles : 256u);   // the k512 kernel: one workgroup per CU, each running its tiles as one stream
   // 16-byte pieces of scale rows need K / 32 to be a multiple of 16 and the scale arrays 16-byte aligned
   const bool wide = g.K % 512 == 0 && reinterpret_cast<uintptr_t>(g.a.scales) % 16 == 0 && reinterpret_cast<uintptr_t>(g.b.scales) % 16 == 0;
   static PerDeviceOnce set[4];
   if (wide) {
-    if (g.out_bf16) return launch_mx(gemm_mx_kernel_k512<true>, set[0], kWideLdsBytes, g, grid, tiles_m, tiles_n, s);
-    return launch_mx(gemm_mx_kernel_k512<false>, set[1], kWideLdsBytes, g, grid, tiles_m, tiles_n, s);
+    if (g.out_bf16) return launch_mx(gemm_mx_kernel_k512<true>, set[0], kWideLdsBytes, g, grid_cus, tiles_m, tiles_n, s);
+    return launch_mx(gemm_mx_kernel_k512<false>, set[1], kWideLdsBytes, g, grid_cus, tiles_m, tiles_n, s);
   }
   if (g.out_bf16) return launch_mx(gemm_mx_kernel_any_k<true>, set[2], kLdsBytes, g, grid, tiles_m, tiles_n, s);
   return launch_mx(gemm_mx_kernel_any_k<false>, set[3], kLdsBytes, g, grid, tiles_m, tiles_n, s);

@@ -112,6 +112,23 @@ def test_mx_gemm_all_ops(mnk):
     assert rel_fro(dw.cpu().numpy(), oracle.mx_gemm_f64(rat, rbt)) <= GEMM_TOL
 
 
+@pytest.mark.parametrize("K", [512, 1536])
+def test_mx_gemm_with_more_tiles_than_compute_units(K):
+    """17 x 18 tiles of 256 x 256, the last row and column of them ragged: the kernel for K % 512 == 0 is launched with
+    one workgroup per CU, 50 of which run two tiles as one stream of stages (K = 512: one scale chunk per tile, the
+    shortest tile; K = 1536: an odd number of chunks, so the scale ring's phase differs from tile to tile)."""
+    M, N = 4128, 4384
+    ab = synth.normal_with_outliers(M, K, 1.0, 920 + K, frac=0.01)
+    bb = synth.normal(N, K, 0.05, 921 + K)
+    qa = nv.nvfp4_quantize(to_dev(ab), nv.LAYOUT_ROW, nv.BLOCK_MX32)
+    qb = nv.nvfp4_quantize(to_dev(bb), nv.LAYOUT_ROW, nv.BLOCK_MX32)
+    ra, rb = oracle.mx_quantize(ab, oracle.ROW), oracle.mx_quantize(bb, oracle.ROW)
+    d = nv.nvfp4_gemm(qa, qb, nv.OP_DGRAD, nv.OUT_F32)
+    assert d.shape == (M, N) and rel_fro(d.cpu().numpy(), oracle.mx_gemm_f64(ra, rb)) <= GEMM_TOL
+    d16 = nv.nvfp4_gemm(qa, qb, nv.OP_DGRAD, nv.OUT_BF16)
+    assert torch.equal(d16, d.to(torch.bfloat16))
+
+
 def test_mx_and_nvfp4_operands_do_not_mix():
     xb = synth.normal(128, 128, 1.0, 920)
     a = nv.nvfp4_quantize(to_dev(xb), nv.LAYOUT_ROW, nv.BLOCK_MX32)
