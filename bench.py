@@ -583,8 +583,9 @@ def main() -> int:
                      "note": "call time = amax pass + fold + cast pass; one-pass bytes = bf16 read once + both copies written, "
                              "two-pass bytes = the bf16 tensor counted twice (the second read does cross HBM: see traffic)"},
         "dequantize_ms": sum(a.elapsed_time(b) for a, b in deq_events) / len(deq_events),
-        "roofline": {"kernel": "one nvfp4_gemm call = decode_f16_kernel (A, B) + gemm_f16_kernel (256x256 tiles, plus a "
-                               "split-K launch for a partial last round of tiles)",
+        "roofline": {"kernel": "one nvfp4_gemm call = decode_f16_kernel (A, B) + gemm_f16_kernel (256x256 tiles, one "
+                               "workgroup per CU running its tiles as one stream of K steps; for a partial last round of "
+                               "tiles a split-K launch of it + splitk_sum_kernel)",
                      "bound": "mfma", "achieved": gemm_tflops, "peak": PEAK_MFMA_F16_TFLOPS,
                      "unit": "TFLOP/s", "frac": gemm_tflops / PEAK_MFMA_F16_TFLOPS,
                      "traffic": pc.get("gemm_call_traffic_bytes"),
