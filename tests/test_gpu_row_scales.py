@@ -138,6 +138,20 @@ def test_gemm_with_row_scales_all_ops(mnk):
     gemm_all_routes(qd, qw1, nv.OP_DGRAD, oracle.gemm_f64(rd["row"], rw1["row"]))
 
 
+@pytest.mark.parametrize("mnk", [(4112, 4368, 128), (4352, 4096, 1024)])
+def test_gemm_with_row_scales_and_more_tiles_than_compute_units(mnk):
+    """The per-row output stage in the two launch forms the small shapes above do not reach: 306 tiles (ragged last
+    row and column) run as streams of tiles by one workgroup per CU; 272 tiles = one whole round + 16 tiles split
+    two ways along K, whose partial tiles the sum launch scales per row."""
+    M, N, K = mnk
+    x = synth.bf16_bits_to_f32(synth.normal_with_outliers(M, K, 1.0, 1700 + M, frac=0.01))
+    x *= np.exp2(-(np.arange(M) % 12))[:, None].astype(np.float32)             # rows of different magnitude
+    qx, rx = check(synth.f32_to_bf16_bits(x), nv.LAYOUT_ROW, nv.ROUND_RNE, False)
+    wb = synth.normal(K, N, 0.02, 1800 + N)
+    qw = nv.nvfp4_quantize(to_dev(wb), nv.LAYOUT_COL, nv.BLOCK_16x16)
+    gemm_all_routes(qx, qw, nv.OP_FPROP, oracle.gemm_f64(rx["row"], oracle.quantize(wb, oracle.COL, oracle.BLOCK_16x16)))
+
+
 def test_bad_combinations_are_refused():
     x = to_dev(synth.normal(64, 64, 1.0, 1700))
     for kw in (dict(block_dim=nv.BLOCK_16x16), dict(block_dim=nv.BLOCK_MX32), dict(rht_on_col=4), dict(rht_on_col=128)):
