@@ -1,18 +1,21 @@
 // Two-pass form of the block-scaled GEMM (App. B.3 Eq. 5) for gfx950, used when
 // the caller lends a workspace:
 //   pass 1  decode both NVFP4 operands to FP16, value * block_scale (exact: the
-//           product has at most 6 significant bits), K-contiguous, into the
-//           workspace;
+//           product has at most 6 significant bits), into the workspace, in the
+//           order pass 2 loads them;
 //   pass 2  a plain FP16 x FP16 -> FP32 MFMA GEMM whose main loop has no VALU
-//           work at all: tiles go from global memory straight into LDS
-//           (global_load_lds_dwordx4), fragments come from LDS, 16x16x32 MFMAs
-//           (measured under the chip's power limit: a register-only loop of
-//           v_mfma_f32_16x16x32_f16 sustains 12-20 % more flop/s than one of
-//           v_mfma_f32_32x32x16_f16 on the same operand values).
+//           work but address increments: tiles go from global memory straight
+//           into LDS (global_load_lds_dwordx4), fragments come from LDS,
+//           16x16x32 MFMAs (measured under the chip's power limit: a
+//           register-only loop of v_mfma_f32_16x16x32_f16 sustains 12-20 % more
+//           flop/s than one of v_mfma_f32_32x32x16_f16 on the same operand
+//           values); a workgroup runs its tiles as one stream of K steps;
+//   pass 3  only for a last, partial round of tiles, which pass 2 splits along
+//           K: the sum of the partial tiles.
 // Why: decoding inside the GEMM loop costs about one VALU instruction per
 // element, and VALU instructions co-issued with MFMAs take matrix-pipe time
-// (measured: the fused kernel runs at 1.0-1.07 PFLOP/s, this pair at about
-// 1.39 PFLOP/s in the GEMM proper, the decode pass adding 5-8 % of its time).
+// (measured: the fused kernel runs at 1.0-1.07 PFLOP/s, this route at 1.5-1.6
+// in the GEMM proper, the decode pass adding 5-8 % of its time).
 // The results are identical to the fused kernel's up to FP32 summation order.
 #include <type_traits>
 
