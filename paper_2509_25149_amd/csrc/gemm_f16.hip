@@ -53,35 +53,34 @@ __device__ __forceinline__ half2v scale_h2(uint32_t e4m3_byte) {
   return r;
 }
 
-// Layout of a decoded operand ([outer, K] elements, K a multiple of 64): the pieces the GEMM loads with one
-// instruction -- 8 rows x 64 k = 1 KiB -- are contiguous, and the K steps of an 8-row block follow each other:
-//   byte address of element (r, k) = (((r / 8) * (K / 64) + k / 64) * 8 + r % 8) * 128 + position * 16 + (k % 8) * 2,
-//   position = (k % 64) / 8 ^ ((r >> 1) & 7),
-// i.e. the 16-byte chunks of a row's 128 bytes already sit where the GEMM's LDS swizzle wants them, so a load
-// instruction reads 1 KiB of consecutive addresses, lane l its bytes 16 l .. 16 l + 15.  Against rows of K * 2 bytes
-// (8 separate 128-byte pieces per instruction, K * 2 bytes apart, a stride that puts the pieces of all 256 tile
-// rows into few cache channels) the GEMM's K step took 5-10 % less time on the three 12B shapes (1.41 -> 1.27,
-// 1.22 -> 1.20, 1.42 -> 1.32 us by timestamps inside the kernel, same process, same data, identical results).
+// Layout of a decoded operand ([outer, K] elements, outer a multiple of 16, K of 64): the piece the GEMM loads with
+// one instruction and reads back as one MFMA fragment -- 16 rows x 32 k = 1 KiB -- is contiguous, the K steps of a
+// 16-row block follow each other, and inside a piece the 16-byte chunks (8 k of one row) are in fragment order, the
+// lane's order (lane l of an MFMA operand holds chunk l / 16 of row l % 16):
+//   byte address of element (r, k) = ((r / 16) * (K / 32) + k / 32) * 1024 + (((k % 32) / 8) * 16 + r % 16) * 16 + (k % 8) * 2.
+// So a load instruction reads 1 KiB of consecutive addresses into 1 KiB of consecutive LDS, and a fragment read is
+// 1 KiB of consecutive LDS, lane l its bytes 16 l .. 16 l + 15: no bank conflicts, no swizzle.  (Measured with 8-row x
+// 64-k pieces against rows of K * 2 bytes -- 8 separate 128-byte pieces per instruction, a stride that puts the
+// pieces of all 256 tile rows into few cache channels: the GEMM's K step took 5-10 % less time on the three 12B
+// shapes, same process, same data, identical results.)
 //
-// The decode pass: a workgroup takes an 8-row block x 1024 k (16 K steps).  It reads the block's codes and scales
-// row by row (512 and 64 contiguous bytes per row), passes them through LDS, and writes the 16 KiB of FP16 in output
-// order, a thread 16 bytes at a time, consecutive threads consecutive addresses -- so that both sides of the pass
-// move whole cache lines.  (With each thread fetching the 8 bytes of codes behind its own 32 bytes of output, reads
-// came in 64-byte pieces K / 2 bytes apart and the pass took half as long again.)  Both operands are decoded by
-// one launch: the 8-row blocks of B follow those of A in the grid.
-constexpr int kDecodeSteps = 16;                        // K steps per workgroup
-constexpr int kDecodeCodeRow = kDecodeSteps * 32 + 32;  // bytes per row of codes in LDS; the 32 keep 8 rows off each other's banks
-constexpr int kDecodeScaleRow = kDecodeSteps * 4 + 4;   // likewise for the scales
+// The decode pass: a workgroup takes a 16-row block x 512 k.  It reads the block's codes and scales row by row (256
+// and 32 contiguous bytes per row), passes them through LDS, and writes 16 pieces of FP16 in output order, a thread
+// 16 bytes at a time, consecutive threads consecutive addresses -- so that both sides of the pass move whole cache
+// lines.  Both operands are decoded by one launch: the 16-row blocks of B follow those of A in the grid.
+constexpr int kDecodeK = 512;                           // k per workgroup
+constexpr int kDecodeCodeRow = kDecodeK / 2 + 16;       // bytes per row of codes in LDS; the 16 keep 16 rows off each other's banks
+constexpr int kDecodeScaleRow = kDecodeK / 16 + 4;      // likewise for the scales
 __global__ __launch_bounds__(256) void decode_f16_kernel(const uint8_t* __restrict__ a_codes,
                                                          const uint8_t* __restrict__ a_scales, int a_blocks,
                                                          _Float16* __restrict__ a_out,
                                                          const uint8_t* __restrict__ b_codes,
                                                          const uint8_t* __restrict__ b_scales, int b_blocks,
                                                          _Float16* __restrict__ b_out, int64_t K) {
-  __shared__ __attribute__((aligned(16))) uint8_t lds_codes[8 * kDecodeCodeRow];
-  __shared__ __attribute__((aligned(4))) uint8_t lds_scales[8 * kDecodeScaleRow];
-  // consecutive workgroups walk along K: they read consecutive pieces of the same 8 rows and write consecutive 16 KiB
-  const int k_groups = static_cast<int>((K / 64 + kDecodeSteps - 1) / kDecodeSteps);
+  __shared__ __attribute__((aligned(16))) uint8_t lds_codes[16 * kDecodeCodeRow];
+  __shared__ __attribute__((aligned(4))) uint8_t lds_scales[16 * kDecodeScaleRow];
+  // consecutive workgroups walk along K: they read consecutive pieces of the same 16 rows and write consecutive 16 KiB
+  const int k_groups = static_cast<int>((K + kDecodeK - 1) / kDecodeK);
   int blk = static_cast<int>(blockIdx.x) / k_groups;
   const int k_group = static_cast<int>(blockIdx.x) - blk * k_groups;
   const bool in_a = blk < a_blocks;
@@ -91,68 +90,64 @@ __global__ __launch_bounds__(256) void decode_f16_kernel(const uint8_t* __restri
   const uint8_t* scales = in_a ? a_scales : b_scales;
   uint4* out = reinterpret_cast<uint4*>(in_a ? a_out : b_out);
   const int t = static_cast<int>(threadIdx.x);
-  const int KT = static_cast<int>(K / 64), kt0 = k_group * kDecodeSteps;
+  const int64_t k0 = static_cast<int64_t>(k_group) * kDecodeK;
   {
-    // codes: thread -> row t / 32, 32 elements (16 bytes) at k = 64 kt0 + 32 (t % 32)
-    const int row = t >> 5, piece = t & 31;
-    const int64_t k = static_cast<int64_t>(kt0) * 64 + piece * 32;
+    // codes: thread -> row t / 16, 32 elements (16 bytes) at k = k0 + 32 (t % 16)
+    const int row = t >> 4, piece = t & 15;
+    const int64_t k = k0 + piece * 32;
     if (k < K)
       *reinterpret_cast<uint4*>(lds_codes + row * kDecodeCodeRow + piece * 16) =
-          *reinterpret_cast<const uint4*>(codes + ((static_cast<int64_t>(blk) * 8 + row) * K + k) / 2);
-    // scales: threads 0..127 -> row t / 16, the four scale bytes of K step kt0 + t % 16
+          *reinterpret_cast<const uint4*>(codes + ((static_cast<int64_t>(blk) * 16 + row) * K + k) / 2);
+    // scales: threads 0..127 -> row t / 8, the four scale bytes of the 64 k from k0 + 64 (t % 8)
     if (t < 128) {
-      const int srow = t >> 4, j = t & 15;
-      if (kt0 + j < KT)
+      const int srow = t >> 3, j = t & 7;
+      if (k0 + j * 64 < K)
         *reinterpret_cast<uint32_t*>(lds_scales + srow * kDecodeScaleRow + j * 4) =
-            *reinterpret_cast<const uint32_t*>(scales + (static_cast<int64_t>(blk) * 8 + srow) * (K / 16) + static_cast<int64_t>(kt0 + j) * 4);
+            *reinterpret_cast<const uint32_t*>(scales + ((static_cast<int64_t>(blk) * 16 + srow) * K + k0 + j * 64) / 16);
     }
   }
   __syncthreads();
+  const int64_t pieces_per_block = K / 32;
 #pragma unroll
-  for (int u = 0; u < kDecodeSteps / 4; ++u) {
-    // 16-byte piece number o of the workgroup's output: K step kt0 + o / 64, row (o / 8) % 8, position o % 8
+  for (int u = 0; u < 4; ++u) {
+    // 16-byte chunk number o of the workgroup's output: piece o / 64 (32 k each), chunk (o / 16) % 4 of it, row o % 16
     const int o = u * 256 + t;
-    const int step = o >> 6, r8 = (o >> 3) & 7, pos = o & 7;
-    if (kt0 + step >= KT) break;
-    const int chunk = pos ^ ((blk * 4 + (r8 >> 1)) & 7);   // = pos ^ ((row >> 1) & 7), row = 8 blk + r8
-    const uint32_t c = *reinterpret_cast<const uint32_t*>(lds_codes + r8 * kDecodeCodeRow + step * 32 + chunk * 4);
-    const uint32_t s4 = *reinterpret_cast<const uint32_t*>(lds_scales + r8 * kDecodeScaleRow + step * 4);
-    out[(static_cast<int64_t>(blk) * KT + kt0 + step) * 64 + r8 * 8 + pos] = dec8(c, scale_h2((s4 >> ((chunk >> 1) * 8)) & 0xffu));
+    const int piece = o >> 6, chunk = (o >> 4) & 3, r16 = o & 15;
+    if (k0 + piece * 32 >= K) break;
+    const uint32_t c = *reinterpret_cast<const uint32_t*>(lds_codes + r16 * kDecodeCodeRow + piece * 16 + chunk * 4);
+    const uint32_t s4 = *reinterpret_cast<const uint32_t*>(lds_scales + r16 * kDecodeScaleRow + (piece >> 1) * 4);
+    const uint32_t scale = (s4 >> ((((piece & 1) * 2) + (chunk >> 1)) * 8)) & 0xffu;
+    out[(static_cast<int64_t>(blk) * pieces_per_block + k0 / 32 + piece) * 64 + chunk * 16 + r16] = dec8(c, scale_h2(scale));
   }
 }
 
 // ---------------------------------------------------------------- pass 2: FP16 GEMM
-// 256 x 256 outputs per workgroup, K step 64, 256 threads = 4 wavefronts (2 x 2), one per SIMD,
+// 256 x 256 outputs per workgroup, 256 threads = 4 wavefronts (2 x 2), one per SIMD,
 // each 128 x 128 outputs as 8 x 8 MFMA 16x16 blocks: 256 accumulator registers, which live in
 // the accumulation half of the register file, and 16 fragment loads per 64 MFMAs (a 128 x 64
-// wave tile needs 12 per 32).  LDS holds two stages of (A tile, B tile), 64 KiB each; a stage is
-// filled by direct global->LDS loads: one instruction moves 64 lanes x 16 bytes into 1 KiB of
-// consecutive LDS, i.e. 8 tile rows of 128 bytes, and lane l fetches the 16-byte chunk that
-// belongs at chunk position l & 7 of row l >> 3 under the XOR swizzle
-// (chunk c of row r lives at position c ^ ((r >> 1) & 7)).
+// wave tile needs 12 per 32).  LDS is a ring of four stages of 32 k: (A tile, B tile) as 16 + 16 pieces of
+// 16 rows x 32 k, 32 KiB a stage.  A stage is filled by direct global->LDS loads: one instruction moves 64 lanes x 16
+// bytes, one piece of the decoded operand, into 1 KiB of consecutive LDS, which is one MFMA fragment in lane order.
 //
 // With one wavefront per SIMD nothing else can fill the matrix pipe while this one waits, so the
-// loop is software-pipelined across its barrier and its instruction order is fixed by hand (inline
+// loop is software-pipelined and its instruction order is fixed by hand (inline
 // assembly keeps the compiler from regrouping it; measured 1.18 against 1.06 PFLOP/s for the
 // 8-wavefront form on the same operands, at a lower clock: the chip's power limit sets the speed,
-// and this form moves a third less data from LDS per flop):
-//   block 1   64 MFMAs on the first 32 k of the stage; after every fourth, one of the 16 fragment
-//             loads for the second 32 k
-//   wait      own fragment loads back, own global->LDS loads (issued one step ago) landed; barrier:
-//             every wavefront holds all it needs of this stage, and the next stage is complete
-//   block 2   64 MFMAs on the second 32 k; after every second, alternately one fragment load for
-//             the first 32 k of the next stage and one global->LDS load of the stage after that,
-//             into the buffer just freed
-// so the barrier falls between two blocks of MFMAs that are already fed.
-constexpr int TM = 256, TN = 256, TK = 64;
+// and this form moves a third less data from LDS per flop).  Stage g:
+//   64 MFMAs on the fragments read during stage g - 1; after every fourth, one of the 16 fragment loads of stage
+//   g + 1; after every eighth, one of the wavefront's 8 global->LDS loads of stage g + 4 into the buffer of stage g,
+//   which nobody reads any more
+//   wait      own fragment loads back; own global->LDS loads of stage g + 2 landed (those of g + 3 and g + 4 may
+//             still be on their way); barrier: every wavefront holds stage g + 1 in registers, stage g + 2 is complete
+// so a load has three to four stages -- some 1.5 us -- to arrive in.
+constexpr int TM = 256, TN = 256, TK = 64;       // TK: the unit K is split and counted in, two stages
 constexpr int kThreads = 256;
-constexpr int kRowBytes = TK * 2;
-constexpr int kPieceBytes = 8 * kRowBytes;      // what one load instruction moves: 8 rows of a K step, 1 KiB, contiguous in the decoded operand
-constexpr int kOperandBytes = TM * kRowBytes;   // 32 KiB
-constexpr int kStageBytes = 2 * kOperandBytes;  // 64 KiB
-constexpr int kLdsBytes = 2 * kStageBytes;
-
-__device__ __forceinline__ int swz(int row, int chunk) { return row * kRowBytes + ((chunk ^ ((row >> 1) & 7)) << 4); }
+constexpr int kStageK = 32;
+constexpr int kPieceBytes = 16 * kStageK * 2;           // what one load instruction moves: 16 rows x 32 k, 1 KiB, contiguous in the decoded operand
+constexpr int kOperandBytes = (TM / 16) * kPieceBytes;  // 16 KiB
+constexpr int kStageBytes = 2 * kOperandBytes;          // 32 KiB
+constexpr int kStages = 4;
+constexpr int kLdsBytes = kStages * kStageBytes;
 
 // Fragments of one 32-wide half of a K step for a 128 x 128 wave tile.  A 16x16x32 MFMA operand
 // is 16 rows x 32 k: lane l holds the 8 consecutive k of 16-byte chunk (l >> 4) of row (l & 15).
@@ -182,12 +177,11 @@ __device__ __forceinline__ void lds_read16(half8v& dst, uint32_t addr) {
   asm volatile("ds_read_b128 %0, %1 offset:%2" : "=&v"(dst) : "v"(addr), "n"(kOff));
 }
 
-// Fragment q of a 16-fragment set: 0..7 = A rows i * 16, 8..15 = B rows j * 16 (2 KiB apart; the
-// swizzle term does not change with multiples of 16 rows).
+// Fragment q of a 16-fragment set: 0..7 = A rows i * 16, 8..15 = B rows j * 16: one piece each.
 template <int q>
 __device__ __forceinline__ void read_frag(Frags& f, uint32_t a_addr, uint32_t b_addr) {
-  if constexpr (q < 8) lds_read16<q * 16 * kRowBytes>(f.a[q], a_addr);
-  else lds_read16<(q - 8) * 16 * kRowBytes>(f.b[q - 8], b_addr);
+  if constexpr (q < 8) lds_read16<q * kPieceBytes>(f.a[q], a_addr);
+  else lds_read16<(q - 8) * kPieceBytes>(f.b[q - 8], b_addr);
 }
 
 // 64 lanes x 16 bytes from global memory (wave-uniform base + per-lane 32-bit offset) straight into
@@ -254,10 +248,10 @@ __global__ __launch_bounds__(kThreads) void gemm_f16_kernel(const _Float16* __re
     return wg;   // the tile's number within the launch
   };
 
-  // Direct-load sources: instruction q of wavefront w fills rows w * 64 + 8 q .. + 7 of a tile, which the decoded
-  // operand holds as 1 KiB of consecutive bytes per K step, in LDS order (lane l: bytes 16 l .. 16 l + 15).  An address
+  // Direct-load sources: instruction q of wavefront w fills rows w * 64 + 16 q .. + 15 of a tile, which the decoded
+  // operand holds as 1 KiB of consecutive bytes per stage, in LDS order (lane l: bytes 16 l .. 16 l + 15).  An address
   // is a wave-uniform 64-bit base per operand tile plus a per-lane 32-bit offset per instruction (256 rows of K * 2
-  // bytes: K < 2^21, checked on the host), which holds the 8-row block and the K step being fetched.  A block past
+  // bytes: K < 2^21, checked on the host), which holds the 16-row block and the stage being fetched.  A block past
   // the end of an operand is replaced by the operand's last block (rows come in multiples of 16); it only feeds
   // outputs that are never stored.
   // One instruction per load inside the loop (a single wavefront per SIMD issues in order: what it spends on anything
@@ -269,45 +263,39 @@ __global__ __launch_bounds__(kThreads) void gemm_f16_kernel(const _Float16* __re
   // compiler could keep from before the first tile would have to live through every output stage, which needs the
   // registers itself, and end up in scratch memory, to be fetched back inside the K steps.
   const uint32_t lds0 = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(lds));
-  uint32_t lane_bytes = 0;                   // the lane's part of a load offset
-  uint32_t a_lo = 0, a_hi = 0, b_lo = 0, b_hi = 0;   // fragment addresses in stage 0: first / second 32 k of the step
+  uint32_t lane_bytes = 0;          // the lane's part of a load offset
+  uint32_t a_frag = 0, b_frag = 0;  // the lane's 16 bytes of the wavefront's first A / B fragment in ring buffer 0
   auto lane_setup = [&]() {
-    const int lane = lane_id();
-    lane_bytes = static_cast<uint32_t>(lane) * 16u;
-    const int arow = (wave >> 1) * 128 + (lane & 15), brow = (wave & 1) * 128 + (lane & 15), lq = lane >> 4;
-    a_lo = lds0 + swz(arow, lq);
-    a_hi = lds0 + swz(arow, 4 + lq);
-    b_lo = lds0 + kOperandBytes + swz(brow, lq);
-    b_hi = lds0 + kOperandBytes + swz(brow, 4 + lq);
+    lane_bytes = static_cast<uint32_t>(lane_id()) * 16u;
+    a_frag = lds0 + (wave >> 1) * (8 * kPieceBytes) + lane_bytes;
+    b_frag = lds0 + kOperandBytes + (wave & 1) * (8 * kPieceBytes) + lane_bytes;
   };
   lane_setup();
   const char* base_a = nullptr;
   const char* base_b = nullptr;
-  uint32_t voff[16];   // q 0..7 A, 8..15 B
-  // Point the loads at K step kt of tile (tm, tn).
-  auto aim = [&](int tm, int tn, int kt) {
+  uint32_t voff[8];   // q 0..3 A, 4..7 B
+  // Point the loads at stage st (32 k) of tile (tm, tn).
+  auto aim = [&](int tm, int tn, int st) {
     const int64_t m_first = static_cast<int64_t>(tm) * TM, n_first = static_cast<int64_t>(tn) * TN;
     base_a = reinterpret_cast<const char*>(A) + m_first * K * 2 - 3 * 1024;
     base_b = reinterpret_cast<const char*>(B) + n_first * K * 2 - 3 * 1024;
-    // 8-row blocks counted from the tile's first; a block's K steps are K / 64 KiB
-    const uint32_t last_a = static_cast<uint32_t>(M - 8 - m_first) >> 3, last_b = static_cast<uint32_t>(N - 8 - n_first) >> 3;
+    // 16-row blocks counted from the tile's first; a block's stages are K / 32 KiB
+    const uint32_t last_a = static_cast<uint32_t>(M - 16 - m_first) >> 4, last_b = static_cast<uint32_t>(N - 16 - n_first) >> 4;
 #pragma unroll
-    for (int q = 0; q < 8; ++q) {
-      const uint32_t blk = static_cast<uint32_t>(wave * 8 + q);
-      const uint32_t fixed = static_cast<uint32_t>(3 - (q & 3)) * 1024u + static_cast<uint32_t>(kt) * kPieceBytes;
-      voff[q] = lane_bytes + min(blk, last_a) * static_cast<uint32_t>(K * 16) + fixed;
-      voff[8 + q] = lane_bytes + min(blk, last_b) * static_cast<uint32_t>(K * 16) + fixed;
+    for (int q = 0; q < 4; ++q) {
+      const uint32_t blk = static_cast<uint32_t>(wave * 4 + q);
+      const uint32_t fixed = static_cast<uint32_t>(3 - q) * 1024u + static_cast<uint32_t>(st) * kPieceBytes;
+      voff[q] = lane_bytes + min(blk, last_a) * static_cast<uint32_t>(K * 32) + fixed;
+      voff[4 + q] = lane_bytes + min(blk, last_b) * static_cast<uint32_t>(K * 32) + fixed;
     }
   };
-  const uint32_t fill0 = lds0 + wave * 8192;   // this wavefront's 8 KiB of each operand tile
-  // load q of the 16 that fill stage `stage`
-  auto issue = [&](auto qc, int stage) {
+  const uint32_t fill0 = lds0 + wave * (4 * kPieceBytes);   // this wavefront's 4 KiB of each operand tile
+  // load q of the wavefront's 8 that fill ring buffer `buf`
+  auto issue = [&](auto qc, uint32_t buf) {
     constexpr int q = decltype(qc)::value;
-    const char* base = q < 8 ? base_a : base_b;
-    if constexpr ((q & 3) == 0)
-      load_1k_to_lds(voff[q], base, fill0 + stage * kStageBytes + (q < 8 ? 0 : kOperandBytes) + (q & 4) * 1024);
-    else
-      load_1k_to_lds_next<(q & 3) * 1024>(voff[q], base);
+    const char* base = q < 4 ? base_a : base_b;
+    if constexpr ((q & 3) == 0) load_1k_to_lds(voff[q], base, fill0 + buf * kStageBytes + (q < 4 ? 0 : kOperandBytes));
+    else load_1k_to_lds_next<(q & 3) * 1024>(voff[q], base);
   };
 
   const int KT = static_cast<int>(K / TK);
@@ -318,74 +306,85 @@ __global__ __launch_bounds__(kThreads) void gemm_f16_kernel(const _Float16* __re
   const int tile_local = locate(item / k_splits, tm, tn);
   int kt_begin = static_cast<int>(static_cast<int64_t>(KT) * split / k_splits);
   int kt_end = static_cast<int>(static_cast<int64_t>(KT) * (split + 1) / k_splits);   // > kt_begin: KT >= k_splits
-  // The K step the loads point at: they run two steps ahead of the MFMAs.
-  int fetch_kt = kt_begin;
-  aim(tm, tn, fetch_kt);
-  static_for<0, 16>([&](auto q) { issue(q, 0); });
-  if (fetch_kt + 1 < kt_end) {
-    ++fetch_kt;
+  // The stage the loads were last pointed at: they run four stages ahead of the MFMAs.
+  int fetch_st = 2 * kt_begin;
+  aim(tm, tn, fetch_st);
+  static_for<0, 8>([&](auto q) { issue(q, 0); });
 #pragma unroll
-    for (int q = 0; q < 16; ++q) voff[q] += kPieceBytes;
+  for (uint32_t buf = 1; buf < kStages; ++buf) {
+    if (fetch_st + 1 < 2 * kt_end) {   // (an item of two stages fetches its last three times)
+      ++fetch_st;
+#pragma unroll
+      for (int q = 0; q < 8; ++q) voff[q] += kPieceBytes;
+    }
+    static_for<0, 8>([&](auto q) { issue(q, buf); });
   }
-  static_for<0, 16>([&](auto q) { issue(q, 1); });
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  asm volatile("s_waitcnt vmcnt(16)" ::: "memory");   // the first two stages
   __builtin_amdgcn_s_barrier();
 
   Frags f0, f1;
   float4v acc[8][8];
-  uint32_t parity = 0;          // of the number of K steps done so far: which LDS stage holds the current one
+  uint32_t g = 0;               // stages done so far; stage g lives in ring buffer g % 4
   bool stores_behind = false;   // the previous tile's kTileStores stores were issued after the loads now in flight
   for (;;) {
-    // The tile's first fragments.  (After a tile of the same stream its last step has read them already; they are read
-    // again so that the output stage had their registers to work with.)
-    static_for<0, 16>([&](auto q) { read_frag<decltype(q)::value>(f0, a_lo + parity * kStageBytes, b_lo + parity * kStageBytes); });
+    // The tile's first fragments.  (After a tile of the same stream its last stage has read them already; they are read
+    // again so that the output stage had their registers to work with.)  The barrier: the first stage loads into the
+    // buffer these came from.
+    {
+      const uint32_t cur = (g & 3u) * kStageBytes;
+      static_for<0, 16>([&](auto q) { read_frag<decltype(q)::value>(f0, a_frag + cur, b_frag + cur); });
+    }
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    // The next tile of this workgroup, if any: its K steps follow this tile's without a break (k_splits == 1 then).
+    __builtin_amdgcn_s_barrier();
+    // The next tile of this workgroup, if any: its stages follow this tile's without a break (k_splits == 1 then).
     const int next_item = item + static_cast<int>(gridDim.x);
     const bool has_next = next_item < items;
     int next_tm = 0, next_tn = 0;
     if (has_next) locate(next_item, next_tm, next_tn);
+    const int st_end = 2 * kt_end;
 
-    // One K step; kFirst: the item's first (accumulators start from zero, and the stores of the tile before may still
-    // be in flight behind the loads this step waits for).
-    auto k_step = [&](auto first_tag) {
-      constexpr bool kFirst = decltype(first_tag)::value;
-      const uint32_t cur = parity * kStageBytes, nxt = cur ^ kStageBytes;
-      // The loads move on one step: within the tile, or to the next tile's step 0, or, with nothing to follow, not at
-      // all (the last step is fetched again, into a buffer nobody reads any more: no branches around the loads).
+    // One stage on the fragments in `fc`, reading the next stage's into `fn`.  kFirst: the item's first (accumulators
+    // start from zero); kRelaxed: one of its first two (the stores of the tile before may still be in flight behind
+    // the loads this stage waits for).
+    auto stage = [&](auto first_tag, auto relaxed_tag, Frags& fc, Frags& fn) {
+      constexpr bool kFirst = decltype(first_tag)::value, kRelaxed = decltype(relaxed_tag)::value;
+      const uint32_t buf = g & 3u, nxt = ((g + 1u) & 3u) * kStageBytes;
+      // The loads move on one stage: within the tile, or to the next tile's stage 0, or, with nothing to follow, not at
+      // all (the last stage is fetched again, into a buffer nobody reads any more: no branches around the loads).
       uint32_t advance = kPieceBytes;
-      if (fetch_kt + 1 < kt_end) {
-        ++fetch_kt;
+      if (fetch_st + 1 < st_end) {
+        ++fetch_st;
       } else {
         advance = 0;
         if (has_next) {
-          fetch_kt = 0;
+          fetch_st = 0;
           aim(next_tm, next_tn, 0);
         }
       }
       static_for<0, 64>([&](auto ic) {
         constexpr int n = decltype(ic)::value;
-        if constexpr (kFirst) mfma_first(acc[n >> 3][n & 7], f0.b[n & 7], f0.a[n >> 3]);
-        else mfma(acc[n >> 3][n & 7], f0.b[n & 7], f0.a[n >> 3]);
-        if constexpr ((n & 3) == 1) read_frag<(n >> 2)>(f1, a_hi + cur, b_hi + cur);
-        if constexpr ((n & 3) == 3) voff[n >> 2] += advance;
+        if constexpr (kFirst) mfma_first(acc[n >> 3][n & 7], fc.b[n & 7], fc.a[n >> 3]);
+        else mfma(acc[n >> 3][n & 7], fc.b[n & 7], fc.a[n >> 3]);
+        if constexpr ((n & 3) == 1) read_frag<(n >> 2)>(fn, a_frag + nxt, b_frag + nxt);
+        if constexpr ((n & 7) == 3) {
+          voff[n >> 3] += advance;
+          issue(std::integral_constant<int, (n >> 3)>{}, buf);
+        }
       });
-      // Memory operations complete in issue order, so "at most kTileStores outstanding" means that the loads issued
-      // before those stores have landed.
-      if (kFirst && stores_behind) asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(kTileStores<kBf16Out>) : "memory");
-      else asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+      // Memory operations complete in issue order.  Behind the loads of stage g + 2 this wavefront has issued those of
+      // g + 3 and g + 4, 8 each, and, across a tile boundary, the stores of the tile before.
+      if (kRelaxed && stores_behind)
+        asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(16 + kTileStores<kBf16Out> > 63 ? 63 : 16 + kTileStores<kBf16Out>) : "memory");
+      else asm volatile("s_waitcnt vmcnt(16) lgkmcnt(0)" ::: "memory");
       __builtin_amdgcn_s_barrier();
-      static_for<0, 64>([&](auto ic) {
-        constexpr int n = decltype(ic)::value;
-        mfma(acc[n >> 3][n & 7], f1.b[n & 7], f1.a[n >> 3]);
-        if constexpr ((n & 3) == 1) read_frag<(n >> 2)>(f0, a_lo + nxt, b_lo + nxt);
-        if constexpr ((n & 3) == 3) issue(std::integral_constant<int, (n >> 2)>{}, static_cast<int>(parity));
-      });
-      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-      parity ^= 1u;
+      ++g;
     };
-    k_step(std::true_type{});
-    for (int kt = kt_begin + 1; kt < kt_end; ++kt) k_step(std::false_type{});
+    stage(std::true_type{}, std::true_type{}, f0, f1);
+    stage(std::false_type{}, std::true_type{}, f1, f0);
+    for (int kt = kt_begin + 1; kt < kt_end; ++kt) {
+      stage(std::false_type{}, std::false_type{}, f0, f1);
+      stage(std::false_type{}, std::false_type{}, f1, f0);
+    }
 
     // Everything below is computed here, per tile: were the compiler to move the output stage's loop-invariant
     // address arithmetic in front of the stream, it would have to keep it in registers through the K steps, which
@@ -400,8 +399,8 @@ __global__ __launch_bounds__(kThreads) void gemm_f16_kernel(const _Float16* __re
     const int Nt = static_cast<int>(N - n0 < TN ? N - n0 : TN);
     // The MFMA results must have left the pipe before ordinary instructions read the accumulators (the compiler
     // cannot see into the assembly statements to insert these wait states itself).  With nothing to follow, the
-    // trailing global->LDS loads must have landed before LDS is reused or the wavefront ends; otherwise the next
-    // tile's first K step is in LDS by now and its second on its way there.
+    // trailing global->LDS loads must have landed before the wavefront ends; otherwise the next
+    // tile's first two stages are in LDS by now and two more on their way there.
     if (has_next) {
       asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
     } else {
@@ -430,7 +429,7 @@ __global__ __launch_bounds__(kThreads) void gemm_f16_kernel(const _Float16* __re
     kt_begin = 0;
     kt_end = KT;
     lane_setup();
-    aim(tm, tn, fetch_kt);
+    aim(tm, tn, fetch_st);
   }
 }
 
@@ -563,10 +562,10 @@ static hipError_t launch_f16(bool bf16_out, const _Float16* a16, const _Float16*
 }
 #undef NVFP4_LAUNCH_F16
 
-// Grid of the decode pass for `blocks` 8-row blocks: a workgroup per block and group of kDecodeSteps K steps.  False
+// Grid of the decode pass for `blocks` 16-row blocks: a workgroup per block and kDecodeK elements of K.  False
 // if that is more than a grid can hold (operands beyond 2^44 elements).
 static bool decode_grid(int64_t blocks, int64_t K, dim3* grid) {
-  const int64_t n = blocks * ((K / TK + kDecodeSteps - 1) / kDecodeSteps);
+  const int64_t n = blocks * ((K + kDecodeK - 1) / kDecodeK);
   if (n > 0x7fffffff) return false;
   *grid = dim3(static_cast<unsigned>(n));
   return true;
@@ -574,9 +573,9 @@ static bool decode_grid(int64_t blocks, int64_t K, dim3* grid) {
 
 hipError_t launch_predecode(const Operand& op, int64_t K, void* fp16_out, hipStream_t s) {
   dim3 grid;
-  if (!decode_grid(op.outer / 8, K, &grid)) return hipErrorInvalidValue;
+  if (!decode_grid(op.outer / 16, K, &grid)) return hipErrorInvalidValue;
   hipLaunchKernelGGL(decode_f16_kernel, grid, dim3(256), 0, s, op.codes, op.scales,
-                     static_cast<int>(op.outer / 8), static_cast<_Float16*>(fp16_out), op.codes, op.scales, 0,
+                     static_cast<int>(op.outer / 16), static_cast<_Float16*>(fp16_out), op.codes, op.scales, 0,
                      static_cast<_Float16*>(fp16_out), K);
   return hipGetLastError();
 }
@@ -594,9 +593,9 @@ hipError_t launch_gemm_two_pass(const GemmArgs& g, hipStream_t s) {
   // One launch decodes what is still to decode.
   if (rows_a + rows_b > 0) {
     dim3 grid;
-    if (!decode_grid((rows_a + rows_b) / 8, K, &grid)) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(decode_f16_kernel, grid, dim3(256), 0, s, g.a.codes, g.a.scales, static_cast<int>(rows_a / 8), a_ws,
-                       g.b.codes, g.b.scales, static_cast<int>(rows_b / 8), b_ws, K);
+    if (!decode_grid((rows_a + rows_b) / 16, K, &grid)) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(decode_f16_kernel, grid, dim3(256), 0, s, g.a.codes, g.a.scales, static_cast<int>(rows_a / 16), a_ws,
+                       g.b.codes, g.b.scales, static_cast<int>(rows_b / 16), b_ws, K);
   }
   const int tiles_m = static_cast<int>((M + TM - 1) / TM), tiles_n = static_cast<int>((N + TN - 1) / TN);
   const int tiles = tiles_m * tiles_n;

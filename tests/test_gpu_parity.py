@@ -450,15 +450,11 @@ def test_predecoded_operands_give_the_same_bits():
     w_row16 = nv.nvfp4_predecode(qw, nv.COPY_ROW)
     assert w_col16.shape == (d_out, d_in) and w_row16.shape == (d_in, d_out)
     # The decoded copy is value * block scale (no tensor scale): times s_dec it is the dequantized tensor, up to FP32
-    # rounding -- once its elements are put back in row order.  The buffer holds them as the GEMM loads them: 8-row
-    # blocks, within a block the K steps of 64, within a step the 8 rows of 128 bytes, and within a row the eight
-    # 16-byte chunks at position chunk ^ ((row >> 1) & 7).
-    tiled = w_col16.view(d_out // 8, d_in // 64, 8, 8, 8)            # [block][K step][row in block][position][8 elements]
-    rows = torch.arange(d_out, device="cuda").view(d_out // 8, 1, 8, 1)
-    chunk_at = torch.arange(8, device="cuda").view(1, 1, 1, 8) ^ ((rows >> 1) & 7)   # the chunk stored at each position
-    by_chunk = torch.empty_like(tiled)
-    by_chunk.scatter_(3, chunk_at.unsqueeze(-1).expand_as(tiled), tiled)
-    row_major = by_chunk.permute(0, 2, 1, 3, 4).reshape(d_out, d_in)
+    # rounding -- once its elements are put back in row order.  The buffer holds them as the GEMM loads them: 16-row
+    # blocks, within a block the steps of 32 k, and within a step (1 KiB) the 16-byte chunks chunk-major: the 16 rows'
+    # first 8 k, then their second, third and fourth.
+    tiled = w_col16.view(d_out // 16, d_in // 32, 4, 16, 8)          # [block][step][chunk][row in block][8 elements]
+    row_major = tiled.permute(0, 3, 1, 2, 4).reshape(d_out, d_in)
     deq = nv.nvfp4_dequantize(qw, nv.COPY_COL)
     assert torch.allclose(row_major.float() * qw.col_ts[0], deq, rtol=1e-6, atol=0)
     # less scratch is enough now: only X (or dY) and the partial tiles
