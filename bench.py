@@ -61,16 +61,19 @@ def probe_lib():
         L.bench_mfma_probe_threads.restype = ctypes.c_int
         L.bench_mfma_rate.restype = ctypes.c_int
         L.bench_mfma_rate.argtypes = [ctypes.c_int, ctypes.c_int64, ctypes.c_void_p, ctypes.POINTER(ctypes.c_double), ctypes.c_void_p]
+        L.bench_mfma_rate_gemm_block.restype = ctypes.c_int
+        L.bench_mfma_rate_gemm_block.argtypes = L.bench_mfma_rate.argtypes
         L.bench_stream_copy.restype = ctypes.c_int
         L.bench_stream_copy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
         _probe = L
     return _probe
 
 
-def mfma_rate(torch, kind: int, iters: int, buf) -> float:
+def mfma_rate(torch, kind: int, iters: int, buf, gemm_block: bool = False) -> float:
     import ctypes
     flops = ctypes.c_double(0.0)
-    rc = probe_lib().bench_mfma_rate(kind, iters, buf.data_ptr(), ctypes.byref(flops), torch.cuda.current_stream().cuda_stream)
+    fn = probe_lib().bench_mfma_rate_gemm_block if gemm_block else probe_lib().bench_mfma_rate
+    rc = fn(kind, iters, buf.data_ptr(), ctypes.byref(flops), torch.cuda.current_stream().cuda_stream)
     if rc != 0:
         raise RuntimeError(f"bench_mfma_rate failed ({rc})")
     return flops.value
@@ -374,6 +377,14 @@ def matrix_pipe_context(torch, nv, reps: int = 3, iters: int = 100000):
         b.record()
         torch.cuda.synchronize()
         res[f"register_only_mfma_{name}_TFLOPs"] = flops / (a.elapsed_time(b) * 1e-3) / 1e12
+    # the GEMM kernel's register block: 8 x 8 accumulators, one wavefront per SIMD (64 MFMAs per trip: a eighth of the trips)
+    mfma_rate(torch, 2, iters // 80, buf, gemm_block=True)
+    a, b = ev(), ev()
+    a.record()
+    flops = sum(mfma_rate(torch, 2, iters // 8, buf, gemm_block=True) for _ in range(reps))
+    b.record()
+    torch.cuda.synchronize()
+    res["register_only_mfma_nvfp4_like_values_gemm_register_block_TFLOPs"] = flops / (a.elapsed_time(b) * 1e-3) / 1e12
     g = torch.Generator(device="cuda").manual_seed(5)
     xa = torch.randn((TOKENS, D_MODEL), generator=g, device="cuda", dtype=torch.float16)
     wb = torch.randn((D_MODEL, D_FFN), generator=g, device="cuda", dtype=torch.float16)
@@ -389,7 +400,9 @@ def matrix_pipe_context(torch, nv, reps: int = 3, iters: int = 100000):
     res["vendor_fp16_gemm_fprop_shape_TFLOPs"] = 10 * 2.0 * TOKENS * D_MODEL * D_FFN / (a.elapsed_time(b) * 1e-3) / 1e12
     res["note"] = ("not part of `value`: v_mfma_f32_16x16x32_f16 in a register-only loop (512 workgroups x 4 wavefronts, 16 "
                    "independent accumulators) per operand kind -- the chip is power-limited, the rate depends on the "
-                   "operand bits; and torch.matmul FP16 [8192,5120]x[5120,20480] on N(0,1) data")
+                   "operand bits; the same with the GEMM kernel's register block (256 workgroups x 4 wavefronts, 8 x 8 "
+                   "accumulators: an operand register serves 8 instructions in a row); and torch.matmul FP16 "
+                   "[8192,5120]x[5120,20480] on N(0,1) data")
     return res
 
 
@@ -627,6 +640,8 @@ def main() -> int:
         out["matrix_pipe_context"] = matrix_pipe_context(torch, nv)
         ctx = out["matrix_pipe_context"]
         out["roofline"]["frac_of_register_only_rate_nvfp4_like_values"] = gemm_tflops / ctx["register_only_mfma_nvfp4_like_values_TFLOPs"]
+        out["roofline"]["frac_of_register_only_rate_gemm_register_block"] = (
+            gemm_tflops / ctx["register_only_mfma_nvfp4_like_values_gemm_register_block_TFLOPs"])
     if not args.no_cpu_baseline:
         del bufs[1:], sets[1:]
         out["cpu_baseline"] = cpu_baseline(torch, nv, x, w, dy, gemm_ws)

@@ -5,6 +5,10 @@
 //                       wavefront, so timing it gives the rate the matrix pipe sustains on this board under its
 //                       power limit for operand values of a given kind.  bench.py quotes it beside the published
 //                       peak ("matrix_pipe_context").
+//   bench_mfma_rate_gemm_block  the same with the GEMM kernel's own register block: one workgroup of 4 wavefronts
+//                       per CU (one per SIMD), 8 x 8 accumulators from 8 + 8 operand registers, so that an operand
+//                       register serves 8 instructions in a row as it does there (which costs less power: this loop
+//                       runs about a fifth faster than the 4 x 4 one on the same values).
 //   bench_stream_copy   a plain device copy of known size (16 bytes per lane and trip, grid-stride): under
 //                       rocprofv3 --pmc its FETCH_SIZE / WRITE_SIZE readings calibrate the counters against known
 //                       HBM traffic, and its time is the box's plain streaming bandwidth.
@@ -66,6 +70,35 @@ __global__ __launch_bounds__(256) void mfma_rate_kernel(int kind, long long iter
   out[tid] = t[0] + t[1] + t[2] + t[3];
 }
 
+__global__ __launch_bounds__(256) void mfma_rate_gemm_block_kernel(int kind, long long iters, float* __restrict__ out) {
+  const uint32_t tid = blockIdx.x * 256 + threadIdx.x;
+  probe_half8 a[8], b[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      a[i][e] = probe_value(kind, probe_hash(tid * 128 + i * 8 + e));
+      b[i][e] = probe_value(kind, probe_hash(tid * 128 + 64 + i * 8 + e));
+    }
+  probe_float4 acc[8][8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[i][j] = probe_float4{0.0f, 0.0f, 0.0f, 0.0f};
+  for (long long it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+      for (int j = 0; j < 8; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[i], b[j], acc[i][j], 0, 0, 0);
+  }
+  probe_float4 t = probe_float4{0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int j = 0; j < 8; ++j) t += acc[i][j];
+  out[tid] = t[0] + t[1] + t[2] + t[3];
+}
+
 __global__ __launch_bounds__(256) void stream_copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n16) {
   const size_t stride = static_cast<size_t>(gridDim.x) * 256;
   for (size_t i = static_cast<size_t>(blockIdx.x) * 256 + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
@@ -85,6 +118,17 @@ int bench_mfma_rate(int operand_kind, int64_t iters, float* out, double* flops, 
   hipLaunchKernelGGL(mfma_rate_kernel, dim3(kProbeWorkgroups), dim3(256), 0, static_cast<hipStream_t>(stream), operand_kind,
                      static_cast<long long>(iters), out);
   *flops = static_cast<double>(kProbeWorkgroups) * 4.0 * static_cast<double>(iters) * 16.0 * (2.0 * 16 * 16 * 32);
+  return hipGetLastError() == hipSuccess ? 0 : -5;
+}
+
+// The same with 256 workgroups and 64 MFMAs per trip (8 x 8 accumulators); iters 1 .. 2^22; out as above (the first
+// half of it is written).
+int bench_mfma_rate_gemm_block(int operand_kind, int64_t iters, float* out, double* flops, void* stream) {
+  if (!out || !flops || reinterpret_cast<uintptr_t>(out) % 4) return -1;
+  if (operand_kind < 0 || operand_kind > 2 || iters <= 0 || iters > (int64_t{1} << 22)) return -1;
+  hipLaunchKernelGGL(mfma_rate_gemm_block_kernel, dim3(kProbeWorkgroups / 2), dim3(256), 0, static_cast<hipStream_t>(stream),
+                     operand_kind, static_cast<long long>(iters), out);
+  *flops = static_cast<double>(kProbeWorkgroups / 2) * 4.0 * static_cast<double>(iters) * 64.0 * (2.0 * 16 * 16 * 32);
   return hipGetLastError() == hipSuccess ? 0 : -5;
 }
 

@@ -250,10 +250,12 @@ __global__ __launch_bounds__(kThreads) void gemm_f16_kernel(const _Float16* __re
 
   // Direct-load sources: instruction q of wavefront w fills rows w * 64 + 16 q .. + 15 of a tile, which the decoded
   // operand holds as 1 KiB of consecutive bytes per stage, in LDS order (lane l: bytes 16 l .. 16 l + 15).  An address
-  // is a wave-uniform 64-bit base per operand tile plus a per-lane 32-bit offset per instruction (256 rows of K * 2
-  // bytes: K < 2^21, checked on the host), which holds the 16-row block and the stage being fetched.  A block past
-  // the end of an operand is replaced by the operand's last block (rows come in multiples of 16); it only feeds
-  // outputs that are never stored.
+  // is a wave-uniform 64-bit base per operand, which holds the tile and the stage being fetched, plus a per-lane
+  // 32-bit offset per instruction (256 rows of K * 2 bytes: K < 2^21, checked on the host), which holds the 16-row
+  // block and does not change within a tile: moving on by a stage is two scalar additions per operand.  (Every
+  // vector instruction between two MFMAs costs: with the stage added to the 8 per-lane offsets instead, the three
+  // 12B GEMM calls took 2 % longer.)  A block past the end of an operand is replaced by the operand's last block
+  // (rows come in multiples of 16); it only feeds outputs that are never stored.
   // One instruction per load inside the loop (a single wavefront per SIMD issues in order: what it spends on anything
   // else, the matrix pipe waits): M0, the LDS destination, is written once per four loads; loads q % 4 = 1, 2, 3 reach
   // the next KiB through the instruction's immediate offset, which moves the LDS and the global address alike, so
@@ -277,14 +279,14 @@ __global__ __launch_bounds__(kThreads) void gemm_f16_kernel(const _Float16* __re
   // Point the loads at stage st (32 k) of tile (tm, tn).
   auto aim = [&](int tm, int tn, int st) {
     const int64_t m_first = static_cast<int64_t>(tm) * TM, n_first = static_cast<int64_t>(tn) * TN;
-    base_a = reinterpret_cast<const char*>(A) + m_first * K * 2 - 3 * 1024;
-    base_b = reinterpret_cast<const char*>(B) + n_first * K * 2 - 3 * 1024;
+    base_a = reinterpret_cast<const char*>(A) + m_first * K * 2 + (st - 3) * kPieceBytes;
+    base_b = reinterpret_cast<const char*>(B) + n_first * K * 2 + (st - 3) * kPieceBytes;
     // 16-row blocks counted from the tile's first; a block's stages are K / 32 KiB
     const uint32_t last_a = static_cast<uint32_t>(M - 16 - m_first) >> 4, last_b = static_cast<uint32_t>(N - 16 - n_first) >> 4;
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
       const uint32_t blk = static_cast<uint32_t>(wave * 4 + q);
-      const uint32_t fixed = static_cast<uint32_t>(3 - q) * 1024u + static_cast<uint32_t>(st) * kPieceBytes;
+      const uint32_t fixed = static_cast<uint32_t>(3 - q) * 1024u;
       voff[q] = lane_bytes + min(blk, last_a) * static_cast<uint32_t>(K * 32) + fixed;
       voff[4 + q] = lane_bytes + min(blk, last_b) * static_cast<uint32_t>(K * 32) + fixed;
     }
@@ -314,8 +316,8 @@ __global__ __launch_bounds__(kThreads) void gemm_f16_kernel(const _Float16* __re
   for (uint32_t buf = 1; buf < kStages; ++buf) {
     if (fetch_st + 1 < 2 * kt_end) {   // (an item of two stages fetches its last three times)
       ++fetch_st;
-#pragma unroll
-      for (int q = 0; q < 8; ++q) voff[q] += kPieceBytes;
+      base_a += kPieceBytes;
+      base_b += kPieceBytes;
     }
     static_for<0, 8>([&](auto q) { issue(q, buf); });
   }
@@ -366,10 +368,9 @@ __global__ __launch_bounds__(kThreads) void gemm_f16_kernel(const _Float16* __re
         if constexpr (kFirst) mfma_first(acc[n >> 3][n & 7], fc.b[n & 7], fc.a[n >> 3]);
         else mfma(acc[n >> 3][n & 7], fc.b[n & 7], fc.a[n >> 3]);
         if constexpr ((n & 3) == 1) read_frag<(n >> 2)>(fn, a_frag + nxt, b_frag + nxt);
-        if constexpr ((n & 7) == 3) {
-          voff[n >> 3] += advance;
-          issue(std::integral_constant<int, (n >> 3)>{}, buf);
-        }
+        if constexpr (n == 3) base_a += advance;
+        if constexpr (n == 35) base_b += advance;
+        if constexpr ((n & 7) == 3) issue(std::integral_constant<int, (n >> 3)>{}, buf);
       });
       // Memory operations complete in issue order.  Behind the loads of stage g + 2 this wavefront has issued those of
       // g + 3 and g + 4, 8 each, and, across a tile boundary, the stores of the tile before.

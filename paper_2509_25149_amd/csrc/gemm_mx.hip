@@ -353,9 +353,9 @@ __global__ __launch_bounds__(kThreads) void gemm_mx_kernel_k512(Operand A, Opera
     sel01 = kb | ((4 + kb) << 8);
   };
   lane_setup();
-  // Load addresses: a wave-uniform 64-bit base per operand tile (codes, scales) plus per-lane 32-bit offsets, which
-  // hold the row, the chunk and the stage / scale chunk being fetched (256 rows of K / 2 bytes: K < 2^24, checked on
-  // the host).  An 8-row block past the end of an operand is replaced by the operand's last block (rows come in
+  // Load addresses: a wave-uniform 64-bit base per operand (codes, scales), which holds the tile and the stage /
+  // scale chunk being fetched, plus per-lane 32-bit offsets, which hold the row and the chunk and do not change
+  // within a tile (256 rows of K / 2 bytes: K < 2^24, checked on the host): moving the loads on is scalar work.  An 8-row block past the end of an operand is replaced by the operand's last block (rows come in
   // multiples of 32); it only feeds outputs that are never stored.  Scale rows are clamped per lane.
   const uint8_t* base_a = nullptr;
   const uint8_t* base_b = nullptr;
@@ -366,20 +366,19 @@ __global__ __launch_bounds__(kThreads) void gemm_mx_kernel_k512(Operand A, Opera
   // Point the loads at stage `stage` and scale chunk `chunk` of tile (tm, tn).
   auto aim = [&](int tm, int tn, int stage, int chunk) {
     const int64_t m_first = static_cast<int64_t>(tm) * TM, n_first = static_cast<int64_t>(tn) * TN;
-    base_a = A.codes + m_first * code_ld;
-    base_b = B.codes + n_first * code_ld;
-    base_sa = A.scales + m_first * scale_ld;
-    base_sb = B.scales + n_first * scale_ld;
+    base_a = A.codes + m_first * code_ld + stage * kWideRowBytes;
+    base_b = B.codes + n_first * code_ld + stage * kWideRowBytes;
+    base_sa = A.scales + m_first * scale_ld + chunk * 16;
+    base_sb = B.scales + n_first * scale_ld + chunk * 16;
     const uint32_t last_a = static_cast<uint32_t>(A.outer - 8 - m_first), last_b = static_cast<uint32_t>(B.outer - 8 - n_first);
 #pragma unroll
     for (int q = 0; q < 8; ++q) {
       const uint32_t r = static_cast<uint32_t>(wave * 64 + q * 8);
-      const uint32_t fixed = static_cast<uint32_t>(stage) * kWideRowBytes;
-      voff[q] = ((q & 1) ? lane_odd : lane_even) + min(r, last_a) * static_cast<uint32_t>(code_ld) + fixed;
-      voff[8 + q] = ((q & 1) ? lane_odd : lane_even) + min(r, last_b) * static_cast<uint32_t>(code_ld) + fixed;
+      voff[q] = ((q & 1) ? lane_odd : lane_even) + min(r, last_a) * static_cast<uint32_t>(code_ld);
+      voff[8 + q] = ((q & 1) ? lane_odd : lane_even) + min(r, last_b) * static_cast<uint32_t>(code_ld);
     }
-    vsa = min(lane_srow, last_a + 7) * static_cast<uint32_t>(scale_ld) + static_cast<uint32_t>(chunk) * 16u;
-    vsb = min(lane_srow, last_b + 7) * static_cast<uint32_t>(scale_ld) + static_cast<uint32_t>(chunk) * 16u;
+    vsa = min(lane_srow, last_a + 7) * static_cast<uint32_t>(scale_ld);
+    vsb = min(lane_srow, last_b + 7) * static_cast<uint32_t>(scale_ld);
   };
   // load number q (0..15) of a stage into stage buffer `buf`: 0..7 A, 8..15 B
   auto issue_codes = [&](auto qc, int buf) {
@@ -400,8 +399,8 @@ __global__ __launch_bounds__(kThreads) void gemm_mx_kernel_k512(Operand A, Opera
   locate(item, tm, tn);
   aim(tm, tn, 0, 0);
   static_for<0, 16>([&](auto q) { issue_codes(q, 0); });
-#pragma unroll
-  for (int q = 0; q < 16; ++q) voff[q] += kWideRowBytes;
+  base_a += kWideRowBytes;
+  base_b += kWideRowBytes;
   static_for<0, 16>([&](auto q) { issue_codes(q, 1); });
   issue_scales(0);
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -438,8 +437,8 @@ __global__ __launch_bounds__(kThreads) void gemm_mx_kernel_k512(Operand A, Opera
       // to follow, nowhere (the last stage and chunk are fetched again into buffers nobody reads any more).
       uint32_t code_advance = kWideRowBytes;
       if ((st & 1) == 0 && (st >> 1) + 1 < chunks) {
-        vsa += 16u;
-        vsb += 16u;
+        base_sa += 16;
+        base_sb += 16;
       }
       if (st + 2 == stages) {
         code_advance = 0;
@@ -455,7 +454,10 @@ __global__ __launch_bounds__(kThreads) void gemm_mx_kernel_k512(Operand A, Opera
           mfma<(n & 3), ((n >> 3) & 3)>(acc[n >> 3][n & 7], f0.b[n & 7], f0.a[n >> 3], f0.pb[(n & 7) >> 2], f0.pa[n >> 5]);
         if constexpr ((n & 1) == 1 && (n >> 1) < kFragReads)
           read_frag_wide<(n >> 1)>(f1, raw, a_hi + cur, b_hi + cur, a_scales + sc1, b_scales + sc1);
-        if constexpr ((n & 3) == 2) voff[n >> 2] += code_advance;
+        if constexpr (n == 2) {
+          base_a += code_advance;
+          base_b += code_advance;
+        }
       });
       if (kFirst && stores_behind) asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(kTileStoresMx<kBf16Out>) : "memory");
       else asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
