@@ -251,7 +251,7 @@ int nvfp4_gemm(const nvfp4_qtensor* a, const nvfp4_qtensor* b, int op, void* d, 
  *               hold the operands still to decode and the partial tiles)
  *   fp16_out    device, 16-byte aligned, outer * K * 2 bytes (outer x K = rows x cols for the row copy, cols x rows for
  *               the col copy; K must be a multiple of 64, NVFP4_ERR_BAD_SHAPE otherwise).  The elements are stored in
- *               the order the GEMM kernel loads them (8 rows x 64 k per KiB), not row by row: the buffer is for
+ *               the order the GEMM kernel loads them (16 rows x 32 k per KiB), not row by row: the buffer is for
  *               nvfp4_gemm only.  Owned by the caller, must stay valid while the descriptor points to it
  *   fp16_bytes  its size; NVFP4_ERR_WORKSPACE if too small
  * nvfp4_quantize into the same descriptor clears both fields (the codes change), as does any call that rewrites it.

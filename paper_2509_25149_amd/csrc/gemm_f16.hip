@@ -211,12 +211,12 @@ constexpr int kTileStores = kBf16Out ? 24 : 48;
 // Tiles [tile_begin, tile_begin + tile_count) of the 256x256 tiling are covered.
 //
 // k_splits == 1: a workgroup takes tiles blockIdx.x, blockIdx.x + gridDim.x, ... of the launch (the host launches one
-// workgroup per CU when there are more tiles than CUs) and runs them as ONE stream of K steps: the loads issued during a
-// tile's last two steps already fetch the next tile's first two, so that the pipeline neither drains nor refills at
+// workgroup per CU when there are more tiles than CUs) and runs them as ONE stream of stages: the loads issued during a
+// tile's last four stages already fetch the next tile's first four, so that the pipeline neither drains nor refills at
 // a tile boundary -- what remains there is reading the 256 sums out, scaling, converting and issuing the stores,
 // which then drain under the next tile's MFMAs (measured with timestamps in the one-tile-per-workgroup form: 4.2 us
 // of pipeline fill, 5.5 us of output stage, most of it waiting for the stores of all CUs at once, and 0.6 us between
-// workgroups, per 118 us of main loop at K = 5120).  Needs K >= 2 steps; the host launches one workgroup per tile
+// workgroups, per 118 us of main loop at K = 5120).  Needs K >= 4 stages (2 K steps of 64); the host launches one workgroup per tile
 // otherwise.
 //
 // k_splits > 1 (one work item per workgroup) fills the chip during a last, partial round of tiles: a tile is shared by
